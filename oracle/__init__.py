@@ -1,0 +1,20 @@
+"""CPU oracle for the PulseCol attention hot path.
+
+TEST INFRASTRUCTURE ONLY.  This package is the slow, plain definition of what
+the GPU library must compute.  It shares no code with the HIP path and must
+never be imported by the product package; only the test-suite, the smoke
+check and the benchmark's ``cpu_baseline`` leg may use it.
+"""
+
+from .pulsecol_oracle import (  # noqa: F401
+    attention_logits,
+    column_scores,
+    dense_attention,
+    num_keep,
+    refresh_schedule,
+    row_softmax,
+    select_columns,
+    sparse_attention_masked,
+    sparse_attention_tiled,
+    topk_columns,
+)

@@ -1,0 +1,246 @@
+"""Plain fp64 definitions of the PulseCol attention hot path (numpy, CPU).
+
+TEST INFRASTRUCTURE ONLY -- never imported by the product package.
+
+Every function works on ONE attention head: ``Q, K, V`` are ``[n, d]`` float64
+arrays (bf16 / fp32 inputs widened exactly by the caller, so input rounding is
+not counted as error).  Column sets are ``idx[U, k]`` integer arrays, one row per
+query group; ``group_size == 0`` means a single group that holds every query
+(U = 1).  Nothing here is blocked, fused or reordered beyond what the cited
+passage states; the only concession to memory is that independent query rows
+may be processed a slab at a time (``row_chunk``), which changes no value.
+
+Pins (tests/test_oracle_pins.py): closed-form softmax examples, the textbook
+dense attention of an independent library, row-stochastic invariants, brute
+force over all column subsets (Eq. 7), Eq. 2 against Alg. 1, hand-worked
+refresh schedules (Eq. 8).  The paper prints no numeric example of its own, so
+agreement with the authors' kernels is "parity unpinned"; agreement with the
+definitions is what the pins establish.
+"""
+
+from __future__ import annotations
+
+import math
+from fractions import Fraction
+
+import numpy as np
+
+_F64 = np.float64
+
+
+def _as_f64(x) -> np.ndarray:
+    a = np.asarray(x, dtype=_F64)
+    if a.ndim != 2:
+        raise ValueError("expected an [n, d] array for one head")
+    return a
+
+
+def _floor_of_product(ratio: float, count: int) -> int:
+    """floor(ratio * count) with the ratio read as the decimal the caller wrote."""
+    return math.floor(Fraction(repr(float(ratio))) * int(count))
+
+
+# --------------------------------------------------------------------------
+# Eq. 3: sparsity budget -> number of kept columns per query row
+# --------------------------------------------------------------------------
+def num_keep(n: int, keep_ratio: float) -> int:
+    """k = max(1, floor(keep_ratio * n)), keep_ratio = 1 - rho.
+
+    Sec. 3.1, sparsity-budget constraint: at most (1 - rho) n^2 retained pairs
+    per head, i.e. at most (1 - rho) n per query row; floor honours the "<=".
+    """
+    if n < 1 or not (0.0 < keep_ratio <= 1.0):
+        raise ValueError("need n >= 1 and 0 < keep_ratio <= 1")
+    return max(1, _floor_of_product(keep_ratio, n))
+
+
+# --------------------------------------------------------------------------
+# Eq. 1 and the dense attention that follows it
+# --------------------------------------------------------------------------
+def attention_logits(Q, K, scale: float | None = None) -> np.ndarray:
+    """Z = Q K^T / sqrt(d_h)   (Sec. 3.1, logits equation).  Z[i, j] = q_i . k_j * scale."""
+    Q = _as_f64(Q)
+    K = _as_f64(K)
+    if scale is None:
+        scale = 1.0 / math.sqrt(Q.shape[1])
+    return (Q @ K.T) * scale
+
+
+def row_softmax(Z: np.ndarray) -> np.ndarray:
+    """softmax over the key axis of each query row; -inf entries get weight 0."""
+    m = np.max(Z, axis=1, keepdims=True)
+    E = np.exp(Z - m)
+    return E / np.sum(E, axis=1, keepdims=True)
+
+
+def dense_attention(Q, K, V, scale: float | None = None, rows=None) -> np.ndarray:
+    """A = softmax(Z) V   (Sec. 3.1, full bidirectional attention, no mask).
+
+    ``rows`` (optional) restricts the result to those query rows.
+    """
+    Q = _as_f64(Q)
+    V = _as_f64(V)
+    if rows is not None:
+        Q = Q[np.asarray(rows)]
+    return row_softmax(attention_logits(Q, K, scale)) @ V
+
+
+# --------------------------------------------------------------------------
+# Eq. 5: group column scores
+# --------------------------------------------------------------------------
+def _groups(n: int, group_size: int):
+    """Contiguous query groups G_1..G_U; group_size 0 -> one group of all rows."""
+    if group_size < 0:
+        raise ValueError("group_size must be >= 0")
+    g = n if group_size == 0 else group_size
+    return [(lo, min(n, lo + g)) for lo in range(0, n, g)]
+
+
+def column_scores(Q, K, group_size: int = 0, scale: float | None = None,
+                  row_chunk: int = 2048) -> np.ndarray:
+    """s[u, j] = (1/|G_u|) sum_{i in G_u} P[i, j],  P = row softmax of the FULL logits.
+
+    Sec. 3.3, group-wise column-sparse pattern estimation (score equation).
+    Returns float64 ``[U, n]``.
+    """
+    Q = _as_f64(Q)
+    K = _as_f64(K)
+    n = Q.shape[0]
+    groups = _groups(n, group_size)
+    s = np.zeros((len(groups), K.shape[0]), dtype=_F64)
+    for u, (lo, hi) in enumerate(groups):
+        for r0 in range(lo, hi, row_chunk):
+            r1 = min(hi, r0 + row_chunk)
+            P = row_softmax(attention_logits(Q[r0:r1], K, scale))
+            s[u] += P.sum(axis=0)
+        s[u] /= (hi - lo)
+    return s
+
+
+# --------------------------------------------------------------------------
+# Eq. 6 / Eq. 7: top-k columns per group
+# --------------------------------------------------------------------------
+def topk_columns(s, k: int) -> np.ndarray:
+    """C_u = TopK(s_u, k) for every row of ``s``; returns int64 ``[U, k]`` ascending.
+
+    Sec. 3.3, TopK equation.  Equal scores: the lower column index wins (any
+    maximiser of the Eq. 7 objective is correct; this fixes one).  The set is
+    emitted in ascending column order; the order carries no meaning.
+    """
+    s = np.atleast_2d(np.asarray(s, dtype=_F64))
+    U, n = s.shape
+    if not (1 <= k <= n):
+        raise ValueError("need 1 <= k <= n")
+    out = np.empty((U, k), dtype=np.int64)
+    for u in range(U):
+        order = np.argsort(-s[u], kind="stable")  # score descending, index ascending on ties
+        out[u] = np.sort(order[:k])
+    return out
+
+
+def select_columns(Q, K, keep_ratio: float, group_size: int = 0,
+                   scale: float | None = None) -> np.ndarray:
+    """The whole identification pass: Eq. 3 -> Eq. 5 -> Eq. 6."""
+    k = num_keep(np.asarray(Q).shape[0], keep_ratio)
+    return topk_columns(column_scores(Q, K, group_size, scale), k)
+
+
+# --------------------------------------------------------------------------
+# Eq. 2: masked sparse attention (the definition of the sparse result)
+# --------------------------------------------------------------------------
+def sparse_attention_masked(Q, K, V, idx, group_size: int = 0,
+                            scale: float | None = None, rows=None) -> np.ndarray:
+    """A~ = softmax(Z + M(S)) V with S[i, j] = 1 iff j in idx[u(i)], M = 0 / -inf.
+
+    Sec. 3.1, masked sparse-attention equation, with the group-shared mask of
+    Sec. 3.3.  ``rows`` (optional) restricts the result to those query rows.
+    Column indices must be unique within a row of ``idx`` (a 0/1 mask cannot
+    express multiplicity).
+    """
+    Q = _as_f64(Q)
+    K = _as_f64(K)
+    V = _as_f64(V)
+    idx = np.atleast_2d(np.asarray(idx, dtype=np.int64))
+    n = Q.shape[0]
+    nk = K.shape[0]
+    groups = _groups(n, group_size)
+    if idx.shape[0] != len(groups):
+        raise ValueError("idx needs one row per query group")
+    row_ids = np.arange(n) if rows is None else np.asarray(rows, dtype=np.int64)
+    g = n if group_size == 0 else group_size
+    O = np.empty((row_ids.size, V.shape[1]), dtype=_F64)
+    for u in np.unique(row_ids // g):
+        sel = np.nonzero(row_ids // g == u)[0]
+        M = np.full(nk, -np.inf)
+        M[idx[u]] = 0.0
+        Z = attention_logits(Q[row_ids[sel]], K, scale) + M[None, :]
+        O[sel] = row_softmax(Z) @ V
+    return O
+
+
+# --------------------------------------------------------------------------
+# Alg. 1: column-sparse attention forward, tile by tile with online softmax
+# --------------------------------------------------------------------------
+def sparse_attention_tiled(Q, K, V, idx, block_m: int, block_n: int,
+                           group_size: int = 0, scale: float | None = None) -> np.ndarray:
+    """Appendix B pseudocode, in its own order and notation.
+
+    Query blocks of ``block_m`` rows; each walks its index list in tiles of
+    ``block_n`` positions, gathers K_I, V_I, forms R = Q_i K_I^T (scaled), the
+    tile statistics (m~, P~, l~) and merges them into (m_i, l_i, acc_i); the
+    output is diag(l_i)^-1 acc_i.  A query block must lie inside one group.
+    Duplicate indices are counted with multiplicity, as the listing would.
+    """
+    Q = _as_f64(Q)
+    K = _as_f64(K)
+    V = _as_f64(V)
+    idx = np.atleast_2d(np.asarray(idx, dtype=np.int64))
+    n, d = Q.shape
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    g = n if group_size == 0 else group_size
+    if group_size and (group_size % block_m):
+        raise ValueError("block_m must divide group_size")
+    n_s = idx.shape[1]
+    T_q = -(-n // block_m)
+    T_s = -(-n_s // block_n)
+    O = np.empty((n, V.shape[1]), dtype=_F64)
+    for i in range(T_q):
+        r0, r1 = i * block_m, min(n, (i + 1) * block_m)
+        Q_i = Q[r0:r1]
+        m_i = np.full(r1 - r0, -np.inf)
+        l_i = np.zeros(r1 - r0)
+        acc_i = np.zeros((r1 - r0, V.shape[1]))
+        I_i = idx[r0 // g]
+        for t in range(T_s):
+            I_it = I_i[t * block_n:(t + 1) * block_n]
+            K_I, V_I = K[I_it], V[I_it]
+            R = (Q_i @ K_I.T) * scale
+            m_t = R.max(axis=1)
+            P_t = np.exp(R - m_t[:, None])
+            l_t = P_t.sum(axis=1)
+            m_new = np.maximum(m_i, m_t)
+            a_old = np.exp(m_i - m_new)
+            a_new = np.exp(m_t - m_new)
+            l_i = a_old * l_i + a_new * l_t
+            acc_i = a_old[:, None] * acc_i + a_new[:, None] * (P_t @ V_I)
+            m_i = m_new
+        O[r0:r1] = acc_i / l_i[:, None]
+    return O
+
+
+# --------------------------------------------------------------------------
+# Eq. 8: refresh schedule
+# --------------------------------------------------------------------------
+def refresh_schedule(T: int, eta: float, R: int) -> list[int]:
+    """1-based refresh steps tau_1..tau_R   (Sec. 3.3, schedule equation).
+
+    T_win = floor(eta T) (at least 1 so that tau_1 = 1 exists);
+    R = 1 -> {1}; else tau_r = 1 + floor((r-1)(T_win-1)/(R-1)).
+    """
+    if T < 1 or R < 1 or not (0.0 < eta <= 1.0):
+        raise ValueError("need T >= 1, R >= 1, 0 < eta <= 1")
+    T_win = max(1, _floor_of_product(eta, T))
+    if R == 1:
+        return [1]
+    return [1 + ((r - 1) * (T_win - 1)) // (R - 1) for r in range(1, R + 1)]

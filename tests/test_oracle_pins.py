@@ -1,0 +1,371 @@
+"""Pins for the CPU oracle: everything here is fixed by the paper's definitions or by
+mathematics, never by the oracle's own output.
+
+Each pin is a function of an oracle namespace ``o`` so that the mutation tests at
+the bottom can run the same pins against deliberately broken copies of the oracle
+(on the CPU) and confirm that every planted mistake is caught.
+"""
+
+import itertools
+import json
+import math
+import os
+import types
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as _oracle
+from oracle import pulsecol_oracle as _impl
+from paper_2605_20813_amd import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _frac(x):
+    return float(Fraction(x)) if isinstance(x, str) else float(x)
+
+
+def _table(rows):
+    return np.array([[_frac(v) for v in r] for r in rows], dtype=np.float64)
+
+
+def _closed_form():
+    with open(os.path.join(GOLDEN, "closed_form_3x4.json")) as f:
+        g = json.load(f)
+
+    def coeff(c):
+        if isinstance(c, list):  # ["ln", a, m] -> m * ln(a)
+            return c[2] * math.log(c[1])
+        return float(c)
+
+    Q = np.array([[coeff(c) for c in r] for r in g["Q_log_coeff"]])
+    return g, Q, _table(g["K"]), _table(g["V"])
+
+
+def _rand(n, d, seed, nk=None):
+    r = np.random.default_rng(seed)
+    return r.standard_normal((n, d)), r.standard_normal((nk or n, d)), r.standard_normal((nk or n, d))
+
+
+# ----------------------------------------------------------------------------
+# pins (each takes the oracle namespace)
+# ----------------------------------------------------------------------------
+def pin_closed_form(o):
+    g, Q, K, V = _closed_form()
+    np.testing.assert_allclose(np.exp(o.attention_logits(Q, K)), [[3, 1, 1], [1, 7, 1], [2, 1, 1]], rtol=1e-13)
+    np.testing.assert_allclose(o.row_softmax(o.attention_logits(Q, K)), _table(g["P"]), rtol=1e-13)
+    np.testing.assert_allclose(o.dense_attention(Q, K, V), _table(g["dense"]), rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(o.column_scores(Q, K), _table(g["scores_one_group"]), rtol=1e-13)
+    np.testing.assert_allclose(o.column_scores(Q, K, group_size=2), _table(g["scores_group_size_2"]), rtol=1e-13)
+    np.testing.assert_allclose(o.column_scores(Q, K, group_size=1), _table(g["P"]), rtol=1e-13)
+    assert o.topk_columns(o.column_scores(Q, K), 2).tolist() == g["top2_one_group"]
+    assert o.topk_columns(o.column_scores(Q, K, group_size=2), 1).tolist() == g["top1_group_size_2"]
+    for idx, key in (([[0, 1]], "sparse_idx_0_1"), ([[0, 2]], "sparse_idx_0_2")):
+        want = _table(g[key])
+        np.testing.assert_allclose(o.sparse_attention_masked(Q, K, V, idx), want, rtol=1e-13, atol=1e-15)
+        for bm, bn in ((1, 1), (2, 1), (3, 2), (2, 5)):
+            np.testing.assert_allclose(o.sparse_attention_tiled(Q, K, V, idx, bm, bn), want, rtol=1e-13, atol=1e-15)
+
+
+def pin_dense_matches_library(o):
+    # independent routine: torch's fused scaled-dot-product attention in fp64
+    Q, K, V = _rand(37, 16, 1)
+    want = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(Q)[None], torch.from_numpy(K)[None], torch.from_numpy(V)[None])[0].numpy()
+    np.testing.assert_allclose(o.dense_attention(Q, K, V), want, rtol=1e-11, atol=1e-13)
+    rows = [3, 0, 36]
+    np.testing.assert_allclose(o.dense_attention(Q, K, V, rows=rows), want[rows], rtol=1e-11, atol=1e-13)
+
+
+def pin_scores_invariants(o):
+    Q, K, _ = _rand(50, 8, 2)
+    for G in (0, 1, 7, 16, 50):
+        s = o.column_scores(Q, K, group_size=G)
+        U = 1 if G == 0 else -(-50 // G)
+        assert s.shape == (U, 50)
+        assert (s >= 0).all()
+        np.testing.assert_allclose(s.sum(axis=1), 1.0, rtol=1e-13)     # rows of P sum to one
+    # K == 0: every logit equal, P uniform, s_j = 1/n
+    np.testing.assert_allclose(o.column_scores(Q, np.zeros_like(K)), np.full((1, 50), 1 / 50), rtol=1e-13)
+    # one key aligned with every query and huge: takes all the mass
+    Qp = np.abs(Q) + 0.1
+    Kb = K.copy()
+    Kb[11] = 200.0
+    s = o.column_scores(Qp, Kb)
+    assert s[0, 11] > 1 - 1e-9
+    # slab size is a memory bound only
+    np.testing.assert_allclose(o.column_scores(Q, K, row_chunk=7), o.column_scores(Q, K, row_chunk=4096), rtol=1e-14)
+    # the mean over a group of the single-row scores is the group score
+    rows = o.column_scores(Q, K, group_size=1)
+    np.testing.assert_allclose(o.column_scores(Q, K, group_size=7)[2], rows[14:21].mean(axis=0), rtol=1e-13)
+
+
+def pin_topk_bruteforce(o):
+    # Eq. 7: the chosen set maximises the captured mass over ALL subsets of size k
+    for seed, n, k, G in ((3, 8, 3, 0), (4, 10, 4, 5), (5, 12, 5, 0), (6, 9, 1, 3), (7, 7, 7, 0)):
+        Q, K, _ = _rand(n, 4, seed)
+        s = o.column_scores(Q, K, group_size=G)
+        idx = o.topk_columns(s, k)
+        groups = [(0, n)] if G == 0 else [(lo, min(n, lo + G)) for lo in range(0, n, G)]
+        for u, (lo, hi) in enumerate(groups):
+            P = o.row_softmax(o.attention_logits(Q[lo:hi], K))
+            best = max(P[:, list(C)].sum() for C in itertools.combinations(range(n), k))
+            got = P[:, idx[u]].sum()
+            assert got == pytest.approx(best, rel=1e-13)
+            assert len(set(idx[u].tolist())) == k and list(idx[u]) == sorted(idx[u])
+
+
+def pin_topk_order_and_ties(o):
+    r = np.random.default_rng(8)
+    s = r.random((3, 200))
+    idx = o.topk_columns(s, 17)
+    for u in range(3):
+        want = sorted(sorted(range(200), key=lambda j: -s[u, j])[:17])
+        assert idx[u].tolist() == want
+    assert o.topk_columns(np.full((1, 9), 0.25), 4).tolist() == [[0, 1, 2, 3]]       # all equal -> lowest indices
+    t = np.array([[0.1, 0.5, 0.3, 0.5, 0.3, 0.3, 0.9]])
+    assert o.topk_columns(t, 1).tolist() == [[6]]
+    assert o.topk_columns(t, 2).tolist() == [[1, 6]]                                   # tie at 0.5: index 1 before 3
+    assert o.topk_columns(t, 4).tolist() == [[1, 2, 3, 6]]                             # tie at 0.3: index 2 first
+    assert o.topk_columns(t, 5).tolist() == [[1, 2, 3, 4, 6]]
+    assert o.topk_columns(t, 7).tolist() == [[0, 1, 2, 3, 4, 5, 6]]
+
+
+def pin_sparse_attention_properties(o):
+    n, d = 45, 8
+    Q, K, V = _rand(n, d, 9)
+    r = np.random.default_rng(10)
+    idx = np.sort(r.permutation(n)[:13])[None]
+    ref = o.sparse_attention_masked(Q, K, V, idx)
+    # Eq. 2 == Alg. 1 for any tiling, ragged tails included
+    for bm, bn in ((45, 13), (16, 4), (7, 5), (1, 1), (64, 64)):
+        np.testing.assert_allclose(o.sparse_attention_tiled(Q, K, V, idx, bm, bn), ref, rtol=1e-12, atol=1e-14)
+    # column order inside idx carries no meaning
+    perm = idx[:, r.permutation(13)]
+    np.testing.assert_allclose(o.sparse_attention_masked(Q, K, V, perm), ref, rtol=1e-13)
+    np.testing.assert_allclose(o.sparse_attention_tiled(Q, K, V, perm, 16, 4), ref, rtol=1e-12, atol=1e-14)
+    # keep everything -> dense attention
+    every = np.arange(n)[None]
+    np.testing.assert_allclose(o.sparse_attention_masked(Q, K, V, every), o.dense_attention(Q, K, V), rtol=1e-13)
+    np.testing.assert_allclose(o.sparse_attention_tiled(Q, K, V, every, 8, 8), o.dense_attention(Q, K, V), rtol=1e-12)
+    # weights of a row sum to one: V == 1 -> O == 1; rows are convex combinations of selected V rows
+    np.testing.assert_allclose(o.sparse_attention_masked(Q, K, np.ones_like(V), idx), 1.0, rtol=1e-13)
+    assert (ref <= V[idx[0]].max(axis=0) + 1e-12).all() and (ref >= V[idx[0]].min(axis=0) - 1e-12).all()
+    # one kept column: the output IS that value row
+    np.testing.assert_allclose(o.sparse_attention_masked(Q, K, V, [[29]]), np.tile(V[29], (n, 1)), rtol=1e-14)
+    np.testing.assert_allclose(o.sparse_attention_tiled(Q, K, V, [[29]], 8, 4), np.tile(V[29], (n, 1)), rtol=1e-14)
+    # unselected keys and values cannot matter
+    K2, V2 = K.copy(), V.copy()
+    off = np.setdiff1d(np.arange(n), idx[0])
+    K2[off] += 5.0
+    V2[off] -= 3.0
+    np.testing.assert_allclose(o.sparse_attention_masked(Q, K2, V2, idx), ref, rtol=1e-13)
+    # sampled rows == the same rows of the full result
+    rows = [44, 2, 17]
+    np.testing.assert_allclose(o.sparse_attention_masked(Q, K, V, idx, rows=rows), ref[rows], rtol=1e-14)
+    # groups: each group attends through its own row of idx
+    gidx = np.stack([np.sort(r.permutation(n)[:6]) for _ in range(3)])
+    got = o.sparse_attention_masked(Q, K, V, gidx, group_size=16)
+    for u, (lo, hi) in enumerate(((0, 16), (16, 32), (32, 45))):
+        want = o.sparse_attention_masked(Q[lo:hi], K, V, gidx[u:u + 1])
+        np.testing.assert_allclose(got[lo:hi], want, rtol=1e-13)
+    np.testing.assert_allclose(o.sparse_attention_tiled(Q, K, V, gidx, 8, 4, group_size=16), got, rtol=1e-12)
+    # Alg. 1 counts a repeated index twice: {a, a} still yields V[a]; {a, a, b} weighs a double
+    np.testing.assert_allclose(o.sparse_attention_tiled(Q, K, V, [[5, 5]], 8, 1), np.tile(V[5], (n, 1)), rtol=1e-13)
+    z = o.attention_logits(Q, K)
+    w = np.exp(z[:, [5, 5, 9]])
+    want = (w / w.sum(1, keepdims=True)) @ V[[5, 5, 9]]
+    np.testing.assert_allclose(o.sparse_attention_tiled(Q, K, V, [[5, 5, 9]], 8, 2), want, rtol=1e-12)
+
+
+def pin_scale_override(o):
+    Q, K, V = _rand(20, 16, 11)
+    np.testing.assert_allclose(o.attention_logits(Q, K), (Q @ K.T) / 4.0, rtol=1e-14)
+    np.testing.assert_allclose(o.attention_logits(Q, K, scale=0.3), (Q @ K.T) * 0.3, rtol=1e-14)
+    idx = np.arange(0, 20, 3)[None]
+    a = o.sparse_attention_masked(Q, K, V, idx, scale=0.3)
+    b = o.sparse_attention_masked(Q * 0.3 * 4.0, K, V, idx)
+    np.testing.assert_allclose(a, b, rtol=1e-12)
+
+
+def pin_num_keep(o):
+    assert [o.num_keep(n, r) for n, r in ((256, .25), (4096, .1), (16384, .1), (32768, .05), (32768, .1),
+                                           (32768, .2), (65536, .1))] == [64, 409, 1638, 1638, 3276, 6553, 6553]
+    assert o.num_keep(100, 0.29) == 29          # decimal reading, not the binary product 28.999...
+    assert o.num_keep(5, 0.1) == 1 and o.num_keep(7, 1.0) == 7
+    for bad in ((0, .5), (8, 0.0), (8, 1.5)):
+        with pytest.raises(ValueError):
+            o.num_keep(*bad)
+
+
+def pin_schedule(o):
+    with open(os.path.join(GOLDEN, "eq8_schedules.json")) as f:
+        cases = json.load(f)["cases"]
+    for c in cases:
+        assert o.refresh_schedule(c["T"], c["eta"], c["R"]) == c["tau"], c
+    for T, eta, R in ((100, .5, 7), (1000, .3, 16), (17, 1.0, 17), (50, .1, 3)):
+        tau = o.refresh_schedule(T, eta, R)
+        T_win = max(1, math.floor(Fraction(repr(eta)) * T))
+        assert len(tau) == R and tau[0] == 1 and tau[-1] == T_win
+        assert all(a <= b for a, b in zip(tau, tau[1:])) and max(tau) <= T_win
+
+
+def pin_planted_columns_selected(o):
+    w = wl.WORKLOADS["tiny"]
+    for h in range(w.heads):
+        q, k, _ = wl.make_head(w, 0, h)
+        idx = o.select_columns(q.double().numpy(), k.double().numpy(), w.keep_ratios[0])
+        heavy = set(wl.heavy_columns(w, 0, h).tolist())
+        assert idx.shape == (1, 64) and heavy <= set(idx[0].tolist())
+
+
+PINS = [pin_closed_form, pin_dense_matches_library, pin_scores_invariants, pin_topk_bruteforce,
+        pin_topk_order_and_ties, pin_sparse_attention_properties, pin_scale_override, pin_num_keep,
+        pin_schedule, pin_planted_columns_selected]
+
+
+@pytest.mark.parametrize("pin", PINS, ids=lambda p: p.__name__)
+def test_pin(pin):
+    pin(_oracle)
+
+
+# ----------------------------------------------------------------------------
+# mutation tests: a plausible mistake planted in a COPY of the oracle must trip a pin
+# ----------------------------------------------------------------------------
+def _mutant(**overrides):
+    """A fresh copy of the oracle module with some functions replaced (globals rebound)."""
+    src = open(_impl.__file__).read()
+    mod = types.ModuleType("oracle_mutant")
+    mod.__file__ = _impl.__file__
+    exec(compile(src, _impl.__file__, "exec"), mod.__dict__)
+    for name, fn in overrides.items():
+        mod.__dict__[name] = types.FunctionType(fn.__code__, mod.__dict__, name, fn.__defaults__)
+    return mod
+
+
+def _logits_transposed(Q, K, scale=None):
+    Q, K = _as_f64(Q), _as_f64(K)
+    if scale is None:
+        scale = 1.0 / math.sqrt(Q.shape[1])
+    return (K @ Q.T) * scale
+
+
+def _logits_no_sqrt(Q, K, scale=None):
+    Q, K = _as_f64(Q), _as_f64(K)
+    if scale is None:
+        scale = 1.0 / Q.shape[1]
+    return (Q @ K.T) * scale
+
+
+def _softmax_wrong_axis(Z):
+    m = np.max(Z, axis=0, keepdims=True)
+    E = np.exp(Z - m)
+    return E / np.sum(E, axis=0, keepdims=True)
+
+
+def _softmax_no_normalise(Z):
+    return np.exp(Z - np.max(Z, axis=1, keepdims=True))
+
+
+def _topk_smallest(s, k):
+    s = np.atleast_2d(np.asarray(s, dtype=np.float64))
+    return np.stack([np.sort(np.argsort(s[u], kind="stable")[:k]) for u in range(s.shape[0])])
+
+
+def _topk_high_index_ties(s, k):
+    s = np.atleast_2d(np.asarray(s, dtype=np.float64))
+    n = s.shape[1]
+    return np.stack([np.sort((n - 1 - np.argsort(-s[u, ::-1], kind="stable"))[:k]) for u in range(s.shape[0])])
+
+
+def _scores_sum_not_mean(Q, K, group_size=0, scale=None, row_chunk=2048):
+    Q, K = _as_f64(Q), _as_f64(K)
+    groups = _groups(Q.shape[0], group_size)
+    s = np.zeros((len(groups), K.shape[0]))
+    for u, (lo, hi) in enumerate(groups):
+        s[u] = row_softmax(attention_logits(Q[lo:hi], K, scale)).sum(axis=0)
+    return s
+
+
+def _scores_divide_by_nominal_group(Q, K, group_size=0, scale=None, row_chunk=2048):
+    Q, K = _as_f64(Q), _as_f64(K)
+    groups = _groups(Q.shape[0], group_size)
+    g = Q.shape[0] if group_size == 0 else group_size
+    s = np.zeros((len(groups), K.shape[0]))
+    for u, (lo, hi) in enumerate(groups):
+        s[u] = row_softmax(attention_logits(Q[lo:hi], K, scale)).sum(axis=0) / g
+    return s
+
+
+def _scores_from_logits(Q, K, group_size=0, scale=None, row_chunk=2048):
+    Q, K = _as_f64(Q), _as_f64(K)
+    groups = _groups(Q.shape[0], group_size)
+    s = np.zeros((len(groups), K.shape[0]))
+    for u, (lo, hi) in enumerate(groups):
+        s[u] = attention_logits(Q[lo:hi], K, scale).mean(axis=0)
+    return s
+
+
+def _schedule_zero_based(T, eta, R):
+    T_win = max(1, _floor_of_product(eta, T))
+    if R == 1:
+        return [0]
+    return [((r - 1) * (T_win - 1)) // (R - 1) for r in range(1, R + 1)]
+
+
+def _schedule_window_not_minus_one(T, eta, R):
+    T_win = max(1, _floor_of_product(eta, T))
+    if R == 1:
+        return [1]
+    return [1 + ((r - 1) * T_win) // (R - 1) for r in range(1, R + 1)]
+
+
+def _num_keep_ceil(n, keep_ratio):
+    if n < 1 or not (0.0 < keep_ratio <= 1.0):
+        raise ValueError
+    return max(1, math.ceil(keep_ratio * n))
+
+
+MUTANTS = {
+    "logits_transposed": dict(attention_logits=_logits_transposed),
+    "logits_scale_1_over_d": dict(attention_logits=_logits_no_sqrt),
+    "softmax_over_queries": dict(row_softmax=_softmax_wrong_axis),
+    "softmax_not_normalised": dict(row_softmax=_softmax_no_normalise),
+    "topk_takes_smallest": dict(topk_columns=_topk_smallest),
+    "topk_ties_to_high_index": dict(topk_columns=_topk_high_index_ties),
+    "scores_sum_not_mean": dict(column_scores=_scores_sum_not_mean),
+    "scores_nominal_group_size": dict(column_scores=_scores_divide_by_nominal_group),
+    "scores_from_raw_logits": dict(column_scores=_scores_from_logits),
+    "schedule_zero_based": dict(refresh_schedule=_schedule_zero_based),
+    "schedule_full_window": dict(refresh_schedule=_schedule_window_not_minus_one),
+    "num_keep_ceil": dict(num_keep=_num_keep_ceil),
+}
+
+
+@pytest.mark.parametrize("name", sorted(MUTANTS))
+def test_planted_mistake_is_caught(name):
+    mutant = _mutant(**MUTANTS[name])
+    tripped = []
+    for pin in PINS:
+        try:
+            pin(mutant)
+        except (AssertionError, ValueError, IndexError):
+            tripped.append(pin.__name__)
+    assert tripped, f"no pin notices the planted mistake '{name}'"
+
+
+def test_tiled_merge_mistakes_are_caught():
+    """Alg. 1's merge: dropping the old-accumulator rescale, or the new-tile factor, must show."""
+    src = open(_impl.__file__).read()
+    for needle, broken in (("a_old[:, None] * acc_i", "acc_i"),
+                           ("a_new[:, None] * (P_t @ V_I)", "(P_t @ V_I)"),
+                           ("a_old * l_i + a_new * l_t", "l_i + a_new * l_t"),
+                           ("acc_i / l_i[:, None]", "acc_i")):
+        assert needle in src
+        mod = types.ModuleType("oracle_mutant")
+        exec(compile(src.replace(needle, broken), "mutant", "exec"), mod.__dict__)
+        with pytest.raises(AssertionError):
+            pin_sparse_attention_properties(mod)
