@@ -1,0 +1,146 @@
+/*
+ * pulsecol.h -- C ABI of the MI355X (gfx950) PulseCol attention hot path.
+ *
+ * PulseCol = periodically refreshed column-sparse bidirectional self-attention for
+ * diffusion-LLM denoising steps.  The library holds the two kernels of the method and a
+ * dense baseline:
+ *   - pattern identification (Sec. 3.3 "Group-wise Column-Sparse Pattern Estimation"):
+ *     column scores from the softmax mass of the FULL attention matrix, then top-k;
+ *   - column-sparse attention (Sec. 3.4 and the appendix listing "Column-Sparse
+ *     Attention Forward"): softmax(Q K_S^T / sqrt(d)) V_S over the selected columns only;
+ *   - dense attention softmax(Q K^T / sqrt(d)) V (Sec. 3.1), the baseline being beaten.
+ *
+ * Conventions common to every call
+ *   - Q, K, V, O are DEVICE pointers to [batch, heads, seq, head_dim] tensors whose last
+ *     dimension is contiguous; the other three strides are given in ELEMENTS in
+ *     pulsecol_shape (0 = packed).  Base pointers must be 16-byte aligned and the strides
+ *     multiples of 8 (bf16) or 4 (fp32) elements.  Attention is non-causal; there is no
+ *     padding mask.
+ *   - Column sets are DEVICE int32 arrays idx[batch, heads, U, k]; U is the number of query
+ *     groups per head (U = 1 when group_size == 0: one column set per head).  Entries lie in
+ *     [0, seq) and are unique within a row; pulsecol_select emits them ascending.  The
+ *     sparse kernel counts a repeated entry twice, as the appendix listing would.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work on it: they never synchronise and never read device memory on the host.
+ *     The caller owns every buffer it passes; the context owns only the scratch it
+ *     allocated at creation (row log-sum-exp, column scores, top-k counters, the cached
+ *     pattern).  No call allocates or frees device memory except create/destroy.
+ *   - Every function returns a pulsecol_status; nothing aborts or throws.  On failure no
+ *     kernel has been launched.  pulsecol_last_error gives a text for the last failure on a
+ *     context.  Two calls on one context must not overlap in time (they share scratch).
+ *   - NaN / Inf in the inputs give unspecified values, never a fault.
+ */
+#ifndef PULSECOL_H
+#define PULSECOL_H
+
+#include <stdint.h>
+
+#if defined(__GNUC__)
+#define PULSECOL_API __attribute__((visibility("default")))
+#else
+#define PULSECOL_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pulsecol_ctx pulsecol_ctx;
+
+typedef enum {
+    PULSECOL_OK = 0,
+    PULSECOL_ERR_INVALID_ARG = 1, /* null pointer, size < 1, ratio outside (0,1], k outside [1,seq] */
+    PULSECOL_ERR_UNSUPPORTED = 2, /* head_dim, dtype or group_size the kernels do not cover       */
+    PULSECOL_ERR_ALIGNMENT = 3,   /* base pointer or stride not aligned as stated above           */
+    PULSECOL_ERR_NO_PATTERN = 4,  /* refresh == 0 with no cached pattern, or with a different k   */
+    PULSECOL_ERR_OOM = 5,         /* scratch allocation failed in pulsecol_create                 */
+    PULSECOL_ERR_HIP = 6          /* a HIP runtime call failed; see pulsecol_last_error           */
+} pulsecol_status;
+
+typedef enum { PULSECOL_BF16 = 0, PULSECOL_F32 = 1 } pulsecol_dtype;
+
+/* Problem shape (host struct, copied by pulsecol_create).
+ * Sec. 3.1: per step, layer and head, Q, K, V are n x d_h with n = prompt + generation length. */
+typedef struct {
+    int32_t batch;      /* >= 1 */
+    int32_t heads;      /* >= 1 (multi-head attention: K and V have as many heads as Q)          */
+    int32_t seq;        /* n >= 1                                                               */
+    int32_t head_dim;   /* d_h: 64 or 128                                                        */
+    int32_t dtype;      /* pulsecol_dtype: storage type of Q, K, V, O.  bf16: bf16 MFMA with fp32 */
+                        /* accumulation and fp32 softmax; f32: fp32 throughout.                  */
+    int32_t group_size; /* queries per group (Sec. 3.3); 0 = the whole head is one group (U = 1) */
+    int64_t stride_b;   /* element strides of batch, head and sequence; 0 = packed               */
+    int64_t stride_h;
+    int64_t stride_n;
+    float scale;        /* logit scale; 0 = 1/sqrt(head_dim) (Sec. 3.1, logits equation)         */
+} pulsecol_shape;
+
+/* Host-only check of a shape against the rules above.  Touches no device. */
+PULSECOL_API pulsecol_status pulsecol_validate_shape(const pulsecol_shape* shape);
+
+/* Create a context on HIP device `device`: copies `shape`, allocates the scratch
+ * (4*B*H*seq bytes of row statistics, 4*B*H*U*seq bytes of scores, 4*B*H*U*seq bytes for the
+ * cached pattern, a few KB of counters).  *out is set only on PULSECOL_OK. */
+PULSECOL_API pulsecol_status pulsecol_create(pulsecol_ctx** out, const pulsecol_shape* shape, int device);
+
+/* Free the scratch.  The caller must have synchronised the streams it used.  NULL is OK. */
+PULSECOL_API pulsecol_status pulsecol_destroy(pulsecol_ctx* ctx);
+
+/* Number of kept columns per query row, k = max(1, floor(keep_ratio * seq)), keep_ratio =
+ * 1 - sparsity (Sec. 3.1, sparsity-budget constraint ||S||_0 <= (1 - rho) n^2).  Host only.
+ * Returns -1 when seq < 1 or keep_ratio is outside (0, 1]. */
+PULSECOL_API int32_t pulsecol_num_keep(int32_t seq, double keep_ratio);
+
+/* Pattern identification pass (Sec. 3.3, score and TopK equations), run at the
+ * identification step and at every refresh step.
+ *   refresh != 0: compute the column scores of the CURRENT Q, K from the full softmax
+ *                 attention matrix, keep the k = pulsecol_num_keep(seq, keep_ratio) highest
+ *                 columns of every group (equal scores: lower column index wins), write them
+ *                 ascending to idx_out[B, H, U, k] and cache them in the context.
+ *   refresh == 0: Q and K are ignored (may be NULL); the cached pattern is copied to idx_out.
+ *                 PULSECOL_ERR_NO_PATTERN if nothing is cached or k differs. */
+PULSECOL_API pulsecol_status pulsecol_select(pulsecol_ctx* ctx, const void* Q, const void* K, double keep_ratio,
+                                int refresh, int32_t* idx_out, void* stream);
+
+/* The scoring stage alone (Sec. 3.3, score equation):
+ * scores_out[b, h, u, j] = (1/|G_u|) sum_{i in G_u} softmax_j(q_i . k_j * scale), fp32 [B, H, U, seq].
+ * Row sums of the softmax are accumulated in fp32 in a fixed order: results are
+ * bit-identical from run to run. */
+PULSECOL_API pulsecol_status pulsecol_scores(pulsecol_ctx* ctx, const void* Q, const void* K, float* scores_out,
+                                void* stream);
+
+/* The selection stage alone (Sec. 3.3, TopK equation) on caller-supplied scores
+ * [B, H, U, seq] (fp32, non-negative, device): exact top-k of every row, ties to the lower
+ * index, output ascending int32 [B, H, U, k].  Does not touch the cached pattern. */
+PULSECOL_API pulsecol_status pulsecol_topk(pulsecol_ctx* ctx, const float* scores, int32_t k, int32_t* idx_out,
+                              void* stream);
+
+/* Column-sparse attention forward (Sec. 3.4; appendix listing): for every query row i of
+ * group u, O_i = softmax over the k logits {q_i . k_j * scale : j in idx[b,h,u,:]} applied to
+ * the same rows of V -- equal to the masked form softmax(Z + M(S)) V of Sec. 3.1.  Online
+ * softmax over tiles of gathered K/V rows; nothing of size seq x seq or seq x k is written.
+ * 1 <= k <= seq.  O has the layout and dtype of Q. */
+PULSECOL_API pulsecol_status pulsecol_attn(pulsecol_ctx* ctx, const void* Q, const void* K, const void* V,
+                              const int32_t* idx, int32_t k, void* O, void* stream);
+
+/* Dense attention baseline O = softmax(Q K^T * scale) V (Sec. 3.1).  If lse_out is not NULL
+ * it receives the row log-sum-exp of the scaled logits, fp32 [B, H, seq]. */
+PULSECOL_API pulsecol_status pulsecol_attn_dense(pulsecol_ctx* ctx, const void* Q, const void* K, const void* V,
+                                    void* O, float* lse_out, void* stream);
+
+/* Refresh schedule (Sec. 3.3, schedule equation), host only: T_win = max(1, floor(eta*T));
+ * R == 1 -> {1}; else tau_r = 1 + floor((r-1)(T_win-1)/(R-1)).  Writes R 1-based steps to
+ * steps_out and returns R, or -1 on T < 1, R < 1, eta outside (0, 1] or a NULL pointer. */
+PULSECOL_API int32_t pulsecol_refresh_schedule(int32_t T, double eta, int32_t R, int32_t* steps_out);
+
+/* Launch geometry of the sparse kernel for this context (for reports): query rows per
+ * workgroup (B_M) and gathered columns per tile (B_N).  Host only. */
+PULSECOL_API pulsecol_status pulsecol_attn_tile_shape(const pulsecol_ctx* ctx, int32_t* block_m, int32_t* block_n);
+
+PULSECOL_API const char* pulsecol_status_str(pulsecol_status status);
+PULSECOL_API const char* pulsecol_last_error(const pulsecol_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PULSECOL_H */

@@ -1,0 +1,173 @@
+// Column softmax mass, bf16 inputs (Sec. 3.3, score equation, one group per head):
+//   s_j = (1/n) sum_i exp(z_ij - lse_i),  z_ij = q_i . k_j * scale,
+// with the row log-sum-exp lse_i produced by the row pass (attn_bf16.hip, lse-only mode) and
+// handed over in log2 units, so that p_ij = exp2(z_ij * scale * log2(e) - lse2_i).
+//
+// K-stationary: a workgroup owns 256 key columns (4 waves x 64); each wave keeps its K rows
+// in registers as the MFMA A operand and streams every 64-row Q tile of the head through
+// double-buffered LDS as the B operand.  In S^T[key][query] a lane owns one query column, so
+// exp2(z*c - lse_i*log2e) needs one per-lane scalar per query block, and the column sums are
+// plain per-lane, per-register accumulators; lanes are combined once, after the last tile,
+// in a fixed butterfly order.  P never leaves fp32 and there are no floating-point atomics:
+// the result is bit-identical from run to run.
+#include "pulsecol_device.h"
+#include "pulsecol_kernels.h"
+
+namespace pulsecol {
+namespace {
+
+constexpr int NTHREADS = 256;
+constexpr int KEYS_PER_WG = 256;
+constexpr int QT = 64;              // query rows per streamed tile
+constexpr int FLUSH = 16;           // tiles between flushes of the short accumulator into the long one
+
+template <int D>
+__global__ void __launch_bounds__(NTHREADS) colmass_bf16_kernel(ScoreParams p) {
+    constexpr int PIECES = D / 8;
+    constexpr int KK = D / 16;
+    constexpr int CH = QT * PIECES / NTHREADS;
+    constexpr int ROW_BYTES = D * 2;
+    constexpr int TILE_BYTES = QT * ROW_BYTES;
+
+    __shared__ __attribute__((aligned(16))) unsigned char lds_q[2][TILE_BYTES];
+    __shared__ float lds_lse[2][QT];
+
+    const int n = p.n;
+    const int nkb = (n + KEYS_PER_WG - 1) / KEYS_PER_WG;
+    int bh, kblk;
+    if (!xcd_tile(blockIdx.x, nkb, p.batch * p.heads, &bh, &kblk)) return;
+    const int b = bh / p.heads, h = bh - b * p.heads;
+    const int64_t head_off = (int64_t)b * p.td.sb + (int64_t)h * p.td.sh;
+    const __bf16* __restrict__ Q = (const __bf16*)p.q + head_off;
+    const __bf16* __restrict__ K = (const __bf16*)p.k + head_off;
+    const float* __restrict__ lse = p.lse + (int64_t)bh * n;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int lq = lane & 31, lh = lane >> 5;
+    const int key0 = kblk * KEYS_PER_WG + wave * 64;
+
+    // ---- stationary K fragments: A operand, [key lq][d = kk*16 + 8*lh .. +7]
+    bf16x8 kf[2][KK];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+        int row = key0 + kb * 32 + lq;
+        row = row < n ? row : n - 1;
+        const __bf16* src = K + (int64_t)row * p.td.sn + 8 * lh;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) kf[kb][kk] = *(const bf16x8*)(src + kk * 16);
+    }
+
+    u32x4 stage[CH];
+    float stage_lse = 0.f;
+    auto fetch = [&](int t) {
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+            const int c = tid + NTHREADS * j;
+            int row = t * QT + c / PIECES;
+            row = row < n ? row : n - 1;
+            stage[j] = *(const u32x4*)(Q + (int64_t)row * p.td.sn + (c % PIECES) * 8);
+        }
+        if (tid < QT) {
+            const int row = t * QT + tid;
+            // rows past the end get +inf: exp2(z - inf) = 0, they add nothing to any column
+            stage_lse = row < n ? lse[row] : INFINITY;
+        }
+    };
+    auto commit = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+            const int c = tid + NTHREADS * j;
+            const int row = c / PIECES, piece = c % PIECES;
+            *(u32x4*)(lds_q[buf] + row * ROW_BYTES + ((piece ^ swizzle_k<PIECES>(row)) << 4)) = stage[j];
+        }
+        if (tid < QT) lds_lse[buf][tid] = stage_lse;
+    };
+
+    const int ntiles = (n + QT - 1) / QT;
+    fetch(0);
+    commit(0);
+    __syncthreads();
+
+    const float c2 = p.scale * kLog2e;
+    f32x16 acc_short[2], acc_long[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { acc_short[kb][r] = 0.f; acc_long[kb][r] = 0.f; }
+
+    for (int t = 0; t < ntiles; ++t) {
+        const int buf = t & 1;
+        if (t + 1 < ntiles) fetch(t + 1);
+
+        f32x16 s[2][2];   // [kb][qb]
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[kb][qb][r] = 0.f;
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            const int row = qb * 32 + lq;
+            const unsigned char* rowp = lds_q[buf] + row * ROW_BYTES;
+            const int sw = swizzle_k<PIECES>(row);
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) {
+                const bf16x8 qfrag = *(const bf16x8*)(rowp + (((2 * kk + lh) ^ sw) << 4));
+                s[0][qb] = mfma_bf16(kf[0][kk], qfrag, s[0][qb]);
+                s[1][qb] = mfma_bf16(kf[1][kk], qfrag, s[1][qb]);
+            }
+        }
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            const float l2 = lds_lse[buf][qb * 32 + lq];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    acc_short[kb][r] += fast_exp2(__builtin_fmaf(s[kb][qb][r], c2, -l2));
+        }
+        if ((t % FLUSH) == FLUSH - 1) {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) { acc_long[kb][r] += acc_short[kb][r]; acc_short[kb][r] = 0.f; }
+        }
+
+        if (t + 1 < ntiles) commit(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- combine the 32 query-column lanes of each half (fixed butterfly), scale by 1/n, store
+    const float inv_n = 1.0f / (float)n;
+    float* __restrict__ out = p.scores + (int64_t)bh * n;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            float v = acc_long[kb][r] + acc_short[kb][r];
+#pragma unroll
+            for (int m = 1; m < 32; m <<= 1) v += __shfl_xor(v, m, 64);
+            const int key = key0 + kb * 32 + acc_row(r, lh);
+            if (lq == 0 && key < n) out[key] = v * inv_n;
+        }
+}
+
+template <int D>
+hipError_t launch(const ScoreParams& p, hipStream_t s) {
+    const int nkb = (p.n + KEYS_PER_WG - 1) / KEYS_PER_WG;
+    const int bh_pad = (p.batch * p.heads + 7) / 8 * 8;
+    hipLaunchKernelGGL((colmass_bf16_kernel<D>), dim3(nkb * bh_pad), dim3(NTHREADS), 0, s, p);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_colmass_bf16(const ScoreParams& p, int head_dim, hipStream_t s) {
+    if (head_dim == 128) return launch<128>(p, s);
+    if (head_dim == 64) return launch<64>(p, s);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace pulsecol

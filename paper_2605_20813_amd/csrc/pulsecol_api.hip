@@ -1,0 +1,303 @@
+// C-ABI layer of the library: argument validation, scratch ownership, kernel sequencing.
+// Host code only; every device-side step lives in the kernel translation units.
+#include "../../include/pulsecol.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <new>
+#include <string>
+
+#include "pulsecol_kernels.h"
+
+struct pulsecol_ctx {
+    pulsecol_shape shape;
+    int device = 0;
+    int groups = 1;                 // U
+    float scale = 0.f;
+    pulsecol::TensorDesc td{};
+    float* lse = nullptr;           // [B*H, n]   row log-sum-exp, log2 units
+    float* scores = nullptr;        // [B*H*U, n]
+    int32_t* cached_idx = nullptr;  // [B*H*U, cached_k]
+    int32_t cached_k = 0;           // 0 = nothing cached
+    std::string last_error;
+};
+
+namespace {
+
+thread_local std::string g_last_error;   // failures that have no context to attach to
+
+pulsecol_status fail(pulsecol_ctx* ctx, pulsecol_status st, const std::string& msg) {
+    if (ctx) ctx->last_error = msg;
+    g_last_error = msg;
+    return st;
+}
+
+pulsecol_status fail_hip(pulsecol_ctx* ctx, hipError_t e, const char* what) {
+    return fail(ctx, PULSECOL_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+int elem_align(int dtype) { return dtype == PULSECOL_BF16 ? 8 : 4; }
+
+bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+// keep_ratio * count with a guard against binary representation error of decimal ratios
+int64_t floor_product(double ratio, int64_t count) {
+    return (int64_t)std::floor(ratio * (double)count + 1e-9);
+}
+
+pulsecol_status check_shape(const pulsecol_shape* s, std::string* why) {
+    if (!s) { *why = "shape is NULL"; return PULSECOL_ERR_INVALID_ARG; }
+    if (s->batch < 1 || s->heads < 1 || s->seq < 1) { *why = "batch, heads and seq must be >= 1"; return PULSECOL_ERR_INVALID_ARG; }
+    if (s->group_size < 0) { *why = "group_size must be >= 0"; return PULSECOL_ERR_INVALID_ARG; }
+    if (s->scale < 0.f || !std::isfinite(s->scale)) { *why = "scale must be finite and >= 0"; return PULSECOL_ERR_INVALID_ARG; }
+    if (s->stride_b < 0 || s->stride_h < 0 || s->stride_n < 0) { *why = "strides must be >= 0"; return PULSECOL_ERR_INVALID_ARG; }
+    if (s->dtype != PULSECOL_BF16 && s->dtype != PULSECOL_F32) { *why = "dtype must be PULSECOL_BF16 or PULSECOL_F32"; return PULSECOL_ERR_UNSUPPORTED; }
+    if (s->head_dim != 64 && s->head_dim != 128) { *why = "head_dim must be 64 or 128"; return PULSECOL_ERR_UNSUPPORTED; }
+    if (s->group_size != 0 && s->group_size < s->seq) { *why = "per-group column sets (0 < group_size < seq) are not built yet"; return PULSECOL_ERR_UNSUPPORTED; }
+    if ((int64_t)s->batch * s->heads > (1 << 20)) { *why = "batch*heads too large"; return PULSECOL_ERR_UNSUPPORTED; }
+    if (s->stride_n != 0 && s->stride_n < s->head_dim) { *why = "stride_n smaller than head_dim"; return PULSECOL_ERR_INVALID_ARG; }
+    const int a = elem_align(s->dtype);
+    if (s->stride_b % a || s->stride_h % a || s->stride_n % a) { *why = "strides must be multiples of 16 bytes"; return PULSECOL_ERR_ALIGNMENT; }
+    return PULSECOL_OK;
+}
+
+struct DeviceGuard {
+    int prev = -1;
+    bool switched = false;
+    hipError_t err = hipSuccess;
+    explicit DeviceGuard(int dev) {
+        err = hipGetDevice(&prev);
+        if (err == hipSuccess && prev != dev) {
+            err = hipSetDevice(dev);
+            switched = (err == hipSuccess);
+        }
+    }
+    ~DeviceGuard() { if (switched) (void)hipSetDevice(prev); }
+};
+
+pulsecol::AttnParams attn_params(const pulsecol_ctx* c, const void* Q, const void* K, const void* V, void* O,
+                                 const int32_t* idx, int32_t ns, float* lse, int lse_base2) {
+    pulsecol::AttnParams p{};
+    p.q = Q; p.k = K; p.v = V; p.o = O; p.idx = idx; p.lse = lse; p.lse_base2 = lse_base2;
+    p.td = c->td;
+    p.batch = c->shape.batch; p.heads = c->shape.heads; p.n = c->shape.seq; p.ns = ns;
+    p.scale = c->scale;
+    return p;
+}
+
+hipError_t launch_attn(const pulsecol_ctx* c, const pulsecol::AttnParams& p, pulsecol::AttnMode mode, hipStream_t s) {
+    return c->shape.dtype == PULSECOL_BF16 ? pulsecol::launch_attn_bf16(p, c->shape.head_dim, mode, s)
+                                           : pulsecol::launch_attn_f32(p, c->shape.head_dim, mode, s);
+}
+
+pulsecol_status check_ptrs(pulsecol_ctx* ctx, std::initializer_list<const void*> tensors, const char* who) {
+    for (const void* t : tensors) {
+        if (!t) return fail(ctx, PULSECOL_ERR_INVALID_ARG, std::string(who) + ": NULL tensor pointer");
+        if (misaligned(t)) return fail(ctx, PULSECOL_ERR_ALIGNMENT, std::string(who) + ": tensor pointer not 16-byte aligned");
+    }
+    return PULSECOL_OK;
+}
+
+// scores of the current Q, K into `out` (two launches: row pass, column pass)
+pulsecol_status run_scores(pulsecol_ctx* ctx, const void* Q, const void* K, float* out, hipStream_t s) {
+    pulsecol::AttnParams ap = attn_params(ctx, Q, K, nullptr, nullptr, nullptr, ctx->shape.seq, ctx->lse, 1);
+    hipError_t e = launch_attn(ctx, ap, pulsecol::kLseOnly, s);
+    if (e != hipSuccess) return fail_hip(ctx, e, "row log-sum-exp kernel");
+    pulsecol::ScoreParams sp{};
+    sp.q = Q; sp.k = K; sp.lse = ctx->lse; sp.scores = out; sp.td = ctx->td;
+    sp.batch = ctx->shape.batch; sp.heads = ctx->shape.heads; sp.n = ctx->shape.seq; sp.scale = ctx->scale;
+    e = ctx->shape.dtype == PULSECOL_BF16 ? pulsecol::launch_colmass_bf16(sp, ctx->shape.head_dim, s)
+                                          : pulsecol::launch_colmass_f32(sp, ctx->shape.head_dim, s);
+    if (e != hipSuccess) return fail_hip(ctx, e, "column-mass kernel");
+    return PULSECOL_OK;
+}
+
+pulsecol_status run_topk(pulsecol_ctx* ctx, const float* scores, int32_t k, int32_t* out, hipStream_t s) {
+    pulsecol::TopkParams tp{};
+    tp.scores = scores; tp.idx = out;
+    tp.rows = ctx->shape.batch * ctx->shape.heads * ctx->groups; tp.n = ctx->shape.seq; tp.k = k;
+    const hipError_t e = pulsecol::launch_topk(tp, s);
+    if (e != hipSuccess) return fail_hip(ctx, e, "top-k kernel");
+    return PULSECOL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+pulsecol_status pulsecol_validate_shape(const pulsecol_shape* shape) {
+    std::string why;
+    const pulsecol_status st = check_shape(shape, &why);
+    return st == PULSECOL_OK ? st : fail(nullptr, st, why);
+}
+
+pulsecol_status pulsecol_create(pulsecol_ctx** out, const pulsecol_shape* shape, int device) {
+    if (!out) return fail(nullptr, PULSECOL_ERR_INVALID_ARG, "pulsecol_create: out is NULL");
+    std::string why;
+    pulsecol_status st = check_shape(shape, &why);
+    if (st != PULSECOL_OK) return fail(nullptr, st, "pulsecol_create: " + why);
+    int ndev = 0;
+    hipError_t e = hipGetDeviceCount(&ndev);
+    if (e != hipSuccess) return fail_hip(nullptr, e, "pulsecol_create: hipGetDeviceCount");
+    if (device < 0 || device >= ndev) return fail(nullptr, PULSECOL_ERR_INVALID_ARG, "pulsecol_create: no such device");
+
+    pulsecol_ctx* c = new (std::nothrow) pulsecol_ctx();
+    if (!c) return fail(nullptr, PULSECOL_ERR_OOM, "pulsecol_create: host allocation failed");
+    c->shape = *shape;
+    c->device = device;
+    c->groups = 1;
+    c->scale = shape->scale > 0.f ? shape->scale : 1.0f / std::sqrt((float)shape->head_dim);
+    c->td.sn = shape->stride_n ? shape->stride_n : shape->head_dim;
+    c->td.sh = shape->stride_h ? shape->stride_h : (int64_t)shape->seq * c->td.sn;
+    c->td.sb = shape->stride_b ? shape->stride_b : (int64_t)shape->heads * c->td.sh;
+
+    DeviceGuard guard(device);
+    if (guard.err != hipSuccess) { delete c; return fail_hip(nullptr, guard.err, "pulsecol_create: hipSetDevice"); }
+    const size_t rows = (size_t)shape->batch * shape->heads;
+    const size_t row_bytes = (size_t)shape->seq * sizeof(float);
+    hipError_t e1 = hipMalloc((void**)&c->lse, rows * row_bytes);
+    hipError_t e2 = e1 == hipSuccess ? hipMalloc((void**)&c->scores, rows * c->groups * row_bytes) : e1;
+    hipError_t e3 = e2 == hipSuccess ? hipMalloc((void**)&c->cached_idx, rows * c->groups * row_bytes) : e2;
+    if (e3 != hipSuccess) {
+        if (c->lse) (void)hipFree(c->lse);
+        if (c->scores) (void)hipFree(c->scores);
+        (void)hipGetLastError();
+        delete c;
+        return e3 == hipErrorOutOfMemory ? fail(nullptr, PULSECOL_ERR_OOM, "pulsecol_create: scratch allocation failed")
+                                         : fail_hip(nullptr, e3, "pulsecol_create: hipMalloc");
+    }
+    *out = c;
+    return PULSECOL_OK;
+}
+
+pulsecol_status pulsecol_destroy(pulsecol_ctx* ctx) {
+    if (!ctx) return PULSECOL_OK;
+    DeviceGuard guard(ctx->device);
+    (void)hipFree(ctx->lse);
+    (void)hipFree(ctx->scores);
+    (void)hipFree(ctx->cached_idx);
+    delete ctx;
+    return PULSECOL_OK;
+}
+
+int32_t pulsecol_num_keep(int32_t seq, double keep_ratio) {
+    if (seq < 1 || !(keep_ratio > 0.0) || !(keep_ratio <= 1.0)) return -1;
+    const int64_t k = floor_product(keep_ratio, seq);
+    return (int32_t)(k < 1 ? 1 : (k > seq ? seq : k));
+}
+
+pulsecol_status pulsecol_scores(pulsecol_ctx* ctx, const void* Q, const void* K, float* scores_out, void* stream) {
+    if (!ctx) return fail(nullptr, PULSECOL_ERR_INVALID_ARG, "pulsecol_scores: ctx is NULL");
+    pulsecol_status st = check_ptrs(ctx, {Q, K, scores_out}, "pulsecol_scores");
+    if (st != PULSECOL_OK) return st;
+    DeviceGuard guard(ctx->device);
+    if (guard.err != hipSuccess) return fail_hip(ctx, guard.err, "pulsecol_scores: hipSetDevice");
+    return run_scores(ctx, Q, K, scores_out, (hipStream_t)stream);
+}
+
+pulsecol_status pulsecol_topk(pulsecol_ctx* ctx, const float* scores, int32_t k, int32_t* idx_out, void* stream) {
+    if (!ctx) return fail(nullptr, PULSECOL_ERR_INVALID_ARG, "pulsecol_topk: ctx is NULL");
+    if (!scores || !idx_out) return fail(ctx, PULSECOL_ERR_INVALID_ARG, "pulsecol_topk: NULL pointer");
+    if (k < 1 || k > ctx->shape.seq) return fail(ctx, PULSECOL_ERR_INVALID_ARG, "pulsecol_topk: need 1 <= k <= seq");
+    DeviceGuard guard(ctx->device);
+    if (guard.err != hipSuccess) return fail_hip(ctx, guard.err, "pulsecol_topk: hipSetDevice");
+    return run_topk(ctx, scores, k, idx_out, (hipStream_t)stream);
+}
+
+pulsecol_status pulsecol_select(pulsecol_ctx* ctx, const void* Q, const void* K, double keep_ratio, int refresh,
+                                int32_t* idx_out, void* stream) {
+    if (!ctx) return fail(nullptr, PULSECOL_ERR_INVALID_ARG, "pulsecol_select: ctx is NULL");
+    if (!idx_out) return fail(ctx, PULSECOL_ERR_INVALID_ARG, "pulsecol_select: idx_out is NULL");
+    const int32_t k = pulsecol_num_keep(ctx->shape.seq, keep_ratio);
+    if (k < 0) return fail(ctx, PULSECOL_ERR_INVALID_ARG, "pulsecol_select: keep_ratio must be in (0, 1]");
+    const size_t idx_bytes = (size_t)ctx->shape.batch * ctx->shape.heads * ctx->groups * (size_t)k * sizeof(int32_t);
+    hipStream_t s = (hipStream_t)stream;
+    if (!refresh) {
+        if (ctx->cached_k == 0) return fail(ctx, PULSECOL_ERR_NO_PATTERN, "pulsecol_select: refresh == 0 but no pattern is cached");
+        if (ctx->cached_k != k) return fail(ctx, PULSECOL_ERR_NO_PATTERN, "pulsecol_select: cached pattern has a different k");
+        DeviceGuard guard(ctx->device);
+        if (guard.err != hipSuccess) return fail_hip(ctx, guard.err, "pulsecol_select: hipSetDevice");
+        const hipError_t e = hipMemcpyAsync(idx_out, ctx->cached_idx, idx_bytes, hipMemcpyDeviceToDevice, s);
+        if (e != hipSuccess) return fail_hip(ctx, e, "pulsecol_select: copy of the cached pattern");
+        return PULSECOL_OK;
+    }
+    pulsecol_status st = check_ptrs(ctx, {Q, K}, "pulsecol_select");
+    if (st != PULSECOL_OK) return st;
+    DeviceGuard guard(ctx->device);
+    if (guard.err != hipSuccess) return fail_hip(ctx, guard.err, "pulsecol_select: hipSetDevice");
+    st = run_scores(ctx, Q, K, ctx->scores, s);
+    if (st != PULSECOL_OK) return st;
+    st = run_topk(ctx, ctx->scores, k, idx_out, s);
+    if (st != PULSECOL_OK) return st;
+    ctx->cached_k = 0;
+    const hipError_t e = hipMemcpyAsync(ctx->cached_idx, idx_out, idx_bytes, hipMemcpyDeviceToDevice, s);
+    if (e != hipSuccess) return fail_hip(ctx, e, "pulsecol_select: caching the pattern");
+    ctx->cached_k = k;
+    return PULSECOL_OK;
+}
+
+pulsecol_status pulsecol_attn(pulsecol_ctx* ctx, const void* Q, const void* K, const void* V, const int32_t* idx,
+                              int32_t k, void* O, void* stream) {
+    if (!ctx) return fail(nullptr, PULSECOL_ERR_INVALID_ARG, "pulsecol_attn: ctx is NULL");
+    pulsecol_status st = check_ptrs(ctx, {Q, K, V, O}, "pulsecol_attn");
+    if (st != PULSECOL_OK) return st;
+    if (!idx) return fail(ctx, PULSECOL_ERR_INVALID_ARG, "pulsecol_attn: idx is NULL");
+    if (k < 1 || k > ctx->shape.seq) return fail(ctx, PULSECOL_ERR_INVALID_ARG, "pulsecol_attn: need 1 <= k <= seq");
+    DeviceGuard guard(ctx->device);
+    if (guard.err != hipSuccess) return fail_hip(ctx, guard.err, "pulsecol_attn: hipSetDevice");
+    const pulsecol::AttnParams p = attn_params(ctx, Q, K, V, O, idx, k, nullptr, 0);
+    const hipError_t e = launch_attn(ctx, p, pulsecol::kSparse, (hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "column-sparse attention kernel");
+    return PULSECOL_OK;
+}
+
+pulsecol_status pulsecol_attn_dense(pulsecol_ctx* ctx, const void* Q, const void* K, const void* V, void* O,
+                                    float* lse_out, void* stream) {
+    if (!ctx) return fail(nullptr, PULSECOL_ERR_INVALID_ARG, "pulsecol_attn_dense: ctx is NULL");
+    pulsecol_status st = check_ptrs(ctx, {Q, K, V, O}, "pulsecol_attn_dense");
+    if (st != PULSECOL_OK) return st;
+    DeviceGuard guard(ctx->device);
+    if (guard.err != hipSuccess) return fail_hip(ctx, guard.err, "pulsecol_attn_dense: hipSetDevice");
+    const pulsecol::AttnParams p = attn_params(ctx, Q, K, V, O, nullptr, ctx->shape.seq, lse_out, 0);
+    const hipError_t e = launch_attn(ctx, p, pulsecol::kDense, (hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "dense attention kernel");
+    return PULSECOL_OK;
+}
+
+int32_t pulsecol_refresh_schedule(int32_t T, double eta, int32_t R, int32_t* steps_out) {
+    if (T < 1 || R < 1 || !(eta > 0.0) || !(eta <= 1.0) || !steps_out) return -1;
+    int64_t t_win = floor_product(eta, T);
+    if (t_win < 1) t_win = 1;
+    if (R == 1) { steps_out[0] = 1; return 1; }
+    for (int64_t r = 1; r <= R; ++r) steps_out[r - 1] = (int32_t)(1 + ((r - 1) * (t_win - 1)) / (R - 1));
+    return R;
+}
+
+pulsecol_status pulsecol_attn_tile_shape(const pulsecol_ctx* ctx, int32_t* block_m, int32_t* block_n) {
+    if (!ctx || !block_m || !block_n) return fail(nullptr, PULSECOL_ERR_INVALID_ARG, "pulsecol_attn_tile_shape: NULL pointer");
+    const bool bf = ctx->shape.dtype == PULSECOL_BF16;
+    *block_m = bf ? pulsecol::kBlockM_bf16 : pulsecol::kBlockM_f32;
+    *block_n = bf ? pulsecol::kBlockN_bf16 : pulsecol::kBlockN_f32;
+    return PULSECOL_OK;
+}
+
+const char* pulsecol_status_str(pulsecol_status status) {
+    switch (status) {
+        case PULSECOL_OK: return "ok";
+        case PULSECOL_ERR_INVALID_ARG: return "invalid argument";
+        case PULSECOL_ERR_UNSUPPORTED: return "unsupported configuration";
+        case PULSECOL_ERR_ALIGNMENT: return "misaligned pointer or stride";
+        case PULSECOL_ERR_NO_PATTERN: return "no cached pattern";
+        case PULSECOL_ERR_OOM: return "out of device memory";
+        case PULSECOL_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+const char* pulsecol_last_error(const pulsecol_ctx* ctx) {
+    return ctx ? ctx->last_error.c_str() : g_last_error.c_str();
+}
+
+}  // extern "C"

@@ -1,0 +1,56 @@
+// Host-side launch interface between the C-ABI layer and the kernel translation units.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pulsecol {
+
+struct TensorDesc {          // [B, H, n, D] tensor, last dimension contiguous, strides in elements
+    int64_t sb, sh, sn;
+};
+
+struct AttnParams {
+    const void* q;
+    const void* k;
+    const void* v;
+    void* o;
+    const int32_t* idx;      // [B*H, ns] (one column set per head) or nullptr for dense
+    float* lse;              // optional [B*H, n] row log-sum-exp of the scaled logits
+    int32_t lse_base2;       // 0: natural log; 1: log2 units (what the column-mass pass consumes)
+    TensorDesc td;
+    int32_t batch, heads, n, ns;   // ns = columns attended per row (dense: n)
+    float scale;             // logit scale
+};
+
+struct ScoreParams {
+    const void* q;
+    const void* k;
+    const float* lse;        // [B*H, n], log2 units: log2 sum_j exp(z_ij)
+    float* scores;           // [B*H, n]
+    TensorDesc td;
+    int32_t batch, heads, n;
+    float scale;
+};
+
+struct TopkParams {
+    const float* scores;     // [rows, n]
+    int32_t* idx;            // [rows, k]
+    int32_t rows, n, k;
+};
+
+enum AttnMode { kSparse = 0, kDense = 1, kLseOnly = 2 };
+
+// Tile geometry of the attention kernels.
+constexpr int kBlockM_bf16 = 256;   // query rows per workgroup (4 waves x 64)
+constexpr int kBlockN_bf16 = 64;    // gathered columns per tile
+constexpr int kBlockM_f32 = 128;    // 4 waves x 32
+constexpr int kBlockN_f32 = 32;
+
+hipError_t launch_attn_bf16(const AttnParams& p, int head_dim, AttnMode mode, hipStream_t s);
+hipError_t launch_attn_f32(const AttnParams& p, int head_dim, AttnMode mode, hipStream_t s);
+hipError_t launch_colmass_bf16(const ScoreParams& p, int head_dim, hipStream_t s);
+hipError_t launch_colmass_f32(const ScoreParams& p, int head_dim, hipStream_t s);
+hipError_t launch_topk(const TopkParams& p, hipStream_t s);
+
+}  // namespace pulsecol

@@ -1,0 +1,229 @@
+"""Thin ctypes binding over libpulsecol.so: argument marshalling only.
+
+Function names follow include/pulsecol.h.  PyTorch supplies device memory and the
+current HIP stream; every step of the method runs inside the library's kernels.  There is
+no fallback: if the shared library is missing, loading raises.
+"""
+
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, c_char_p, c_double, c_float, c_int, c_int32, c_int64, c_void_p
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpulsecol.so")
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_ALIGNMENT, ERR_NO_PATTERN, ERR_OOM, ERR_HIP = range(7)
+BF16, F32 = 0, 1
+
+EXPORTS = (
+    "pulsecol_validate_shape", "pulsecol_create", "pulsecol_destroy", "pulsecol_num_keep",
+    "pulsecol_select", "pulsecol_scores", "pulsecol_topk", "pulsecol_attn", "pulsecol_attn_dense",
+    "pulsecol_refresh_schedule", "pulsecol_attn_tile_shape", "pulsecol_status_str", "pulsecol_last_error",
+)
+
+
+class Shape(ctypes.Structure):
+    _fields_ = [("batch", c_int32), ("heads", c_int32), ("seq", c_int32), ("head_dim", c_int32),
+                ("dtype", c_int32), ("group_size", c_int32),
+                ("stride_b", c_int64), ("stride_h", c_int64), ("stride_n", c_int64),
+                ("scale", c_float)]
+
+
+class PulseColError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"pulsecol status {status}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libpulsecol.so (built by ``python -m paper_2605_20813_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2605_20813_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        L.pulsecol_validate_shape.argtypes = [POINTER(Shape)]
+        L.pulsecol_create.argtypes = [POINTER(c_void_p), POINTER(Shape), c_int]
+        L.pulsecol_destroy.argtypes = [c_void_p]
+        L.pulsecol_num_keep.argtypes = [c_int32, c_double]
+        L.pulsecol_num_keep.restype = c_int32
+        L.pulsecol_select.argtypes = [c_void_p, c_void_p, c_void_p, c_double, c_int, c_void_p, c_void_p]
+        L.pulsecol_scores.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+        L.pulsecol_topk.argtypes = [c_void_p, c_void_p, c_int32, c_void_p, c_void_p]
+        L.pulsecol_attn.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_void_p]
+        L.pulsecol_attn_dense.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+        L.pulsecol_refresh_schedule.argtypes = [c_int32, c_double, c_int32, POINTER(c_int32)]
+        L.pulsecol_refresh_schedule.restype = c_int32
+        L.pulsecol_attn_tile_shape.argtypes = [c_void_p, POINTER(c_int32), POINTER(c_int32)]
+        L.pulsecol_status_str.argtypes = [c_int]
+        L.pulsecol_status_str.restype = c_char_p
+        L.pulsecol_last_error.argtypes = [c_void_p]
+        L.pulsecol_last_error.restype = c_char_p
+        _lib = L
+    return _lib
+
+
+def _dtype_code(dtype) -> int:
+    if dtype in (torch.bfloat16, "bf16", BF16):
+        return BF16
+    if dtype in (torch.float32, "f32", F32):
+        return F32
+    raise ValueError(f"unsupported dtype {dtype}")
+
+
+def make_shape(batch, heads, seq, head_dim, dtype, group_size=0, strides=(0, 0, 0), scale=0.0) -> Shape:
+    return Shape(batch, heads, seq, head_dim, _dtype_code(dtype), group_size, *strides, scale)
+
+
+def validate_shape(shape: Shape) -> int:
+    return lib().pulsecol_validate_shape(ctypes.byref(shape))
+
+
+def num_keep(seq: int, keep_ratio: float) -> int:
+    return lib().pulsecol_num_keep(seq, keep_ratio)
+
+
+def refresh_schedule(T: int, eta: float, R: int):
+    buf = (c_int32 * max(R, 1))()
+    r = lib().pulsecol_refresh_schedule(T, eta, R, buf)
+    if r < 0:
+        raise PulseColError(ERR_INVALID_ARG, "pulsecol_refresh_schedule: bad arguments")
+    return list(buf[:r])
+
+
+def status_str(status: int) -> str:
+    return lib().pulsecol_status_str(status).decode()
+
+
+def last_error(handle=None) -> str:
+    return lib().pulsecol_last_error(handle).decode()
+
+
+def _ptr(t):
+    return None if t is None else c_void_p(t.data_ptr())
+
+
+def _stream():
+    return c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+class Context:
+    """Owns one pulsecol_ctx.  Tensors are [B, H, n, d] on the context's device."""
+
+    def __init__(self, batch, heads, seq, head_dim, dtype, group_size=0, strides=(0, 0, 0), scale=0.0, device=0):
+        self.shape = make_shape(batch, heads, seq, head_dim, dtype, group_size, strides, scale)
+        self.torch_dtype = torch.bfloat16 if self.shape.dtype == BF16 else torch.float32
+        self.device = torch.device("cuda", device)
+        self._h = c_void_p()
+        st = lib().pulsecol_create(ctypes.byref(self._h), ctypes.byref(self.shape), device)
+        if st != OK:
+            self._h = None
+            raise PulseColError(st, last_error(None))
+
+    # -- lifetime
+    def close(self):
+        if getattr(self, "_h", None):
+            torch.cuda.synchronize(self.device)
+            lib().pulsecol_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *a):
+        self.close()
+
+    def _check(self, st):
+        if st != OK:
+            raise PulseColError(st, last_error(self._h))
+
+    def _check_tensor(self, t, name):
+        s = self.shape
+        if t.device != self.device or t.dtype != self.torch_dtype:
+            raise ValueError(f"{name}: expected {self.torch_dtype} on {self.device}")
+        if tuple(t.shape) != (s.batch, s.heads, s.seq, s.head_dim):
+            raise ValueError(f"{name}: expected shape {(s.batch, s.heads, s.seq, s.head_dim)}, got {tuple(t.shape)}")
+        want = (s.stride_b or s.heads * (s.stride_h or s.seq * (s.stride_n or s.head_dim)),
+                s.stride_h or s.seq * (s.stride_n or s.head_dim), s.stride_n or s.head_dim, 1)
+        if tuple(t.stride()) != want:
+            raise ValueError(f"{name}: strides {tuple(t.stride())} do not match the context's {want}")
+
+    @property
+    def groups(self) -> int:
+        return 1
+
+    def tile_shape(self):
+        bm, bn = c_int32(), c_int32()
+        self._check(lib().pulsecol_attn_tile_shape(self._h, ctypes.byref(bm), ctypes.byref(bn)))
+        return bm.value, bn.value
+
+    # -- the calls of include/pulsecol.h
+    def select(self, Q, K, keep_ratio: float, refresh: bool = True, idx_out=None):
+        s = self.shape
+        k = num_keep(s.seq, keep_ratio)
+        if k < 0:
+            raise PulseColError(ERR_INVALID_ARG, "keep_ratio must be in (0, 1]")
+        if idx_out is None:
+            idx_out = torch.empty(s.batch, s.heads, self.groups, k, dtype=torch.int32, device=self.device)
+        if refresh:
+            self._check_tensor(Q, "Q")
+            self._check_tensor(K, "K")
+        self._check(lib().pulsecol_select(self._h, _ptr(Q) if refresh else None, _ptr(K) if refresh else None,
+                                          keep_ratio, int(bool(refresh)), _ptr(idx_out), _stream()))
+        return idx_out
+
+    def scores(self, Q, K, scores_out=None):
+        s = self.shape
+        self._check_tensor(Q, "Q")
+        self._check_tensor(K, "K")
+        if scores_out is None:
+            scores_out = torch.empty(s.batch, s.heads, self.groups, s.seq, dtype=torch.float32, device=self.device)
+        self._check(lib().pulsecol_scores(self._h, _ptr(Q), _ptr(K), _ptr(scores_out), _stream()))
+        return scores_out
+
+    def topk(self, scores, k: int, idx_out=None):
+        s = self.shape
+        if scores.dtype != torch.float32 or not scores.is_contiguous() or scores.device != self.device \
+                or scores.numel() != s.batch * s.heads * self.groups * s.seq:
+            raise ValueError("scores: expected contiguous fp32 [B, H, U, seq] on the context's device")
+        if idx_out is None:
+            idx_out = torch.empty(s.batch, s.heads, self.groups, max(k, 1), dtype=torch.int32, device=self.device)
+        self._check(lib().pulsecol_topk(self._h, _ptr(scores), k, _ptr(idx_out), _stream()))
+        return idx_out
+
+    def attn(self, Q, K, V, idx, O=None):
+        for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):
+            self._check_tensor(t, nm)
+        s = self.shape
+        if idx.dtype != torch.int32 or not idx.is_contiguous() or idx.device != self.device \
+                or idx.dim() != 4 or tuple(idx.shape[:3]) != (s.batch, s.heads, self.groups):
+            raise ValueError("idx: expected contiguous int32 [B, H, U, k] on the context's device")
+        if O is None:
+            O = torch.empty_like(Q)
+        else:
+            self._check_tensor(O, "O")
+        self._check(lib().pulsecol_attn(self._h, _ptr(Q), _ptr(K), _ptr(V), _ptr(idx), idx.shape[3], _ptr(O), _stream()))
+        return O
+
+    def attn_dense(self, Q, K, V, O=None, lse_out=None):
+        for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):
+            self._check_tensor(t, nm)
+        if O is None:
+            O = torch.empty_like(Q)
+        else:
+            self._check_tensor(O, "O")
+        self._check(lib().pulsecol_attn_dense(self._h, _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(lse_out), _stream()))
+        return O

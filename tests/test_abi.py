@@ -1,0 +1,108 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, and its host-only entry points (shape validation, keep count, refresh
+schedule, status strings) behave as documented."""
+
+import ctypes
+import json
+import os
+import re
+
+import pytest
+import torch
+
+import oracle
+from paper_2605_20813_amd import pulsecol as pc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "pulsecol.h")
+
+
+def _declared():
+    src = open(HEADER).read()
+    return sorted(set(re.findall(r"PULSECOL_API\s+[\w\s\*]+?\b(pulsecol_\w+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared()
+    assert len(names) >= 13
+    assert sorted(pc.EXPORTS) == names
+    L = ctypes.CDLL(pc.LIB_PATH)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_status_strings():
+    seen = {pc.status_str(i) for i in range(7)}
+    assert len(seen) == 7 and "ok" in seen
+    assert pc.status_str(99) == "unknown status"
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(), pc.OK),
+    (dict(batch=0), pc.ERR_INVALID_ARG),
+    (dict(heads=0), pc.ERR_INVALID_ARG),
+    (dict(seq=0), pc.ERR_INVALID_ARG),
+    (dict(head_dim=96), pc.ERR_UNSUPPORTED),
+    (dict(head_dim=256), pc.ERR_UNSUPPORTED),
+    (dict(group_size=-1), pc.ERR_INVALID_ARG),
+    (dict(group_size=32), pc.ERR_UNSUPPORTED),          # per-group sets: not built yet
+    (dict(group_size=4096), pc.OK),                     # one group covering every query == per head
+    (dict(strides=(0, 0, 100)), pc.ERR_INVALID_ARG),    # stride_n < head_dim
+    (dict(strides=(0, 0, 132)), pc.ERR_ALIGNMENT),      # not a multiple of 8 bf16 elements
+    (dict(strides=(0, 0, 136)), pc.OK),
+    (dict(scale=-1.0), pc.ERR_INVALID_ARG),
+    (dict(scale=float("nan")), pc.ERR_INVALID_ARG),
+])
+def test_validate_shape(kw, want):
+    args = dict(batch=1, heads=32, seq=4096, head_dim=128, dtype=pc.BF16, group_size=0, strides=(0, 0, 0), scale=0.0)
+    args.update(kw)
+    assert pc.validate_shape(pc.make_shape(**args)) == want
+    if want != pc.OK:
+        assert pc.last_error(None)
+
+
+def test_validate_shape_dtype_and_null():
+    s = pc.make_shape(1, 2, 256, 64, pc.F32)
+    assert pc.validate_shape(s) == pc.OK
+    s.dtype = 7
+    assert pc.validate_shape(s) == pc.ERR_UNSUPPORTED
+    assert pc.lib().pulsecol_validate_shape(None) == pc.ERR_INVALID_ARG
+    s4 = pc.make_shape(1, 2, 256, 64, pc.F32, strides=(0, 0, 66))
+    assert pc.validate_shape(s4) == pc.ERR_ALIGNMENT
+
+
+def test_num_keep_matches_the_oracle_rule():
+    for n, r in ((256, .25), (4096, .1), (16384, .1), (32768, .05), (32768, .1), (32768, .2), (65536, .1),
+                 (100, .29), (5, .1), (7, 1.0), (1000, 0.333), (3, 0.5)):
+        assert pc.num_keep(n, r) == oracle.num_keep(n, r), (n, r)
+    assert pc.num_keep(0, .5) == -1 and pc.num_keep(8, 0.0) == -1 and pc.num_keep(8, 1.01) == -1
+    assert pc.num_keep(8, float("nan")) == -1
+
+
+def test_refresh_schedule_matches_golden_and_oracle():
+    with open(os.path.join(ROOT, "tests", "golden", "eq8_schedules.json")) as f:
+        for c in json.load(f)["cases"]:
+            assert pc.refresh_schedule(c["T"], c["eta"], c["R"]) == c["tau"]
+    for T, eta, R in ((100, .5, 7), (1000, .3, 16), (17, 1.0, 17), (50, .1, 3), (100, .29, 5), (3, .1, 2)):
+        assert pc.refresh_schedule(T, eta, R) == oracle.refresh_schedule(T, eta, R)
+    with pytest.raises(pc.PulseColError):
+        pc.refresh_schedule(0, .3, 4)
+    with pytest.raises(pc.PulseColError):
+        pc.refresh_schedule(10, 1.5, 4)
+
+
+def test_null_context_calls_fail_cleanly():
+    L = pc.lib()
+    assert L.pulsecol_attn(None, None, None, None, None, 1, None, None) == pc.ERR_INVALID_ARG
+    assert L.pulsecol_select(None, None, None, 0.1, 1, None, None) == pc.ERR_INVALID_ARG
+    assert L.pulsecol_scores(None, None, None, None, None) == pc.ERR_INVALID_ARG
+    assert L.pulsecol_topk(None, None, 1, None, None) == pc.ERR_INVALID_ARG
+    assert L.pulsecol_attn_dense(None, None, None, None, None, None, None) == pc.ERR_INVALID_ARG
+    assert L.pulsecol_destroy(None) == pc.OK
+    assert L.pulsecol_create(None, None, 0) == pc.ERR_INVALID_ARG
+
+
+@pytest.mark.skipif(torch.cuda.is_available(), reason="only meaningful on a box without a GPU")
+def test_create_without_gpu_reports_an_error():
+    with pytest.raises(pc.PulseColError):
+        pc.Context(1, 2, 256, 64, pc.F32)

@@ -1,0 +1,297 @@
+"""GPU parity: every entry point of the C-ABI library against the fp64 CPU oracle, element by
+element, on seeded synthetic inputs -- small and medium sizes that span several tiles and
+ragged tails, plus the edge cases of the method.  Full-size cases live in
+test_gpu_fullsize.py."""
+
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_20813_amd import pulsecol as pc
+from paper_2605_20813_amd import workloads as wl
+from parity_util import TOL, assert_close, assert_idx_matches, f64, random_idx
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def rand_qkv(B, H, n, d, dtype, seed):
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    return tuple(torch.randn(B, H, n, d, generator=g, dtype=torch.float32).to(dtype) for _ in range(3))
+
+
+def kind_of(dtype):
+    return "bf16" if dtype == torch.bfloat16 else "f32"
+
+
+# ---------------------------------------------------------------------------------------
+# column-sparse attention
+# ---------------------------------------------------------------------------------------
+ATTN_CASES = [
+    # B, H, n, d, dtype, k
+    (1, 2, 256, 64, torch.float32, 64),        # the tiny workload's shape
+    (1, 3, 1000, 128, torch.bfloat16, 137),    # ragged rows, ragged last tile
+    (2, 2, 777, 128, torch.bfloat16, 64),      # exactly one tile, batch 2
+    (1, 2, 777, 128, torch.bfloat16, 65),      # one column in the last tile
+    (1, 1, 300, 128, torch.bfloat16, 1),       # one kept column
+    (1, 2, 520, 128, torch.bfloat16, 520),     # keep everything
+    (1, 9, 260, 128, torch.bfloat16, 100),     # more heads than XCDs, not a multiple of 8
+    (1, 2, 600, 64, torch.bfloat16, 200),      # head_dim 64
+    (1, 2, 333, 128, torch.float32, 77),       # fp32 mode, head_dim 128, ragged
+    (1, 1, 130, 64, torch.float32, 33),
+]
+
+
+@pytest.mark.parametrize("B,H,n,d,dtype,k", ATTN_CASES)
+def test_sparse_attention_matches_oracle(B, H, n, d, dtype, k):
+    say(f"attn case B={B} H={H} n={n} d={d} {dtype} k={k}")
+    Q, K, V = rand_qkv(B, H, n, d, dtype, seed=1000 + n + k)
+    idx = random_idx(n, k, B * H, seed=n * 7 + k).view(B, H, 1, k)
+    with pc.Context(B, H, n, d, dtype) as ctx:
+        O = ctx.attn(Q.to(DEV), K.to(DEV), V.to(DEV), idx.to(DEV))
+        torch.cuda.synchronize()
+    for b in range(B):
+        for h in range(H):
+            want = oracle.sparse_attention_masked(f64(Q[b, h]), f64(K[b, h]), f64(V[b, h]), idx[b, h].numpy())
+            assert_close(O[b, h], want, kind_of(dtype), f"attn b{b} h{h}")
+
+
+@pytest.mark.parametrize("B,H,n,d,dtype", [
+    (1, 2, 256, 64, torch.float32), (1, 3, 1000, 128, torch.bfloat16), (2, 1, 257, 128, torch.bfloat16),
+    (1, 2, 500, 64, torch.bfloat16), (1, 2, 333, 128, torch.float32)])
+def test_dense_attention_and_lse_match_oracle(B, H, n, d, dtype):
+    say(f"dense case B={B} H={H} n={n} d={d} {dtype}")
+    Q, K, V = rand_qkv(B, H, n, d, dtype, seed=2000 + n)
+    with pc.Context(B, H, n, d, dtype) as ctx:
+        lse = torch.empty(B, H, n, dtype=torch.float32, device=DEV)
+        O = ctx.attn_dense(Q.to(DEV), K.to(DEV), V.to(DEV), lse_out=lse)
+        torch.cuda.synchronize()
+    for b in range(B):
+        for h in range(H):
+            q, k_, v = f64(Q[b, h]), f64(K[b, h]), f64(V[b, h])
+            assert_close(O[b, h], oracle.dense_attention(q, k_, v), kind_of(dtype), f"dense b{b} h{h}")
+            Z = oracle.attention_logits(q, k_)
+            m = Z.max(axis=1)
+            want_lse = m + np.log(np.exp(Z - m[:, None]).sum(axis=1))
+            np.testing.assert_allclose(f64(lse[b, h]), want_lse, rtol=0, atol=2e-5 * max(1.0, np.abs(want_lse).max()))
+
+
+def test_keep_everything_equals_dense_on_gpu_and_oracle():
+    B, H, n, d = 1, 2, 640, 128
+    say("keep=1 case")
+    Q, K, V = rand_qkv(B, H, n, d, torch.bfloat16, seed=31)
+    every = torch.arange(n, dtype=torch.int32).repeat(B, H, 1, 1)
+    with pc.Context(B, H, n, d, torch.bfloat16) as ctx:
+        q, k_, v = Q.to(DEV), K.to(DEV), V.to(DEV)
+        Os = ctx.attn(q, k_, v, every.to(DEV))
+        Od = ctx.attn_dense(q, k_, v)
+        torch.cuda.synchronize()
+    assert torch.equal(Os, Od)      # same tiles in the same order: bit-identical
+    for h in range(H):
+        assert_close(Os[0, h], oracle.dense_attention(f64(Q[0, h]), f64(K[0, h]), f64(V[0, h])), "bf16", "keep=1")
+
+
+def test_column_order_and_repeats():
+    B, H, n, d, k = 1, 2, 512, 128, 150
+    say("column-order case")
+    Q, K, V = rand_qkv(B, H, n, d, torch.bfloat16, seed=41)
+    idx = random_idx(n, k, B * H, seed=42).view(B, H, 1, k)
+    shuffled = random_idx(n, k, B * H, seed=42, sort=False).view(B, H, 1, k)
+    assert torch.equal(torch.sort(shuffled, dim=-1).values, idx)
+    with pc.Context(B, H, n, d, torch.bfloat16) as ctx:
+        q, k_, v = Q.to(DEV), K.to(DEV), V.to(DEV)
+        O1 = ctx.attn(q, k_, v, idx.to(DEV))
+        O2 = ctx.attn(q, k_, v, shuffled.to(DEV))
+        O1b = ctx.attn(q, k_, v, idx.to(DEV))
+        # a repeated column counts twice (appendix listing semantics)
+        rep = torch.tensor([5, 5, 9], dtype=torch.int32).repeat(B, H, 1, 1)
+        O3 = ctx.attn(q, k_, v, rep.to(DEV))
+        torch.cuda.synchronize()
+    assert torch.equal(O1, O1b)                                        # run-to-run determinism
+    assert (O1.float() - O2.float()).abs().max().item() <= TOL["bf16"]["max_abs"]
+    for h in range(H):
+        want = oracle.sparse_attention_masked(f64(Q[0, h]), f64(K[0, h]), f64(V[0, h]), idx[0, h].numpy())
+        assert_close(O2[0, h], want, "bf16", "shuffled idx")
+        want3 = oracle.sparse_attention_tiled(f64(Q[0, h]), f64(K[0, h]), f64(V[0, h]), [[5, 5, 9]], 64, 2)
+        assert_close(O3[0, h], want3, "bf16", "repeated idx")
+
+
+def test_ones_value_gives_ones_and_single_column_copies_value():
+    B, H, n, d = 1, 2, 384, 128
+    say("V==1 / k==1 case")
+    Q, K, V = rand_qkv(B, H, n, d, torch.bfloat16, seed=51)
+    idx = random_idx(n, 99, B * H, seed=52).view(B, H, 1, 99)
+    one = torch.tensor([123], dtype=torch.int32).repeat(B, H, 1, 1)
+    with pc.Context(B, H, n, d, torch.bfloat16) as ctx:
+        O = ctx.attn(Q.to(DEV), K.to(DEV), torch.ones_like(V).to(DEV), idx.to(DEV))
+        O1 = ctx.attn(Q.to(DEV), K.to(DEV), V.to(DEV), one.to(DEV))
+        torch.cuda.synchronize()
+    assert (O.float() - 1.0).abs().max().item() <= 1e-2
+    assert torch.equal(O1.cpu(), V[:, :, 123:124, :].expand(B, H, n, d))   # weight exactly 1.0
+
+
+def test_strided_layout():
+    """Tensors stored [B, n, H, d] (the projection's natural output) viewed as [B, H, n, d]."""
+    B, H, n, d, k = 1, 4, 300, 128, 70
+    say("strided case")
+    Q, K, V = rand_qkv(B, H, n, d, torch.bfloat16, seed=61)
+    idx = random_idx(n, k, B * H, seed=62).view(B, H, 1, k)
+
+    def strided(t):
+        return t.to(DEV).permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+
+    q, k_, v = strided(Q), strided(K), strided(V)
+    strides = (n * H * d, d, H * d)
+    with pc.Context(B, H, n, d, torch.bfloat16, strides=strides) as ctx:
+        O = torch.empty(B, n, H, d, dtype=torch.bfloat16, device=DEV).permute(0, 2, 1, 3)
+        ctx.attn(q, k_, v, idx.to(DEV), O=O)
+        sc = ctx.scores(q, k_)
+        torch.cuda.synchronize()
+    with pc.Context(B, H, n, d, torch.bfloat16) as ctx2:
+        O_packed = ctx2.attn(Q.to(DEV), K.to(DEV), V.to(DEV), idx.to(DEV))
+        sc_packed = ctx2.scores(Q.to(DEV), K.to(DEV))
+        torch.cuda.synchronize()
+    assert torch.equal(O.contiguous(), O_packed)
+    assert torch.equal(sc, sc_packed)
+
+
+# ---------------------------------------------------------------------------------------
+# identification pass: scores, top-k, select
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("B,H,n,d,dtype", [
+    (1, 2, 256, 64, torch.float32), (1, 3, 1000, 128, torch.bfloat16), (2, 2, 515, 128, torch.bfloat16),
+    (1, 2, 700, 64, torch.bfloat16), (1, 2, 333, 128, torch.float32)])
+def test_scores_match_oracle(B, H, n, d, dtype):
+    say(f"scores case B={B} H={H} n={n} d={d} {dtype}")
+    Q, K, _ = rand_qkv(B, H, n, d, dtype, seed=3000 + n)
+    K[:, :, ::17] *= 2.5
+    with pc.Context(B, H, n, d, dtype) as ctx:
+        s1 = ctx.scores(Q.to(DEV), K.to(DEV))
+        s2 = ctx.scores(Q.to(DEV), K.to(DEV))
+        torch.cuda.synchronize()
+    assert torch.equal(s1, s2)                                          # fixed summation order
+    assert s1.shape == (B, H, 1, n)
+    for b in range(B):
+        for h in range(H):
+            want = oracle.column_scores(f64(Q[b, h]), f64(K[b, h]))[0]
+            got = f64(s1[b, h, 0])
+            assert abs(got.sum() - 1.0) < 1e-5
+            rel = np.abs(got - want) / want
+            assert rel.max() < 2e-5, f"scores b{b} h{h}: worst relative error {rel.max():.3e}"
+
+
+@pytest.mark.parametrize("rows,n,k,ties", [
+    (2, 256, 64, False), (3, 1000, 137, False), (4, 5000, 1, False), (2, 5000, 5000, False),
+    (3, 4096, 409, True), (2, 1023, 500, True), (1, 65536, 6553, False), (1, 65536, 6553, True),
+    (2, 70001, 7000, True)])
+def test_topk_is_bit_exact_on_identical_scores(rows, n, k, ties):
+    say(f"topk case rows={rows} n={n} k={k} ties={ties}")
+    s = wl.random_scores(rows, n, seed=n + k, ties=ties)
+    with pc.Context(1, rows, n, 128, torch.bfloat16) as ctx:
+        idx = ctx.topk(s.view(1, rows, 1, n).to(DEV), k)
+        torch.cuda.synchronize()
+    want = oracle.topk_columns(f64(s), k)
+    assert np.array_equal(idx.cpu().numpy().reshape(rows, k), want)
+
+
+def test_topk_degenerate_rows():
+    n = 3000
+    say("topk degenerate rows")
+    s = torch.zeros(3, n)
+    s[0] = 0.125                                   # all equal -> lowest indices
+    s[1, 100:110] = 1.0                            # k larger than the number of non-zeros
+    s[2] = torch.arange(n, dtype=torch.float32)    # strictly increasing -> the last k
+    with pc.Context(1, 3, n, 128, torch.bfloat16) as ctx:
+        idx = ctx.topk(s.view(1, 3, 1, n).to(DEV), 25).cpu().numpy().reshape(3, 25)
+    assert np.array_equal(idx, oracle.topk_columns(f64(s), 25))
+    assert idx[0].tolist() == list(range(25))
+    assert idx[1].tolist() == list(range(15)) + list(range(100, 110))
+    assert idx[2].tolist() == list(range(n - 25, n))
+
+
+def test_tiny_workload_select_then_attn():
+    w = wl.WORKLOADS["tiny"]
+    say("tiny workload")
+    Q, K, V = wl.make_qkv(w)
+    keep = w.keep_ratios[0]
+    with pc.Context(w.batch, w.heads, w.seq, w.head_dim, w.torch_dtype) as ctx:
+        q, k_, v = Q.to(DEV), K.to(DEV), V.to(DEV)
+        idx = ctx.select(q, k_, keep)
+        idx_again = ctx.select(None, None, keep, refresh=False)
+        torch.cuda.synchronize()
+        assert torch.equal(idx, idx_again)
+        k = oracle.num_keep(w.seq, keep)
+        assert idx.shape == (1, w.heads, 1, k)
+        for h in range(w.heads):
+            s64 = oracle.column_scores(f64(Q[0, h]), f64(K[0, h]))[0]
+            assert_idx_matches(idx[0, h, 0].cpu().numpy(), s64, k, f"tiny head {h}")
+            assert set(wl.heavy_columns(w, 0, h).tolist()) <= set(idx[0, h, 0].tolist())
+        # attention through the ORACLE's column sets (no oracle input comes from the GPU)
+        oidx = np.stack([oracle.select_columns(f64(Q[0, h]), f64(K[0, h]), keep) for h in range(w.heads)])
+        O = ctx.attn(q, k_, v, torch.from_numpy(oidx).to(torch.int32).view(1, w.heads, 1, k).to(DEV))
+        torch.cuda.synchronize()
+    for h in range(w.heads):
+        want = oracle.sparse_attention_masked(f64(Q[0, h]), f64(K[0, h]), f64(V[0, h]), oidx[h])
+        assert_close(O[0, h], want, "f32", f"tiny attn head {h}")
+
+
+@pytest.mark.parametrize("n,d,dtype,keep", [(1200, 128, torch.bfloat16, 0.1), (900, 64, torch.bfloat16, 0.3),
+                                            (500, 128, torch.float32, 0.2)])
+def test_select_near_tie_rule(n, d, dtype, keep):
+    B, H = 1, 4
+    say(f"select case n={n} d={d} {dtype} keep={keep}")
+    Q, K, _ = rand_qkv(B, H, n, d, dtype, seed=4000 + n)
+    K[:, :, 5::13] *= 2.5
+    with pc.Context(B, H, n, d, dtype) as ctx:
+        idx = ctx.select(Q.to(DEV), K.to(DEV), keep)
+        torch.cuda.synchronize()
+    k = oracle.num_keep(n, keep)
+    for h in range(H):
+        s64 = oracle.column_scores(f64(Q[0, h]), f64(K[0, h]))[0]
+        assert_idx_matches(idx[0, h, 0].cpu().numpy(), s64, k, f"select head {h}")
+
+
+# ---------------------------------------------------------------------------------------
+# error paths that need a live context
+# ---------------------------------------------------------------------------------------
+def test_error_paths_on_device():
+    say("error paths")
+    B, H, n, d = 1, 2, 256, 128
+    Q, K, V = (t.to(DEV) for t in rand_qkv(B, H, n, d, torch.bfloat16, seed=71))
+    idx = random_idx(n, 32, B * H, seed=72).view(B, H, 1, 32).to(DEV)
+    with pc.Context(B, H, n, d, torch.bfloat16) as ctx:
+        with pytest.raises(pc.PulseColError) as e:
+            ctx.select(None, None, 0.1, refresh=False)
+        assert e.value.status == pc.ERR_NO_PATTERN
+        ctx.select(Q, K, 0.1)
+        with pytest.raises(pc.PulseColError) as e:
+            ctx.select(None, None, 0.2, refresh=False)          # cached k differs
+        assert e.value.status == pc.ERR_NO_PATTERN
+        with pytest.raises(pc.PulseColError) as e:
+            ctx.select(Q, K, 1.5)
+        assert e.value.status == pc.ERR_INVALID_ARG
+        L = pc.lib()
+        st = L.pulsecol_attn(ctx._h, Q.data_ptr() + 2, K.data_ptr(), V.data_ptr(), idx.data_ptr(), 32, Q.data_ptr(), None)
+        assert st == pc.ERR_ALIGNMENT
+        st = L.pulsecol_attn(ctx._h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), idx.data_ptr(), n + 1, Q.data_ptr(), None)
+        assert st == pc.ERR_INVALID_ARG
+        st = L.pulsecol_attn(ctx._h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), None, 32, Q.data_ptr(), None)
+        assert st == pc.ERR_INVALID_ARG
+        assert "idx" in pc.last_error(ctx._h)
+        st = L.pulsecol_topk(ctx._h, None, 3, idx.data_ptr(), None)
+        assert st == pc.ERR_INVALID_ARG
+        # the context still works after failures
+        O = ctx.attn(Q, K, V, idx)
+        torch.cuda.synchronize()
+        assert torch.isfinite(O.float()).all()
+    with pytest.raises(pc.PulseColError):
+        pc.Context(1, 2, 256, 128, torch.bfloat16, device=99)
