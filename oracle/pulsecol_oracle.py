@@ -97,11 +97,12 @@ def _groups(n: int, group_size: int):
 
 
 def column_scores(Q, K, group_size: int = 0, scale: float | None = None,
-                  row_chunk: int = 2048) -> np.ndarray:
+                  row_chunk: int = 2048, progress=None) -> np.ndarray:
     """s[u, j] = (1/|G_u|) sum_{i in G_u} P[i, j],  P = row softmax of the FULL logits.
 
     Sec. 3.3, group-wise column-sparse pattern estimation (score equation).
-    Returns float64 ``[U, n]``.
+    Returns float64 ``[U, n]``.  ``progress`` (optional) is called with the number of query
+    rows done after each slab, so that long runs can report that they are alive.
     """
     Q = _as_f64(Q)
     K = _as_f64(K)
@@ -113,6 +114,8 @@ def column_scores(Q, K, group_size: int = 0, scale: float | None = None,
             r1 = min(hi, r0 + row_chunk)
             P = row_softmax(attention_logits(Q[r0:r1], K, scale))
             s[u] += P.sum(axis=0)
+            if progress is not None:
+                progress(r1)
         s[u] /= (hi - lo)
     return s
 
