@@ -4,21 +4,30 @@
 // row normalisers before column masses can be summed).
 //
 // One workgroup = 256 query rows (4 waves x 64 rows), one tile = 64 K/V rows, processed as
-// two half-tiles of 32.  Q stays in registers as the MFMA B operand for the whole kernel.
-// K and V rows are gathered straight into LDS (global_load_lds_dwordx4: 16 lanes cover one
-// 256-byte row, the XOR swizzle is applied on the global side) into three tile slots per
-// operand, and read back as MFMA A operands (V through the transposing LDS read).  Every
-// lane owns one query column of S^T / O^T, so the online-softmax state is two scalars per
-// lane and query block.  P is rounded to bf16 only as the MFMA operand; l is summed from the
-// fp32 P.  The output accumulator lives in the AGPR half of the register file.
+// two half-tiles of 32.  Q stays in registers (AGPRs) as the MFMA B operand for the whole
+// kernel.  K and V rows are gathered straight into LDS (global_load_lds_dwordx4: 16 lanes
+// cover one 256-byte row, the XOR swizzle is applied on the global side) into three tile
+// slots per operand, and read back as MFMA A operands (V through the transposing LDS read).
+// Every lane owns one query column of S^T / O^T, so the online-softmax state is two scalars
+// per lane and query block.  P is rounded to bf16 only as the MFMA operand; l is summed from
+// the fp32 P.  The output accumulator lives in AGPRs and is touched by the matrix pipe only.
 //
 // Software pipeline (one wave per SIMD, so overlap has to come from the instruction
 // stream): half-step j issues the MFMAs of  S(j+1) = K(j+1) Q^T  and  O += V(j-1) P(j-1)
-// while the VALU turns S(j) into P(j).  The three are independent, so the matrix pipe and
-// the vector ALU run side by side.  The reference maximum is raised lazily: a half-tile whose
-// maximum stays within 2^kTau of the reference keeps it (exact: numerator and denominator
-// carry the same factor), so the 128 accumulator registers are rescaled only on rare steps,
-// and then by an exact power of two.
+// while the VALU turns S(j) into P(j).  The half-step is written as a sequence of slots, one
+// MFMA each, fenced so that the compiler keeps the hand-made interleaving: every slot issues
+// its MFMA, then a few VALU operations of the exp / row-max work, and every second slot the
+// LDS read of a fragment needed three MFMA pairs later.  The reference maximum is raised
+// lazily: a half-tile whose maximum stays within 2^kTau of the reference keeps it (exact:
+// numerator and denominator carry the same factor), so the accumulator is rescaled only on
+// rare steps, and then by an exact power of two.
+//
+// The MFMAs are inline assembly (to pin operands to AGPRs), so the compiler does not know
+// their latency: every place where the VALU reads an MFMA result is either separated from
+// the producer by several later MFMAs of the same in-order stream or preceded by
+// mfma_settle().
+#include <utility>
+
 #include "pulsecol_device.h"
 #include "pulsecol_kernels.h"
 
@@ -29,9 +38,75 @@ constexpr int BM = kBlockM_bf16;
 constexpr int BN = kBlockN_bf16;
 constexpr int NTHREADS = 256;
 constexpr int NBUF = 3;            // LDS tile slots per operand
+constexpr int AHEAD = 3;           // fragment reads run this many MFMA pairs ahead of their use
 constexpr float kTau = 8.0f;       // log2 of the growth allowed before the reference max is raised
 
 typedef unsigned char byte;
+
+__device__ __forceinline__ void fence() { __builtin_amdgcn_sched_barrier(0); }
+
+// S = a * q (fresh accumulator) and S += a * q, with q held in AGPRs
+__device__ __forceinline__ void mfma_qk_first(f32x16& s, bf16x8 a, bf16x8 q) {
+    asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "v"(a), "a"(q));
+}
+__device__ __forceinline__ void mfma_qk(f32x16& s, bf16x8 a, bf16x8 q) {
+    asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(a), "a"(q));
+}
+// O += a * p with O held in AGPRs
+__device__ __forceinline__ void mfma_pv(f32x16& o, bf16x8 a, bf16x8 p) {
+    asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(o) : "v"(a), "v"(p));
+}
+// Waits out the write-back of every matrix instruction issued so far (the longest
+// MFMA-result-to-VALU hazard on gfx950 is 18 wait states).  The values the VALU is about to
+// read are routed through the statement so that no use of them can be placed before it.
+__device__ __forceinline__ void mfma_settle(f32x16& s0, f32x16& s1) {
+    asm volatile("s_nop 15\n\ts_nop 15" : "+v"(s0), "+v"(s1));
+}
+template <int N>
+__device__ __forceinline__ void mfma_settle_acc(f32x16 (&o)[2][N]) {
+    static_assert(N == 1 || N == 2 || N == 4, "accumulator blocks");
+    if constexpr (N == 4)
+        asm volatile("s_nop 15\n\ts_nop 15" : "+a"(o[0][0]), "+a"(o[0][1]), "+a"(o[0][2]), "+a"(o[0][3]),
+                                               "+a"(o[1][0]), "+a"(o[1][1]), "+a"(o[1][2]), "+a"(o[1][3]));
+    else if constexpr (N == 2)
+        asm volatile("s_nop 15\n\ts_nop 15" : "+a"(o[0][0]), "+a"(o[0][1]), "+a"(o[1][0]), "+a"(o[1][1]));
+    else
+        asm volatile("s_nop 15\n\ts_nop 15" : "+a"(o[0][0]), "+a"(o[1][0]));
+}
+// Order-only statements: the compiler's instruction selection places pure arithmetic wherever
+// its dependencies allow; routing a value through an empty volatile statement ties the
+// arithmetic that produces it (and everything that consumes it) to this point of the slot
+// sequence.
+__device__ __forceinline__ void pin(float& a) { asm volatile("" : "+v"(a)); }
+__device__ __forceinline__ void pin(float& a, float& b) { asm volatile("" : "+v"(a), "+v"(b)); }
+__device__ __forceinline__ void pin(bf16x8& a) { asm volatile("" : "+v"(a)); }
+__device__ __forceinline__ void pin(f32x16& a, f32x16& b) { asm volatile("" : "+v"(a), "+v"(b)); }
+
+// LDS fragment reads of the scheduled half-step, as inline assembly with hand-placed waits.
+// (The compiler's own wait-count insertion drains lgkmcnt to zero whenever a direct-to-LDS
+// load is in flight; LDS returns data in order, so "all but the N newest reads" is exact.)
+template <int OFF>
+__device__ __forceinline__ bf16x8 lds_read_b128_at(uint32_t addr) {
+    bf16x8 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+template <int OFF0, int OFF1>
+__device__ __forceinline__ bf16x8 lds_read_tr_pair_at(uint32_t addr) {
+    bf16x4 lo, hi;
+    asm volatile("ds_read_b64_tr_b16 %0, %2 offset:%3\n\tds_read_b64_tr_b16 %1, %2 offset:%4"
+                 : "=&v"(lo), "=&v"(hi) : "v"(addr), "n"(OFF0), "n"(OFF1));
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+template <int N>
+__device__ __forceinline__ void lds_wait_all_but(bf16x8& frag) {
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(frag) : "n"(N));
+}
+__device__ __forceinline__ uint32_t lds_address(const void* generic_lds_ptr) {
+    return (uint32_t)(uintptr_t)(PULSECOL_LDS const void*)generic_lds_ptr;
+}
+
+constexpr int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 template <int D, int MODE>
 struct AttnWave {
@@ -40,11 +115,23 @@ struct AttnWave {
     static constexpr int DB = D / 32;                    // 32-wide blocks of the head dimension
     static constexpr int ROW_BYTES = D * 2;
     static constexpr int TILE_BYTES = BN * ROW_BYTES;
+    static constexpr int HALF_BYTES = 32 * ROW_BYTES;
     static constexpr int ROWS_PER_CHUNK = 64 / PIECES;   // one direct-to-LDS load instruction moves 64 x 16 bytes
     static constexpr int CH = BN / ROWS_PER_CHUNK / 4;   // such instructions per wave and tile (per operand)
     static constexpr bool HAS_V = (MODE != kLseOnly);
     static constexpr bool GATHER = (MODE == kSparse);
     static constexpr int ODB = HAS_V ? DB : 1;
+    static constexpr int NPV = HAS_V ? 2 * DB : 0;       // V fragments (= MFMA pairs) of a half-step
+    static constexpr int NP = KK + NPV;                  // MFMA pairs of a half-step
+    static constexpr int NS = 2 * NP;                    // MFMA slots of a half-step
+    static constexpr int EXP_TICKS = 34;                 // 32 values through a 3-stage pipeline
+    static constexpr int MAX_TICKS = 20;
+    static constexpr int MAX_SLOT0 = 2 * KK + 3;         // first slot whose VALU work may read S_out
+    // exp / max ticks finished before slot s (slot NS = end of the half-step)
+    static constexpr int exp_ticks_before(int s) { return ceil_div(EXP_TICKS * s, NS); }
+    static constexpr int max_ticks_before(int s) {
+        return s <= MAX_SLOT0 ? 0 : ceil_div(MAX_TICKS * (s - MAX_SLOT0), NS - MAX_SLOT0);
+    }
     // direct-to-LDS loads per steady-state issue point (the row-number loads are issued before
     // them, so "all but the newest VM_PER_ISSUE" covers every load of earlier iterations)
     static constexpr int VM_PER_ISSUE = CH + (HAS_V ? CH : 0);
@@ -54,19 +141,46 @@ struct AttnWave {
     // problem
     int n, ns, ntiles, nhalf;
     bool ragged;
-    int64_t sn;
-    const __bf16* K;
-    const __bf16* V;
-    const int32_t* idx;
+    uint32_t row_bytes;   // byte stride between sequence positions of K / V in global memory
+    const byte* K;
+    const byte* V;
+    const byte* idx;      // int32 column numbers of this head
     // registers that live across the whole kernel
-    bf16x8 qf[2][KK];
-    f32x16 o_acc[2][ODB];
+    bf16x8 qf[2][KK];     // AGPRs
+    f32x16 o_acc[2][ODB]; // AGPRs
     float c2;
     float mc[2];          // reference maximum in log2 units (raw maximum * c2), equal in both half-waves
     float l_run[2];       // per-lane partial row sum (this lane's keys only)
     float mx_next[2];     // raw maximum of the half-tile whose S is in flight
-    int koff[CH], voff[CH];
+    uint32_t koff[CH], voff[CH];   // global byte offset of this lane's piece inside a row, per load instruction
+    uint32_t kaddr[KK];   // LDS byte offset (inside a tile slot, first half) of this lane's K fragment kk
+    uint32_t vaddr[ODB];  // same for the first 4-row group of the V fragment of d-block db
     int lrow;
+
+    __device__ __forceinline__ void init_addresses() {
+        lrow = lane / PIECES;
+        const int lslot = lane % PIECES;
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int row = (wave * CH + i) * ROWS_PER_CHUNK + lrow;
+            koff[i] = (uint32_t)(lslot ^ swizzle_k<PIECES>(row)) * 16u;
+            voff[i] = (uint32_t)(lslot ^ swizzle_v<PIECES>(row)) * 16u;
+        }
+        // K fragment kk: tile row lq (+32 for the second half), piece 2*kk + lh
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk)
+            kaddr[kk] = (uint32_t)(lq * ROW_BYTES + (((2 * kk + lh) ^ swizzle_k<PIECES>(lq)) << 4));
+        // V fragment: contraction element e of a lane <-> tile row half*32 + hf*16 + 8*(e/4) + 4*lh + e%4.
+        // The transposing read takes the address of row 4*lh + j16/4 (and +8), 8 bytes at
+        // d = db*32 + 16*((lane/16)&1) + 4*(j16%4), j16 = lane%16.
+        const int j16 = lane & 15;
+        const int row0 = 4 * lh + (j16 >> 2);
+        const int colpiece = ((lane >> 4) & 1) * 2 + ((j16 & 3) >> 1);
+        const int inpiece = (j16 & 1) * 8;
+#pragma unroll
+        for (int db = 0; db < ODB; ++db)
+            vaddr[db] = (uint32_t)(row0 * ROW_BYTES + inpiece + (((db * 4 + colpiece) ^ swizzle_v<PIECES>(row0)) << 4));
+    }
 
     // ------------------------------------------------------------------ gathers
     __device__ __forceinline__ void load_rows(int t, int (&dst)[CH]) const {
@@ -75,7 +189,7 @@ struct AttnWave {
         for (int i = 0; i < CH; ++i) {
             int pos = t * BN + (wave * CH + i) * ROWS_PER_CHUNK + lrow;
             pos = pos < ns ? pos : ns - 1;        // ragged tail: any valid row; masked later
-            dst[i] = GATHER ? idx[pos] : pos;
+            dst[i] = GATHER ? *(const int*)(idx + (uint32_t)pos * 4u) : pos;
         }
     }
     // Load instruction i of a wave fills the 1 KB chunk cid = wave*CH + i of a tile slot: lane L
@@ -84,61 +198,33 @@ struct AttnWave {
     // (Every pointer is a restrict parameter so that the loads carry alias scopes: the compiler
     // then knows that LDS reads of other slots need not wait for these loads.)
     __device__ __forceinline__ void issue_tile(byte* __restrict__ kslot, byte* __restrict__ vslot,
-                                               const __bf16* __restrict__ Kg, const __bf16* __restrict__ Vg,
+                                               const byte* __restrict__ Kg, const byte* __restrict__ Vg,
                                                const int (&krows)[CH], const int (&vrows)[CH]) const {
 #pragma unroll
         for (int i = 0; i < CH; ++i)
             __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(Kg + (int64_t)krows[i] * sn + koff[i]),
+                (const __attribute__((address_space(1))) void*)(Kg + ((uint32_t)krows[i] * row_bytes + koff[i])),
                 (PULSECOL_LDS void*)(kslot + (wave * CH + i) * 1024), 16, 0, 0);
         if (HAS_V) {
 #pragma unroll
             for (int i = 0; i < CH; ++i)
                 __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void*)(Vg + (int64_t)vrows[i] * sn + voff[i]),
+                    (const __attribute__((address_space(1))) void*)(Vg + ((uint32_t)vrows[i] * row_bytes + voff[i])),
                     (PULSECOL_LDS void*)(vslot + (wave * CH + i) * 1024), 16, 0, 0);
         }
     }
 
-    // ------------------------------------------------------------------ matrix steps
-    // S[qb] = K(half) Q^T for both query blocks; each K fragment read feeds two MFMAs.
-    __device__ __forceinline__ void qk(const byte* __restrict__ kslot, int half, f32x16 (&S)[2]) const {
-        const int row = half * 32 + lq;
-        const byte* rowp = kslot + row * ROW_BYTES;
-        const int sw = swizzle_k<PIECES>(row);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { S[0][r] = 0.f; S[1][r] = 0.f; }
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-            const bf16x8 a = *(const bf16x8*)(rowp + (((2 * kk + lh) ^ sw) << 4));
-            S[0] = mfma_bf16(a, qf[0][kk], S[0]);
-            S[1] = mfma_bf16(a, qf[1][kk], S[1]);
-        }
+    // ------------------------------------------------------------------ fragment reads
+    __device__ __forceinline__ bf16x8 read_k(const byte* __restrict__ kslot, int half, int kk) const {
+        return *(const bf16x8*)(kslot + half * HALF_BYTES + kaddr[kk]);
     }
-    // O^T += V(half)^T P^T.  Contraction element e of a lane <-> tile row half*32 + hf*16 + 8*(e/4) + 4*lh + e%4.
-    __device__ __forceinline__ void pv(const byte* __restrict__ vslot, int half, const bf16x8 (&P)[2][2]) {
-        if (HAS_V) {
-            const int j16 = lane & 15;
-            const int colpiece = ((lane >> 4) & 1) * 2 + ((j16 & 3) >> 1);   // 16-byte piece inside a 64-byte d-block
-            const int inpiece = (j16 & 1) * 8;                               // byte inside the piece
-#pragma unroll
-            for (int hf = 0; hf < 2; ++hf) {
-                const int row0 = half * 32 + hf * 16 + 4 * lh + (j16 >> 2);
-                const int row1 = row0 + 8;
-                const byte* r0p = vslot + row0 * ROW_BYTES + inpiece;
-                const byte* r1p = vslot + row1 * ROW_BYTES + inpiece;
-                const int sw0 = swizzle_v<PIECES>(row0), sw1 = swizzle_v<PIECES>(row1);
-#pragma unroll
-                for (int db = 0; db < ODB; ++db) {
-                    const int piece = db * 4 + colpiece;
-                    const bf16x4 lo = lds_read_tr(r0p + ((piece ^ sw0) << 4));
-                    const bf16x4 hi = lds_read_tr(r1p + ((piece ^ sw1) << 4));
-                    const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    mfma_bf16_agpr(o_acc[0][db], a, P[0][hf]);
-                    mfma_bf16_agpr(o_acc[1][db], a, P[1][hf]);
-                }
-            }
-        }
+    // V fragment q of a half-step: rows hf*16 .. +15 of the half-tile, d-block db; q = hf*ODB + db
+    __device__ __forceinline__ bf16x8 read_v(const byte* __restrict__ vslot, int half, int q) const {
+        const int hf = q / ODB, db = q % ODB;
+        const byte* p = vslot + half * HALF_BYTES + hf * 16 * ROW_BYTES + vaddr[db];
+        const bf16x4 lo = lds_read_tr(p);
+        const bf16x4 hi = lds_read_tr(p + 8 * ROW_BYTES);
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     }
 
     // ------------------------------------------------------------------ softmax pieces
@@ -151,43 +237,76 @@ struct AttnWave {
                 if (acc_row(r, lh) >= valid) { S[0][r] = -INFINITY; S[1][r] = -INFINITY; }
         }
     }
+    // Row maximum of a half-tile in MAX_TICKS small steps (10 per query block) that can be
+    // spread over MFMA slots.
+    __device__ __forceinline__ void max_tick(int i, const f32x16 (&S)[2], float (&a)[4]) {
+        const int qb = i / 10;
+        const f32x16& s = S[qb];
+        switch (i % 10) {
+            case 0: a[0] = fmaxf(fmaxf(s[0], s[1]), s[2]); break;
+            case 1: a[1] = fmaxf(fmaxf(s[3], s[4]), s[5]); break;
+            case 2: a[2] = fmaxf(fmaxf(s[6], s[7]), s[8]); break;
+            case 3: a[3] = fmaxf(fmaxf(s[9], s[10]), s[11]); break;
+            case 4: a[0] = fmaxf(fmaxf(a[0], s[12]), s[13]); break;
+            case 5: a[1] = fmaxf(fmaxf(a[1], s[14]), s[15]); break;
+            case 6: a[0] = fmaxf(a[0], a[1]); break;
+            case 7: a[2] = fmaxf(a[2], a[3]); break;
+            case 8: a[0] = fmaxf(a[0], a[2]); break;
+            default: mx_next[qb] = half_max(a[0]); pin(mx_next[qb]); break;
+        }
+        if (i % 10 < 9) pin(a[(i % 10) == 7 ? 2 : ((i % 10) < 4 ? i % 10 : ((i % 10) == 5 ? 1 : 0))]);
+    }
     __device__ __forceinline__ void half_tile_max(const f32x16 (&S)[2]) {
+        float a[4];
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-            float a0 = fmaxf(fmaxf(S[qb][0], S[qb][1]), S[qb][2]);
-            float a1 = fmaxf(fmaxf(S[qb][3], S[qb][4]), S[qb][5]);
-            float a2 = fmaxf(fmaxf(S[qb][6], S[qb][7]), S[qb][8]);
-            float a3 = fmaxf(fmaxf(S[qb][9], S[qb][10]), S[qb][11]);
-            a0 = fmaxf(fmaxf(a0, S[qb][12]), S[qb][13]);
-            a1 = fmaxf(fmaxf(a1, S[qb][14]), S[qb][15]);
-            mx_next[qb] = half_max(fmaxf(fmaxf(a0, a1), fmaxf(a2, a3)));
-        }
+        for (int i = 0; i < MAX_TICKS; ++i) max_tick(i, S, a);
     }
-    // P = exp2(S*c2 - mc) against the current reference; sums into l_run
-    __device__ __forceinline__ void exp_half_tile(const f32x16 (&S)[2], bf16x8 (&P)[2][2]) {
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-            const float ref = mc[qb];
-            float rs0 = 0.f, rs1 = 0.f;
-#pragma unroll
-            for (int r = 0; r < 16; r += 2) {
-                const float e0 = fast_exp2(__builtin_fmaf(S[qb][r], c2, -ref));
-                const float e1 = fast_exp2(__builtin_fmaf(S[qb][r + 1], c2, -ref));
-                rs0 += e0;
-                rs1 += e1;
-                P[qb][r >> 3][r & 7] = (__bf16)e0;
-                P[qb][r >> 3][(r & 7) + 1] = (__bf16)e1;
+    // P = exp2(S*c2 - mc) in EXP_TICKS small steps: tick i forms the scaled, shifted logit of
+    // value i, takes exp2 of value i-1, and adds value i-2 to the row sum (packing a bf16 pair
+    // after every odd value).  Value e = qb*16 + r.
+    struct ExpPipe { float t[32]; float x[32]; float rs[2][2]; };
+    __device__ __forceinline__ void exp_tick(int i, const f32x16 (&S)[2], bf16x8 (&P)[2][2], ExpPipe& ep) {
+        if (i < 32) {
+            ep.t[i] = __builtin_fmaf(S[i >> 4][i & 15], c2, -mc[i >> 4]);
+            pin(ep.t[i]);
+        }
+        if (i >= 1 && i <= 32) {
+            ep.x[i - 1] = fast_exp2(ep.t[i - 1]);
+            pin(ep.x[i - 1]);
+        }
+        if (i >= 2 && i <= 33) {
+            const int e = i - 2, qb = e >> 4, r = e & 15;
+            ep.rs[qb][r & 1] += ep.x[e];
+            pin(ep.rs[qb][r & 1]);
+            if (r & 1) {
+                P[qb][r >> 3][(r & 7) - 1] = (__bf16)ep.x[e - 1];
+                P[qb][r >> 3][r & 7] = (__bf16)ep.x[e];
+                pin(P[qb][r >> 3]);
             }
-            l_run[qb] += rs0 + rs1;
         }
     }
+    __device__ __forceinline__ void exp_begin(ExpPipe& ep) {
+        ep.rs[0][0] = ep.rs[0][1] = ep.rs[1][0] = ep.rs[1][1] = 0.f;
+    }
+    __device__ __forceinline__ void exp_end(const ExpPipe& ep) {
+        l_run[0] += ep.rs[0][0] + ep.rs[0][1];
+        l_run[1] += ep.rs[1][0] + ep.rs[1][1];
+    }
+    __device__ __forceinline__ void exp_half_tile(const f32x16 (&S)[2], bf16x8 (&P)[2][2]) {
+        ExpPipe ep;
+        exp_begin(ep);
+#pragma unroll
+        for (int i = 0; i < EXP_TICKS; ++i) exp_tick(i, S, P, ep);
+        exp_end(ep);
+    }
+
     // Raise the reference maximum where the incoming half-tile exceeds it by more than 2^kTau.
     // The reference moves by a whole number of log2 units, so the factor applied to l, to the
     // accumulator and to the pending P(j-1) is an exact power of two.
     __device__ __forceinline__ void raise_reference(bf16x8 (&P_pending)[2][2]) {
         const bool need = (mx_next[0] * c2 > mc[0] + kTau) || (mx_next[1] * c2 > mc[1] + kTau);
         if (__builtin_expect(__ballot(need) == 0ull, 1)) return;
-        if (HAS_V) mfma_agpr_settle();
+        if (HAS_V) mfma_settle_acc(o_acc);
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
             const float m2 = mx_next[qb] * c2;
@@ -213,42 +332,148 @@ struct AttnWave {
     }
 
     // ------------------------------------------------------------------ half-steps
+    // Plain (unscheduled) matrix steps, used by the general half-step.
+    __device__ __forceinline__ void qk_all(const byte* kslot, int half, f32x16 (&S)[2]) const {
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            const bf16x8 a = read_k(kslot, half, kk);
+            if (kk == 0) { mfma_qk_first(S[0], a, qf[0][kk]); mfma_qk_first(S[1], a, qf[1][kk]); }
+            else { mfma_qk(S[0], a, qf[0][kk]); mfma_qk(S[1], a, qf[1][kk]); }
+        }
+    }
+    __device__ __forceinline__ void pv_all(const byte* vslot, int half, const bf16x8 (&P)[2][2]) {
+        if (HAS_V) {
+#pragma unroll
+            for (int q = 0; q < NPV; ++q) {
+                const bf16x8 a = read_v(vslot, half, q);
+                mfma_pv(o_acc[0][q % ODB], a, P[0][q / ODB]);
+                mfma_pv(o_acc[1][q % ODB], a, P[1][q / ODB]);
+            }
+        }
+    }
+
+    // LDS operations that the read of fragment q of a scheduled half-step issues: one for a K
+    // fragment (q < KK, or q >= NP: the next half-step's first K fragments), two for a V fragment.
+    template <bool HAS_NEXT>
+    static constexpr int frag_ops(int q) { return q < KK ? 1 : (q < NP ? 2 : (HAS_NEXT ? 1 : 0)); }
+
     // Fast half-step j (1 <= j <= nhalf-4): S_in = S(j), P_in = P(j-1) -> S_out = S(j+1), P_out = P(j).
-    // qk, exp and pv are independent instruction streams inside one basic block.
-    __device__ __forceinline__ void fast_step(const byte* __restrict__ kslot, int khalf,
-                                              const byte* __restrict__ vslot, int vhalf,
+    // kv / vv are this lane's LDS addresses of the K fragments (tile slot of S(j+1), first
+    // half) and of the V fragments (tile slot of P(j-1), first half, first row group); KH / VH
+    // select the half.  kpre holds the first AHEAD K fragments, already requested; with
+    // HAS_NEXT it is refilled with requests for the following half-step (same K slot, half NKH).
+    template <int KH, int VH, bool HAS_NEXT, int NKH>
+    __device__ __forceinline__ void fast_step(const uint32_t (&kv)[KK], const uint32_t (&vv)[ODB],
+                                              bf16x8 (&kpre)[AHEAD],
                                               f32x16 (&S_in)[2], f32x16 (&S_out)[2],
                                               bf16x8 (&P_in)[2][2], bf16x8 (&P_out)[2][2]) {
         raise_reference(P_in);
-        qk(kslot, khalf, S_out);
-        exp_half_tile(S_in, P_out);
-        pv(vslot, vhalf, P_in);
-        half_tile_max(S_out);
+        bf16x8 fr[NP + AHEAD];
+#pragma unroll
+        for (int i = 0; i < AHEAD; ++i) fr[i] = kpre[i];
+        ExpPipe ep;
+        exp_begin(ep);
+        float mxa[4];
+        fence();
+        fast_pairs<KH, VH, HAS_NEXT, NKH>(std::make_integer_sequence<int, NP>{}, kv, vv, fr, ep, mxa,
+                                          S_in, S_out, P_in, P_out);
+        exp_end(ep);
+        if (!HAS_V) {           // no P V stream to hide behind: wait for S_out, then take its maximum
+            mfma_settle(S_out[0], S_out[1]);
+            half_tile_max(S_out);
+        }
+        if (HAS_NEXT) {
+#pragma unroll
+            for (int i = 0; i < AHEAD; ++i) kpre[i] = fr[NP + i];
+        }
+    }
+    template <int KH, int VH, bool HAS_NEXT, int NKH, int... Ps>
+    __device__ __forceinline__ void fast_pairs(std::integer_sequence<int, Ps...>,
+                                               const uint32_t (&kv)[KK], const uint32_t (&vv)[ODB],
+                                               bf16x8 (&fr)[NP + AHEAD], ExpPipe& ep, float (&mxa)[4],
+                                               f32x16 (&S_in)[2], f32x16 (&S_out)[2],
+                                               bf16x8 (&P_in)[2][2], bf16x8 (&P_out)[2][2]) {
+        (fast_pair<Ps, KH, VH, HAS_NEXT, NKH>(kv, vv, fr, ep, mxa, S_in, S_out, P_in, P_out), ...);
+    }
+    // MFMA pair P of a fast half-step: two slots that share one A fragment.
+    template <int P, int KH, int VH, bool HAS_NEXT, int NKH>
+    __device__ __forceinline__ void fast_pair(const uint32_t (&kv)[KK], const uint32_t (&vv)[ODB],
+                                              bf16x8 (&fr)[NP + AHEAD], ExpPipe& ep, float (&mxa)[4],
+                                              f32x16 (&S_in)[2], f32x16 (&S_out)[2],
+                                              bf16x8 (&P_in)[2][2], bf16x8 (&P_out)[2][2]) {
+        // request the fragment used AHEAD pairs later
+        constexpr int PA = P + AHEAD;
+        if constexpr (PA < KK) {
+            fr[PA] = lds_read_b128_at<KH * HALF_BYTES>(kv[PA]);
+        } else if constexpr (PA < NP) {
+            constexpr int q = PA - KK, hf = q / ODB, db = q % ODB;
+            fr[PA] = lds_read_tr_pair_at<VH * HALF_BYTES + hf * 16 * ROW_BYTES,
+                                         VH * HALF_BYTES + hf * 16 * ROW_BYTES + 8 * ROW_BYTES>(vv[db]);
+        } else if constexpr (HAS_NEXT) {
+            fr[PA] = lds_read_b128_at<NKH * HALF_BYTES>(kv[PA - NP]);
+        }
+        // fragment P has landed once only the requests made after it are outstanding
+        lds_wait_all_but<frag_ops<HAS_NEXT>(P + 1) + frag_ops<HAS_NEXT>(P + 2) + frag_ops<HAS_NEXT>(P + 3)>(fr[P]);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            const int s = 2 * P + qb;
+            if constexpr (P < KK) {
+                if constexpr (P == 0) mfma_qk_first(S_out[qb], fr[P], qf[qb][P]);
+                else mfma_qk(S_out[qb], fr[P], qf[qb][P]);
+            } else {
+                constexpr int q = P - KK;
+                mfma_pv(o_acc[qb][q % ODB], fr[P], P_in[qb][q / ODB]);
+            }
+            fence();
+            // this slot's share of the VALU work
+#pragma unroll
+            for (int i = exp_ticks_before(s); i < exp_ticks_before(s + 1); ++i) exp_tick(i, S_in, P_out, ep);
+            if (HAS_V) {
+                // from here on the VALU may read S_out: its last MFMA was issued >= 3 MFMAs ago
+                if (s == MAX_SLOT0) pin(S_out[0], S_out[1]);
+#pragma unroll
+                for (int i = max_ticks_before(s); i < max_ticks_before(s + 1); ++i) max_tick(i, S_out, mxa);
+            }
+            fence();
+        }
     }
     // General half-step (first step, last tile): same work, plus tail masking; no overlap needed.
     __device__ __forceinline__ void general_step(int j, const byte* kbase, const byte* vbase,
                                                  f32x16 (&S_in)[2], f32x16 (&S_out)[2],
                                                  bf16x8 (&P_in)[2][2], bf16x8 (&P_out)[2][2]) {
         raise_reference(P_in);
-        if (j >= 1) pv(vbase + (((j - 1) >> 1) % NBUF) * TILE_BYTES, (j - 1) & 1, P_in);
+        if (j >= 1) pv_all(vbase + (((j - 1) >> 1) % NBUF) * TILE_BYTES, (j - 1) & 1, P_in);
         exp_half_tile(S_in, P_out);
         if (j + 1 < nhalf) {
-            qk(kbase + (((j + 1) >> 1) % NBUF) * TILE_BYTES, (j + 1) & 1, S_out);
+            qk_all(kbase + (((j + 1) >> 1) % NBUF) * TILE_BYTES, (j + 1) & 1, S_out);
+            mfma_settle(S_out[0], S_out[1]);
             mask_tail(j + 1, S_out);
             half_tile_max(S_out);
         }
     }
     // One steady-state iteration u: issue K(u+3), V(u+2); half-steps j = 2u+1 and 2u+2, which
-    // read K tile u+1 and V tile u.  All four LDS regions are distinct tile slots.
-    __device__ __forceinline__ void steady_pair(const byte* __restrict__ kread, const byte* __restrict__ vread,
+    // read K tile u+1 (slot kread) and V tile u (slot vread).
+    __device__ __forceinline__ void steady_pair(const byte* kread, const byte* vread,
                                                 byte* __restrict__ kwrite, byte* __restrict__ vwrite,
-                                                const __bf16* __restrict__ Kg, const __bf16* __restrict__ Vg,
+                                                const byte* __restrict__ Kg, const byte* __restrict__ Vg,
                                                 const int (&krows)[CH], const int (&vrows)[CH],
                                                 f32x16 (&SA)[2], f32x16 (&SB)[2],
                                                 bf16x8 (&PA)[2][2], bf16x8 (&PB)[2][2]) {
-        issue_tile(kwrite, vwrite, Kg, Vg, krows, vrows);
-        fast_step(kread, 0, vread, 0, SB, SA, PA, PB);   // odd:  S(j) in SB, P(j-1) in PA -> S(j+1) in SA, P(j) in PB
-        fast_step(kread, 1, vread, 1, SA, SB, PB, PA);   // even: S(j) in SA, P(j-1) in PB -> S(j+1) in SB, P(j) in PA
+        static_assert(AHEAD == 3 && KK >= AHEAD, "the hand-placed LDS waits assume this look-ahead");
+        uint32_t kv[KK], vv[ODB];
+        const uint32_t kb = lds_address(kread), vb = lds_address(vread);
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) kv[kk] = kb + kaddr[kk];
+#pragma unroll
+        for (int db = 0; db < ODB; ++db) vv[db] = vb + vaddr[db];
+        bf16x8 kpre[AHEAD];
+#pragma unroll
+        for (int i = 0; i < AHEAD; ++i) kpre[i] = lds_read_b128_at<0>(kv[i]);
+        issue_tile(kwrite, vwrite, Kg, Vg, krows, vrows);   // its address arithmetic covers the LDS latency
+        // odd:  S(j) in SB, P(j-1) in PA -> S(j+1) in SA, P(j) in PB
+        fast_step<0, 0, true, 1>(kv, vv, kpre, SB, SA, PA, PB);
+        // even: S(j) in SA, P(j-1) in PB -> S(j+1) in SB, P(j) in PA
+        fast_step<1, 1, false, 0>(kv, vv, kpre, SA, SB, PB, PA);
     }
 };
 
@@ -292,26 +517,17 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     w.ntiles = (p.ns + BN - 1) / BN;
     w.nhalf = 2 * w.ntiles;
     w.ragged = (p.ns & (BN - 1)) != 0;
-    w.sn = p.td.sn;
-    w.K = (const __bf16*)p.k + head_off;
-    w.V = HAS_V ? (const __bf16*)p.v + head_off : nullptr;
-    w.idx = W::GATHER ? p.idx + (int64_t)bh * p.ns : nullptr;
+    w.row_bytes = (uint32_t)p.td.sn * 2u;
+    w.K = (const byte*)((const __bf16*)p.k + head_off);
+    w.V = HAS_V ? (const byte*)((const __bf16*)p.v + head_off) : nullptr;
+    w.idx = W::GATHER ? (const byte*)(p.idx + (int64_t)bh * p.ns) : nullptr;
     w.c2 = p.scale * kLog2e;                 // exp(z*scale) = exp2(z*c2)
     w.mc[0] = w.mc[1] = -INFINITY;
     w.l_run[0] = w.l_run[1] = 0.f;
-    w.lrow = w.lane / W::PIECES;
-    {
-        const int lslot = w.lane % W::PIECES;
-#pragma unroll
-        for (int i = 0; i < CH; ++i) {
-            const int row = (w.wave * CH + i) * W::ROWS_PER_CHUNK + w.lrow;
-            w.koff[i] = (lslot ^ swizzle_k<W::PIECES>(row)) * 8;
-            w.voff[i] = (lslot ^ swizzle_v<W::PIECES>(row)) * 8;
-        }
-    }
+    w.init_addresses();
     const int n = p.n, nhalf = w.nhalf;
 
-    // ---- Q fragments: B operand, [query lq][d = kk*16 + 8*lh .. +7]
+    // ---- Q fragments: B operand, [query lq][d = kk*16 + 8*lh .. +7], parked in AGPRs
     const int q0 = qblk * BM + w.wave * 64;
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
@@ -324,9 +540,15 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
-        for (int db = 0; db < ODB; ++db)
+        for (int kk = 0; kk < KK; ++kk) asm volatile("" : "+a"(w.qf[qb][kk]));
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int db = 0; db < ODB; ++db) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) w.o_acc[qb][db][r] = 0.f;
+            asm volatile("" : "+a"(w.o_acc[qb][db]));
+        }
 
     // ---- prologue: tiles 0..2 of K and V into their slots; then rows_k = tile 3, rows_v = tile 2
     int rows_k[CH], rows_v[CH], rows_n[CH];
@@ -348,7 +570,8 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
         for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
             for (int e = 0; e < 8; ++e) { PA[qb][hf][e] = (__bf16)0.f; PB[qb][hf][e] = (__bf16)0.f; }
-    w.qk(lds_k, 0, SA);
+    w.qk_all(lds_k, 0, SA);
+    mfma_settle(SA[0], SA[1]);
     w.mask_tail(0, SA);
     w.half_tile_max(SA);
 
@@ -386,10 +609,10 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
             w.general_step(j, lds_k, lds_v, SB, SA, PA, PB);
         }
     }
-    w.pv(lds_v + (HAS_V ? (((nhalf - 1) >> 1) % NBUF) * TILE_BYTES : 0), (nhalf - 1) & 1, PB);
+    w.pv_all(lds_v + (HAS_V ? (((nhalf - 1) >> 1) % NBUF) * TILE_BYTES : 0), (nhalf - 1) & 1, PB);
 
     // ---- epilogue: O = diag(l)^-1 acc, optional row log-sum-exp
-    if (HAS_V) mfma_agpr_settle();
+    if (HAS_V) mfma_settle_acc(w.o_acc);
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
         const float l_tot = half_sum(w.l_run[qb]);

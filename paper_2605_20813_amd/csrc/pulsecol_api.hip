@@ -58,6 +58,11 @@ pulsecol_status check_shape(const pulsecol_shape* s, std::string* why) {
     if (s->group_size != 0 && s->group_size < s->seq) { *why = "per-group column sets (0 < group_size < seq) are not built yet"; return PULSECOL_ERR_UNSUPPORTED; }
     if ((int64_t)s->batch * s->heads > (1 << 20)) { *why = "batch*heads too large"; return PULSECOL_ERR_UNSUPPORTED; }
     if (s->stride_n != 0 && s->stride_n < s->head_dim) { *why = "stride_n smaller than head_dim"; return PULSECOL_ERR_INVALID_ARG; }
+    {   // the kernels address a head's K/V rows with 32-bit byte offsets
+        const int64_t sn = s->stride_n ? s->stride_n : s->head_dim;
+        const int64_t esize = s->dtype == PULSECOL_BF16 ? 2 : 4;
+        if ((int64_t)s->seq * sn * esize >= ((int64_t)1 << 32)) { *why = "seq * stride_n exceeds 4 GiB per head"; return PULSECOL_ERR_UNSUPPORTED; }
+    }
     const int a = elem_align(s->dtype);
     if (s->stride_b % a || s->stride_h % a || s->stride_n % a) { *why = "strides must be multiples of 16 bytes"; return PULSECOL_ERR_ALIGNMENT; }
     return PULSECOL_OK;
