@@ -18,9 +18,12 @@
 // MFMA each, fenced so that the compiler keeps the hand-made interleaving: every slot issues
 // its MFMA, then a few VALU operations of the exp / row-max work, and every second slot the
 // LDS read of a fragment needed three MFMA pairs later.  The reference maximum is raised
-// lazily: a half-tile whose maximum stays within 2^kTau of the reference keeps it (exact:
-// numerator and denominator carry the same factor), so the accumulator is rescaled only on
-// rare steps, and then by an exact power of two.
+// lazily and after the fact: P is formed against the current reference, and only when a
+// lane's row sum of the half-tile exceeds 2^kTau (or is not finite) does the wave take the
+// slow path that finds the true maximum, moves the reference by a whole number of log2
+// units, rescales l and the accumulator by that exact power of two and recomputes P.  The
+// result is exact either way (numerator and denominator carry the same factor); the fast
+// path needs no row maximum at all.
 //
 // The MFMAs are inline assembly (to pin operands to AGPRs), so the compiler does not know
 // their latency: every place where the VALU reads an MFMA result is either separated from
@@ -55,6 +58,20 @@ __device__ __forceinline__ void mfma_qk(f32x16& s, bf16x8 a, bf16x8 q) {
 // O += a * p with O held in AGPRs
 __device__ __forceinline__ void mfma_pv(f32x16& o, bf16x8 a, bf16x8 p) {
     asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(o) : "v"(a), "v"(p));
+}
+// The same three, preceded by "wait until at most N LDS reads are outstanding": used by the
+// first MFMA that consumes a fragment requested a few slots earlier.
+template <int N>
+__device__ __forceinline__ void mfma_qk_first_after(f32x16& s, bf16x8 a, bf16x8 q) {
+    asm volatile("s_waitcnt lgkmcnt(%3)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "v"(a), "a"(q), "n"(N));
+}
+template <int N>
+__device__ __forceinline__ void mfma_qk_after(f32x16& s, bf16x8 a, bf16x8 q) {
+    asm volatile("s_waitcnt lgkmcnt(%3)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(a), "a"(q), "n"(N));
+}
+template <int N>
+__device__ __forceinline__ void mfma_pv_after(f32x16& o, bf16x8 a, bf16x8 p) {
+    asm volatile("s_waitcnt lgkmcnt(%3)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(o) : "v"(a), "v"(p), "n"(N));
 }
 // Waits out the write-back of every matrix instruction issued so far (the longest
 // MFMA-result-to-VALU hazard on gfx950 is 18 wait states).  The values the VALU is about to
@@ -125,13 +142,8 @@ struct AttnWave {
     static constexpr int NP = KK + NPV;                  // MFMA pairs of a half-step
     static constexpr int NS = 2 * NP;                    // MFMA slots of a half-step
     static constexpr int EXP_TICKS = 34;                 // 32 values through a 3-stage pipeline
-    static constexpr int MAX_TICKS = 20;
-    static constexpr int MAX_SLOT0 = 2 * KK + 3;         // first slot whose VALU work may read S_out
-    // exp / max ticks finished before slot s (slot NS = end of the half-step)
+    // exp ticks finished before slot s (slot NS = end of the half-step)
     static constexpr int exp_ticks_before(int s) { return ceil_div(EXP_TICKS * s, NS); }
-    static constexpr int max_ticks_before(int s) {
-        return s <= MAX_SLOT0 ? 0 : ceil_div(MAX_TICKS * (s - MAX_SLOT0), NS - MAX_SLOT0);
-    }
     // direct-to-LDS loads per steady-state issue point (the row-number loads are issued before
     // them, so "all but the newest VM_PER_ISSUE" covers every load of earlier iterations)
     static constexpr int VM_PER_ISSUE = CH + (HAS_V ? CH : 0);
@@ -151,7 +163,6 @@ struct AttnWave {
     float c2;
     float mc[2];          // reference maximum in log2 units (raw maximum * c2), equal in both half-waves
     float l_run[2];       // per-lane partial row sum (this lane's keys only)
-    float mx_next[2];     // raw maximum of the half-tile whose S is in flight
     uint32_t koff[CH], voff[CH];   // global byte offset of this lane's piece inside a row, per load instruction
     uint32_t kaddr[KK];   // LDS byte offset (inside a tile slot, first half) of this lane's K fragment kk
     uint32_t vaddr[ODB];  // same for the first 4-row group of the V fragment of d-block db
@@ -237,80 +248,71 @@ struct AttnWave {
                 if (acc_row(r, lh) >= valid) { S[0][r] = -INFINITY; S[1][r] = -INFINITY; }
         }
     }
-    // Row maximum of a half-tile in MAX_TICKS small steps (10 per query block) that can be
-    // spread over MFMA slots.
-    __device__ __forceinline__ void max_tick(int i, const f32x16 (&S)[2], float (&a)[4]) {
-        const int qb = i / 10;
-        const f32x16& s = S[qb];
-        switch (i % 10) {
-            case 0: a[0] = fmaxf(fmaxf(s[0], s[1]), s[2]); break;
-            case 1: a[1] = fmaxf(fmaxf(s[3], s[4]), s[5]); break;
-            case 2: a[2] = fmaxf(fmaxf(s[6], s[7]), s[8]); break;
-            case 3: a[3] = fmaxf(fmaxf(s[9], s[10]), s[11]); break;
-            case 4: a[0] = fmaxf(fmaxf(a[0], s[12]), s[13]); break;
-            case 5: a[1] = fmaxf(fmaxf(a[1], s[14]), s[15]); break;
-            case 6: a[0] = fmaxf(a[0], a[1]); break;
-            case 7: a[2] = fmaxf(a[2], a[3]); break;
-            case 8: a[0] = fmaxf(a[0], a[2]); break;
-            default: mx_next[qb] = half_max(a[0]); pin(mx_next[qb]); break;
-        }
-        if (i % 10 < 9) pin(a[(i % 10) == 7 ? 2 : ((i % 10) < 4 ? i % 10 : ((i % 10) == 5 ? 1 : 0))]);
+    // maximum over this lane's 16 values and the 16 of the lane that shares its query column
+    __device__ __forceinline__ float half_tile_max(const f32x16& s) const {
+        float a0 = fmaxf(fmaxf(s[0], s[1]), s[2]);
+        float a1 = fmaxf(fmaxf(s[3], s[4]), s[5]);
+        float a2 = fmaxf(fmaxf(s[6], s[7]), s[8]);
+        float a3 = fmaxf(fmaxf(s[9], s[10]), s[11]);
+        a0 = fmaxf(fmaxf(a0, s[12]), s[13]);
+        a1 = fmaxf(fmaxf(a1, s[14]), s[15]);
+        return half_max(fmaxf(fmaxf(a0, a1), fmaxf(a2, a3)));
     }
-    __device__ __forceinline__ void half_tile_max(const f32x16 (&S)[2]) {
-        float a[4];
-#pragma unroll
-        for (int i = 0; i < MAX_TICKS; ++i) max_tick(i, S, a);
-    }
-    // P = exp2(S*c2 - mc) in EXP_TICKS small steps: tick i forms the scaled, shifted logit of
-    // value i, takes exp2 of value i-1, and adds value i-2 to the row sum (packing a bf16 pair
-    // after every odd value).  Value e = qb*16 + r.
-    struct ExpPipe { float t[32]; float x[32]; float rs[2][2]; };
+    // P = exp2(S*c2 - mc) in EXP_TICKS small steps that can be spread over MFMA slots: tick i
+    // packs the bf16 pair that value i-2 completes (and adds it to the row sum with one
+    // dot-product instruction), takes exp2 of value i-1 and forms the scaled, shifted logit of
+    // value i.  Value e = qb*16 + r.  The row sum is therefore the sum of the bf16-rounded
+    // weights, the ones the P V product applies.
+    struct ExpPipe { float t[32]; float x[32]; float rs[2]; };
     __device__ __forceinline__ void exp_tick(int i, const f32x16 (&S)[2], bf16x8 (&P)[2][2], ExpPipe& ep) {
+        if (HAS_V) {
+            if (i >= 2 && i <= 33 && ((i - 2) & 1)) {
+                const int e = i - 2, qb = e >> 4, r = e & 15;
+                bf16x2 w, ones;
+                w[0] = (__bf16)ep.x[e - 1];
+                w[1] = (__bf16)ep.x[e];
+                ones[0] = (__bf16)1.0f;
+                ones[1] = (__bf16)1.0f;
+                P[qb][r >> 3][(r & 7) - 1] = w[0];
+                P[qb][r >> 3][r & 7] = w[1];
+                ep.rs[qb] = __builtin_amdgcn_fdot2_f32_bf16(w, ones, ep.rs[qb], false);
+                pin(P[qb][r >> 3]);
+                pin(ep.rs[qb]);
+            }
+        } else if (i >= 2 && i <= 33) {
+            // row log-sum-exp pass: no P, and the sum stays in fp32 (it normalises the column
+            // masses of the identification pass, which are compared at the 1e-6 level)
+            ep.rs[(i - 2) >> 4] += ep.x[i - 2];
+            pin(ep.rs[(i - 2) >> 4]);
+        }
         if (i < 32) {
             ep.t[i] = __builtin_fmaf(S[i >> 4][i & 15], c2, -mc[i >> 4]);
             pin(ep.t[i]);
         }
-        if (i >= 1 && i <= 32) {
+        if (i >= 1 && i <= 32) {      // its input was formed one tick ago, not by the instruction before
             ep.x[i - 1] = fast_exp2(ep.t[i - 1]);
             pin(ep.x[i - 1]);
         }
-        if (i >= 2 && i <= 33) {
-            const int e = i - 2, qb = e >> 4, r = e & 15;
-            ep.rs[qb][r & 1] += ep.x[e];
-            pin(ep.rs[qb][r & 1]);
-            if (r & 1) {
-                P[qb][r >> 3][(r & 7) - 1] = (__bf16)ep.x[e - 1];
-                P[qb][r >> 3][r & 7] = (__bf16)ep.x[e];
-                pin(P[qb][r >> 3]);
-            }
-        }
     }
-    __device__ __forceinline__ void exp_begin(ExpPipe& ep) {
-        ep.rs[0][0] = ep.rs[0][1] = ep.rs[1][0] = ep.rs[1][1] = 0.f;
+    __device__ __forceinline__ void exp_begin(ExpPipe& ep) { ep.rs[0] = ep.rs[1] = 0.f; }
+    // Close a half-tile: accept the row sums, or -- if some lane's sum says that its weights
+    // outgrew the reference (or is not a number: first half-tile, reference still -inf) -- fix
+    // the reference first.  Every MFMA that adds P(j-1) to the accumulator has been issued.
+    __device__ __forceinline__ void exp_end(ExpPipe& ep, const f32x16 (&S)[2], bf16x8 (&P)[2][2]) {
+        const float limit = __builtin_amdgcn_exp2f(kTau);
+        const bool bad = !(ep.rs[0] <= limit) || !(ep.rs[1] <= limit);
+        if (__builtin_expect(__ballot(bad) != 0ull, 0)) fix_reference(ep, S, P);
+        l_run[0] += ep.rs[0];
+        l_run[1] += ep.rs[1];
     }
-    __device__ __forceinline__ void exp_end(const ExpPipe& ep) {
-        l_run[0] += ep.rs[0][0] + ep.rs[0][1];
-        l_run[1] += ep.rs[1][0] + ep.rs[1][1];
-    }
-    __device__ __forceinline__ void exp_half_tile(const f32x16 (&S)[2], bf16x8 (&P)[2][2]) {
-        ExpPipe ep;
-        exp_begin(ep);
-#pragma unroll
-        for (int i = 0; i < EXP_TICKS; ++i) exp_tick(i, S, P, ep);
-        exp_end(ep);
-    }
-
-    // Raise the reference maximum where the incoming half-tile exceeds it by more than 2^kTau.
-    // The reference moves by a whole number of log2 units, so the factor applied to l, to the
-    // accumulator and to the pending P(j-1) is an exact power of two.
-    __device__ __forceinline__ void raise_reference(bf16x8 (&P_pending)[2][2]) {
-        const bool need = (mx_next[0] * c2 > mc[0] + kTau) || (mx_next[1] * c2 > mc[1] + kTau);
-        if (__builtin_expect(__ballot(need) == 0ull, 1)) return;
+    // Slow path: true maximum of the half-tile per query, reference moved up by a whole number
+    // of log2 units, l and the accumulator scaled by that exact power of two, P recomputed.
+    __device__ __forceinline__ void fix_reference(ExpPipe& ep, const f32x16 (&S)[2], bf16x8 (&P)[2][2]) {
         if (HAS_V) mfma_settle_acc(o_acc);
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
-            const float m2 = mx_next[qb] * c2;
-            if (m2 > mc[qb] + kTau) {
+            const float m2 = half_tile_max(S[qb]) * c2;        // same value in both half-waves
+            if (m2 > mc[qb] + 1.0f) {
                 const bool first = mc[qb] == -INFINITY;
                 const float steps = first ? 0.f : ceilf(m2 - mc[qb]);
                 const float alpha = first ? 0.f : fast_exp2(-steps);
@@ -321,14 +323,36 @@ struct AttnWave {
                     for (int db = 0; db < ODB; ++db)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) o_acc[qb][db][r] *= alpha;
-#pragma unroll
-                    for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-                        for (int e = 0; e < 8; ++e)
-                            P_pending[qb][hf][e] = (__bf16)((float)P_pending[qb][hf][e] * alpha);
                 }
+                float rs = 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; r += 2) {
+                    const float x0 = fast_exp2(__builtin_fmaf(S[qb][r], c2, -mc[qb]));
+                    const float x1 = fast_exp2(__builtin_fmaf(S[qb][r + 1], c2, -mc[qb]));
+                    if (HAS_V) {
+                        bf16x2 w, ones;
+                        w[0] = (__bf16)x0;
+                        w[1] = (__bf16)x1;
+                        ones[0] = (__bf16)1.0f;
+                        ones[1] = (__bf16)1.0f;
+                        P[qb][r >> 3][r & 7] = w[0];
+                        P[qb][r >> 3][(r & 7) + 1] = w[1];
+                        rs = __builtin_amdgcn_fdot2_f32_bf16(w, ones, rs, false);
+                    } else {
+                        rs += x0;
+                        rs += x1;
+                    }
+                }
+                ep.rs[qb] = rs;
             }
         }
+    }
+    __device__ __forceinline__ void exp_half_tile(const f32x16 (&S)[2], bf16x8 (&P)[2][2]) {
+        ExpPipe ep;
+        exp_begin(ep);
+#pragma unroll
+        for (int i = 0; i < EXP_TICKS; ++i) exp_tick(i, S, P, ep);
+        exp_end(ep, S, P);
     }
 
     // ------------------------------------------------------------------ half-steps
@@ -367,21 +391,15 @@ struct AttnWave {
                                               bf16x8 (&kpre)[AHEAD],
                                               f32x16 (&S_in)[2], f32x16 (&S_out)[2],
                                               bf16x8 (&P_in)[2][2], bf16x8 (&P_out)[2][2]) {
-        raise_reference(P_in);
         bf16x8 fr[NP + AHEAD];
 #pragma unroll
         for (int i = 0; i < AHEAD; ++i) fr[i] = kpre[i];
         ExpPipe ep;
         exp_begin(ep);
-        float mxa[4];
         fence();
-        fast_pairs<KH, VH, HAS_NEXT, NKH>(std::make_integer_sequence<int, NP>{}, kv, vv, fr, ep, mxa,
+        fast_pairs<KH, VH, HAS_NEXT, NKH>(std::make_integer_sequence<int, NP>{}, kv, vv, fr, ep,
                                           S_in, S_out, P_in, P_out);
-        exp_end(ep);
-        if (!HAS_V) {           // no P V stream to hide behind: wait for S_out, then take its maximum
-            mfma_settle(S_out[0], S_out[1]);
-            half_tile_max(S_out);
-        }
+        exp_end(ep, S_in, P_out);
         if (HAS_NEXT) {
 #pragma unroll
             for (int i = 0; i < AHEAD; ++i) kpre[i] = fr[NP + i];
@@ -390,15 +408,15 @@ struct AttnWave {
     template <int KH, int VH, bool HAS_NEXT, int NKH, int... Ps>
     __device__ __forceinline__ void fast_pairs(std::integer_sequence<int, Ps...>,
                                                const uint32_t (&kv)[KK], const uint32_t (&vv)[ODB],
-                                               bf16x8 (&fr)[NP + AHEAD], ExpPipe& ep, float (&mxa)[4],
+                                               bf16x8 (&fr)[NP + AHEAD], ExpPipe& ep,
                                                f32x16 (&S_in)[2], f32x16 (&S_out)[2],
                                                bf16x8 (&P_in)[2][2], bf16x8 (&P_out)[2][2]) {
-        (fast_pair<Ps, KH, VH, HAS_NEXT, NKH>(kv, vv, fr, ep, mxa, S_in, S_out, P_in, P_out), ...);
+        (fast_pair<Ps, KH, VH, HAS_NEXT, NKH>(kv, vv, fr, ep, S_in, S_out, P_in, P_out), ...);
     }
     // MFMA pair P of a fast half-step: two slots that share one A fragment.
     template <int P, int KH, int VH, bool HAS_NEXT, int NKH>
     __device__ __forceinline__ void fast_pair(const uint32_t (&kv)[KK], const uint32_t (&vv)[ODB],
-                                              bf16x8 (&fr)[NP + AHEAD], ExpPipe& ep, float (&mxa)[4],
+                                              bf16x8 (&fr)[NP + AHEAD], ExpPipe& ep,
                                               f32x16 (&S_in)[2], f32x16 (&S_out)[2],
                                               bf16x8 (&P_in)[2][2], bf16x8 (&P_out)[2][2]) {
         // request the fragment used AHEAD pairs later
@@ -413,27 +431,27 @@ struct AttnWave {
             fr[PA] = lds_read_b128_at<NKH * HALF_BYTES>(kv[PA - NP]);
         }
         // fragment P has landed once only the requests made after it are outstanding
-        lds_wait_all_but<frag_ops<HAS_NEXT>(P + 1) + frag_ops<HAS_NEXT>(P + 2) + frag_ops<HAS_NEXT>(P + 3)>(fr[P]);
+        constexpr int NEWER = frag_ops<HAS_NEXT>(P + 1) + frag_ops<HAS_NEXT>(P + 2) + frag_ops<HAS_NEXT>(P + 3);
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
             const int s = 2 * P + qb;
             if constexpr (P < KK) {
-                if constexpr (P == 0) mfma_qk_first(S_out[qb], fr[P], qf[qb][P]);
-                else mfma_qk(S_out[qb], fr[P], qf[qb][P]);
+                if constexpr (P == 0) {
+                    if (qb == 0) mfma_qk_first_after<NEWER>(S_out[qb], fr[P], qf[qb][P]);
+                    else mfma_qk_first(S_out[qb], fr[P], qf[qb][P]);
+                } else {
+                    if (qb == 0) mfma_qk_after<NEWER>(S_out[qb], fr[P], qf[qb][P]);
+                    else mfma_qk(S_out[qb], fr[P], qf[qb][P]);
+                }
             } else {
                 constexpr int q = P - KK;
-                mfma_pv(o_acc[qb][q % ODB], fr[P], P_in[qb][q / ODB]);
+                if (qb == 0) mfma_pv_after<NEWER>(o_acc[qb][q % ODB], fr[P], P_in[qb][q / ODB]);
+                else mfma_pv(o_acc[qb][q % ODB], fr[P], P_in[qb][q / ODB]);
             }
             fence();
             // this slot's share of the VALU work
 #pragma unroll
             for (int i = exp_ticks_before(s); i < exp_ticks_before(s + 1); ++i) exp_tick(i, S_in, P_out, ep);
-            if (HAS_V) {
-                // from here on the VALU may read S_out: its last MFMA was issued >= 3 MFMAs ago
-                if (s == MAX_SLOT0) pin(S_out[0], S_out[1]);
-#pragma unroll
-                for (int i = max_ticks_before(s); i < max_ticks_before(s + 1); ++i) max_tick(i, S_out, mxa);
-            }
             fence();
         }
     }
@@ -441,14 +459,12 @@ struct AttnWave {
     __device__ __forceinline__ void general_step(int j, const byte* kbase, const byte* vbase,
                                                  f32x16 (&S_in)[2], f32x16 (&S_out)[2],
                                                  bf16x8 (&P_in)[2][2], bf16x8 (&P_out)[2][2]) {
-        raise_reference(P_in);
         if (j >= 1) pv_all(vbase + (((j - 1) >> 1) % NBUF) * TILE_BYTES, (j - 1) & 1, P_in);
         exp_half_tile(S_in, P_out);
         if (j + 1 < nhalf) {
             qk_all(kbase + (((j + 1) >> 1) % NBUF) * TILE_BYTES, (j + 1) & 1, S_out);
             mfma_settle(S_out[0], S_out[1]);
             mask_tail(j + 1, S_out);
-            half_tile_max(S_out);
         }
     }
     // One steady-state iteration u: issue K(u+3), V(u+2); half-steps j = 2u+1 and 2u+2, which
@@ -573,7 +589,6 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     w.qk_all(lds_k, 0, SA);
     mfma_settle(SA[0], SA[1]);
     w.mask_tail(0, SA);
-    w.half_tile_max(SA);
 
     // j = 0: S(0) in SA -> P(0) in PA, S(1) in SB
     w.general_step(0, lds_k, lds_v, SA, SB, PB, PA);
