@@ -124,9 +124,7 @@ PULSECOL_API pulsecol_status pulsecol_attn(pulsecol_ctx* ctx, const void* Q, con
                               const int32_t* idx, int32_t k, void* O, void* stream);
 
 /* Dense attention baseline O = softmax(Q K^T * scale) V (Sec. 3.1).  If lse_out is not NULL
- * it receives the row log-sum-exp of the scaled logits, fp32 [B, H, seq]; in bf16 mode it is
- * taken from the sum of the bf16-rounded softmax weights the kernel applies (relative
- * accuracy about 1e-4; the identification pass uses its own fp32 row sums). */
+ * it receives the row log-sum-exp of the scaled logits, fp32 [B, H, seq]. */
 PULSECOL_API pulsecol_status pulsecol_attn_dense(pulsecol_ctx* ctx, const void* Q, const void* K, const void* V,
                                     void* O, float* lse_out, void* stream);
 

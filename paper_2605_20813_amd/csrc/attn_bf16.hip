@@ -40,7 +40,8 @@ namespace {
 constexpr int BM = kBlockM_bf16;
 constexpr int BN = kBlockN_bf16;
 constexpr int NTHREADS = 256;
-constexpr int NBUF = 3;            // LDS tile slots per operand
+constexpr int NBUF_K = 3;          // LDS tile slots for K
+constexpr int NBUF_V = 4;          // and for V, whose tiles stay in use half an iteration longer
 constexpr int AHEAD = 3;           // fragment reads run this many MFMA pairs ahead of their use
 constexpr float kTau = 8.0f;       // log2 of the growth allowed before the reference max is raised
 
@@ -121,6 +122,12 @@ __device__ __forceinline__ void lds_wait_all_but(bf16x8& frag) {
 }
 __device__ __forceinline__ uint32_t lds_address(const void* generic_lds_ptr) {
     return (uint32_t)(uintptr_t)(PULSECOL_LDS const void*)generic_lds_ptr;
+}
+
+// s_waitcnt vmcnt(v) with the other counters left alone (gfx9 encoding: vmcnt in [3:0] and [15:14])
+template <int v>
+__device__ __forceinline__ void wait_vmcnt_at_most() {
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (v & 0xF) | ((v & 0x30) << 10));
 }
 
 constexpr int ceil_div(int a, int b) { return (a + b - 1) / b; }
@@ -225,6 +232,17 @@ struct AttnWave {
         }
     }
 
+    __device__ __forceinline__ void issue_k_one(int i, byte* kslot, const int (&krows)[CH]) const {
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void*)(K + ((uint32_t)krows[i] * row_bytes + koff[i])),
+            (PULSECOL_LDS void*)(kslot + (wave * CH + i) * 1024), 16, 0, 0);
+    }
+    __device__ __forceinline__ void issue_v_one(int i, byte* vslot, const int (&vrows)[CH]) const {
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void*)(V + ((uint32_t)vrows[i] * row_bytes + voff[i])),
+            (PULSECOL_LDS void*)(vslot + (wave * CH + i) * 1024), 16, 0, 0);
+    }
+
     // ------------------------------------------------------------------ fragment reads
     __device__ __forceinline__ bf16x8 read_k(const byte* __restrict__ kslot, int half, int kk) const {
         return *(const bf16x8*)(kslot + half * HALF_BYTES + kaddr[kk]);
@@ -259,31 +277,19 @@ struct AttnWave {
         return half_max(fmaxf(fmaxf(a0, a1), fmaxf(a2, a3)));
     }
     // P = exp2(S*c2 - mc) in EXP_TICKS small steps that can be spread over MFMA slots: tick i
-    // packs the bf16 pair that value i-2 completes (and adds it to the row sum with one
-    // dot-product instruction), takes exp2 of value i-1 and forms the scaled, shifted logit of
-    // value i.  Value e = qb*16 + r.  The row sum is therefore the sum of the bf16-rounded
-    // weights, the ones the P V product applies.
-    struct ExpPipe { float t[32]; float x[32]; float rs[2]; };
+    // adds value i-2 to the fp32 row sum (packing a bf16 pair after every odd value), forms the
+    // scaled, shifted logit of value i and takes exp2 of value i-1.  Value e = qb*16 + r.
+    struct ExpPipe { float t[32]; float x[32]; float rs[2][2]; };
     __device__ __forceinline__ void exp_tick(int i, const f32x16 (&S)[2], bf16x8 (&P)[2][2], ExpPipe& ep) {
-        if (HAS_V) {
-            if (i >= 2 && i <= 33 && ((i - 2) & 1)) {
-                const int e = i - 2, qb = e >> 4, r = e & 15;
-                bf16x2 w, ones;
-                w[0] = (__bf16)ep.x[e - 1];
-                w[1] = (__bf16)ep.x[e];
-                ones[0] = (__bf16)1.0f;
-                ones[1] = (__bf16)1.0f;
-                P[qb][r >> 3][(r & 7) - 1] = w[0];
-                P[qb][r >> 3][r & 7] = w[1];
-                ep.rs[qb] = __builtin_amdgcn_fdot2_f32_bf16(w, ones, ep.rs[qb], false);
+        if (i >= 2 && i <= 33) {
+            const int e = i - 2, qb = e >> 4, r = e & 15;
+            ep.rs[qb][r & 1] += ep.x[e];            // two partial sums keep the add chains short
+            pin(ep.rs[qb][r & 1]);
+            if (HAS_V && (r & 1)) {
+                P[qb][r >> 3][(r & 7) - 1] = (__bf16)ep.x[e - 1];
+                P[qb][r >> 3][r & 7] = (__bf16)ep.x[e];
                 pin(P[qb][r >> 3]);
-                pin(ep.rs[qb]);
             }
-        } else if (i >= 2 && i <= 33) {
-            // row log-sum-exp pass: no P, and the sum stays in fp32 (it normalises the column
-            // masses of the identification pass, which are compared at the 1e-6 level)
-            ep.rs[(i - 2) >> 4] += ep.x[i - 2];
-            pin(ep.rs[(i - 2) >> 4]);
         }
         if (i < 32) {
             ep.t[i] = __builtin_fmaf(S[i >> 4][i & 15], c2, -mc[i >> 4]);
@@ -294,16 +300,20 @@ struct AttnWave {
             pin(ep.x[i - 1]);
         }
     }
-    __device__ __forceinline__ void exp_begin(ExpPipe& ep) { ep.rs[0] = ep.rs[1] = 0.f; }
+    __device__ __forceinline__ void exp_begin(ExpPipe& ep) {
+        ep.rs[0][0] = ep.rs[0][1] = ep.rs[1][0] = ep.rs[1][1] = 0.f;
+    }
     // Close a half-tile: accept the row sums, or -- if some lane's sum says that its weights
     // outgrew the reference (or is not a number: first half-tile, reference still -inf) -- fix
     // the reference first.  Every MFMA that adds P(j-1) to the accumulator has been issued.
     __device__ __forceinline__ void exp_end(ExpPipe& ep, const f32x16 (&S)[2], bf16x8 (&P)[2][2]) {
         const float limit = __builtin_amdgcn_exp2f(kTau);
-        const bool bad = !(ep.rs[0] <= limit) || !(ep.rs[1] <= limit);
+        ep.rs[0][0] += ep.rs[0][1];
+        ep.rs[1][0] += ep.rs[1][1];
+        const bool bad = !(ep.rs[0][0] <= limit) || !(ep.rs[1][0] <= limit);
         if (__builtin_expect(__ballot(bad) != 0ull, 0)) fix_reference(ep, S, P);
-        l_run[0] += ep.rs[0];
-        l_run[1] += ep.rs[1];
+        l_run[0] += ep.rs[0][0];
+        l_run[1] += ep.rs[1][0];
     }
     // Slow path: true maximum of the half-tile per query, reference moved up by a whole number
     // of log2 units, l and the accumulator scaled by that exact power of two, P recomputed.
@@ -329,21 +339,14 @@ struct AttnWave {
                 for (int r = 0; r < 16; r += 2) {
                     const float x0 = fast_exp2(__builtin_fmaf(S[qb][r], c2, -mc[qb]));
                     const float x1 = fast_exp2(__builtin_fmaf(S[qb][r + 1], c2, -mc[qb]));
+                    rs += x0;
+                    rs += x1;
                     if (HAS_V) {
-                        bf16x2 w, ones;
-                        w[0] = (__bf16)x0;
-                        w[1] = (__bf16)x1;
-                        ones[0] = (__bf16)1.0f;
-                        ones[1] = (__bf16)1.0f;
-                        P[qb][r >> 3][r & 7] = w[0];
-                        P[qb][r >> 3][(r & 7) + 1] = w[1];
-                        rs = __builtin_amdgcn_fdot2_f32_bf16(w, ones, rs, false);
-                    } else {
-                        rs += x0;
-                        rs += x1;
+                        P[qb][r >> 3][r & 7] = (__bf16)x0;
+                        P[qb][r >> 3][(r & 7) + 1] = (__bf16)x1;
                     }
                 }
-                ep.rs[qb] = rs;
+                ep.rs[qb][0] = rs;
             }
         }
     }
@@ -381,14 +384,26 @@ struct AttnWave {
     template <bool HAS_NEXT>
     static constexpr int frag_ops(int q) { return q < KK ? 1 : (q < NP ? 2 : (HAS_NEXT ? 1 : 0)); }
 
+    // What the first half-step of an iteration issues besides its own work: the row numbers of
+    // the tile after next and the direct-to-LDS loads of K(u+3) and V(u+2), one per MFMA pair.
+    struct IssueCtx {
+        byte* kwrite;
+        byte* vwrite;
+        int next_tile;
+    };
+
     // Fast half-step j (1 <= j <= nhalf-4): S_in = S(j), P_in = P(j-1) -> S_out = S(j+1), P_out = P(j).
     // kv / vv are this lane's LDS addresses of the K fragments (tile slot of S(j+1), first
     // half) and of the V fragments (tile slot of P(j-1), first half, first row group); KH / VH
     // select the half.  kpre holds the first AHEAD K fragments, already requested; with
-    // HAS_NEXT it is refilled with requests for the following half-step (same K slot, half NKH).
-    template <int KH, int VH, bool HAS_NEXT, int NKH>
+    // HAS_NEXT it is refilled with requests for the following half-step (addresses knext, half
+    // NKH).  ROLE 0 = first half-step of an iteration (spreads the loads of IssueCtx over its
+    // pairs), ROLE 1 = second (holds the workgroup barrier, see steady_pair).
+    template <int KH, int VH, bool HAS_NEXT, int NKH, int ROLE>
     __device__ __forceinline__ void fast_step(const uint32_t (&kv)[KK], const uint32_t (&vv)[ODB],
-                                              bf16x8 (&kpre)[AHEAD],
+                                              const uint32_t (&knext)[AHEAD], bf16x8 (&kpre)[AHEAD],
+                                              const IssueCtx& io, const int (&krows)[CH], const int (&vrows)[CH],
+                                              int (&rows_n)[CH],
                                               f32x16 (&S_in)[2], f32x16 (&S_out)[2],
                                               bf16x8 (&P_in)[2][2], bf16x8 (&P_out)[2][2]) {
         bf16x8 fr[NP + AHEAD];
@@ -397,28 +412,47 @@ struct AttnWave {
         ExpPipe ep;
         exp_begin(ep);
         fence();
-        fast_pairs<KH, VH, HAS_NEXT, NKH>(std::make_integer_sequence<int, NP>{}, kv, vv, fr, ep,
-                                          S_in, S_out, P_in, P_out);
+        fast_pairs<KH, VH, HAS_NEXT, NKH, ROLE>(std::make_integer_sequence<int, NP>{}, kv, vv, knext, fr, ep,
+                                                io, krows, vrows, rows_n, S_in, S_out, P_in, P_out);
         exp_end(ep, S_in, P_out);
         if (HAS_NEXT) {
 #pragma unroll
             for (int i = 0; i < AHEAD; ++i) kpre[i] = fr[NP + i];
         }
     }
-    template <int KH, int VH, bool HAS_NEXT, int NKH, int... Ps>
+    template <int KH, int VH, bool HAS_NEXT, int NKH, int ROLE, int... Ps>
     __device__ __forceinline__ void fast_pairs(std::integer_sequence<int, Ps...>,
                                                const uint32_t (&kv)[KK], const uint32_t (&vv)[ODB],
+                                               const uint32_t (&knext)[AHEAD],
                                                bf16x8 (&fr)[NP + AHEAD], ExpPipe& ep,
+                                               const IssueCtx& io, const int (&krows)[CH], const int (&vrows)[CH],
+                                               int (&rows_n)[CH],
                                                f32x16 (&S_in)[2], f32x16 (&S_out)[2],
                                                bf16x8 (&P_in)[2][2], bf16x8 (&P_out)[2][2]) {
-        (fast_pair<Ps, KH, VH, HAS_NEXT, NKH>(kv, vv, fr, ep, S_in, S_out, P_in, P_out), ...);
+        (fast_pair<Ps, KH, VH, HAS_NEXT, NKH, ROLE>(kv, vv, knext, fr, ep, io, krows, vrows, rows_n,
+                                                    S_in, S_out, P_in, P_out), ...);
     }
     // MFMA pair P of a fast half-step: two slots that share one A fragment.
-    template <int P, int KH, int VH, bool HAS_NEXT, int NKH>
+    template <int P, int KH, int VH, bool HAS_NEXT, int NKH, int ROLE>
     __device__ __forceinline__ void fast_pair(const uint32_t (&kv)[KK], const uint32_t (&vv)[ODB],
+                                              const uint32_t (&knext)[AHEAD],
                                               bf16x8 (&fr)[NP + AHEAD], ExpPipe& ep,
+                                              const IssueCtx& io, const int (&krows)[CH], const int (&vrows)[CH],
+                                              int (&rows_n)[CH],
                                               f32x16 (&S_in)[2], f32x16 (&S_out)[2],
                                               bf16x8 (&P_in)[2][2], bf16x8 (&P_out)[2][2]) {
+        static_assert((HAS_V ? 2 : 1) * CH + 1 <= NP, "one load instruction per MFMA pair");
+        if constexpr (ROLE == 0) {
+            if constexpr (P == 0) load_rows(io.next_tile, rows_n);
+            if constexpr (P >= 1 && P <= CH) issue_k_one(P - 1, io.kwrite, krows);
+            if constexpr (HAS_V && P > CH && P <= 2 * CH) issue_v_one(P - CH - 1, io.vwrite, vrows);
+        } else if constexpr (HAS_V && P == KK) {
+            // All K reads of this iteration are complete (their fragments have been consumed).
+            // Everything loaded before this iteration's own loads has landed; after the barrier
+            // the other waves' shares are visible too, and the slots they free may be refilled.
+            wait_vmcnt_at_most<VM_PER_ISSUE>();
+            __builtin_amdgcn_s_barrier();
+        }
         // request the fragment used AHEAD pairs later
         constexpr int PA = P + AHEAD;
         if constexpr (PA < KK) {
@@ -428,7 +462,7 @@ struct AttnWave {
             fr[PA] = lds_read_tr_pair_at<VH * HALF_BYTES + hf * 16 * ROW_BYTES,
                                          VH * HALF_BYTES + hf * 16 * ROW_BYTES + 8 * ROW_BYTES>(vv[db]);
         } else if constexpr (HAS_NEXT) {
-            fr[PA] = lds_read_b128_at<NKH * HALF_BYTES>(kv[PA - NP]);
+            fr[PA] = lds_read_b128_at<NKH * HALF_BYTES>(knext[PA - NP]);
         }
         // fragment P has landed once only the requests made after it are outstanding
         constexpr int NEWER = frag_ops<HAS_NEXT>(P + 1) + frag_ops<HAS_NEXT>(P + 2) + frag_ops<HAS_NEXT>(P + 3);
@@ -459,45 +493,41 @@ struct AttnWave {
     __device__ __forceinline__ void general_step(int j, const byte* kbase, const byte* vbase,
                                                  f32x16 (&S_in)[2], f32x16 (&S_out)[2],
                                                  bf16x8 (&P_in)[2][2], bf16x8 (&P_out)[2][2]) {
-        if (j >= 1) pv_all(vbase + (((j - 1) >> 1) % NBUF) * TILE_BYTES, (j - 1) & 1, P_in);
+        if (j >= 1) pv_all(vbase + (((j - 1) >> 1) % NBUF_V) * TILE_BYTES, (j - 1) & 1, P_in);
         exp_half_tile(S_in, P_out);
         if (j + 1 < nhalf) {
-            qk_all(kbase + (((j + 1) >> 1) % NBUF) * TILE_BYTES, (j + 1) & 1, S_out);
+            qk_all(kbase + (((j + 1) >> 1) % NBUF_K) * TILE_BYTES, (j + 1) & 1, S_out);
             mfma_settle(S_out[0], S_out[1]);
             mask_tail(j + 1, S_out);
         }
     }
-    // One steady-state iteration u: issue K(u+3), V(u+2); half-steps j = 2u+1 and 2u+2, which
-    // read K tile u+1 (slot kread) and V tile u (slot vread).
-    __device__ __forceinline__ void steady_pair(const byte* kread, const byte* vread,
-                                                byte* __restrict__ kwrite, byte* __restrict__ vwrite,
-                                                const byte* __restrict__ Kg, const byte* __restrict__ Vg,
-                                                const int (&krows)[CH], const int (&vrows)[CH],
+    // One steady-state iteration u: half-steps j = 2u+1 and 2u+2, which read K tile u+1
+    // (fragment addresses kv) and V tile u (vv).  The first half-step issues the loads of
+    // K(u+3) and V(u+2); the second one holds the barrier -- placed after its last K read, so
+    // that the slot of K(u+1) is free and K(u+2), V(u+1) are visible -- and then requests the
+    // first K fragments of the next iteration (addresses knext) while its P V MFMAs run.
+    __device__ __forceinline__ void steady_pair(const uint32_t (&kv)[KK], const uint32_t (&vv)[ODB],
+                                                const uint32_t (&knext)[AHEAD], bf16x8 (&kpre)[AHEAD],
+                                                const IssueCtx& io, const int (&krows)[CH], const int (&vrows)[CH],
+                                                int (&rows_n)[CH],
                                                 f32x16 (&SA)[2], f32x16 (&SB)[2],
                                                 bf16x8 (&PA)[2][2], bf16x8 (&PB)[2][2]) {
         static_assert(AHEAD == 3 && KK >= AHEAD, "the hand-placed LDS waits assume this look-ahead");
-        uint32_t kv[KK], vv[ODB];
-        const uint32_t kb = lds_address(kread), vb = lds_address(vread);
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk) kv[kk] = kb + kaddr[kk];
-#pragma unroll
-        for (int db = 0; db < ODB; ++db) vv[db] = vb + vaddr[db];
-        bf16x8 kpre[AHEAD];
-#pragma unroll
-        for (int i = 0; i < AHEAD; ++i) kpre[i] = lds_read_b128_at<0>(kv[i]);
-        issue_tile(kwrite, vwrite, Kg, Vg, krows, vrows);   // its address arithmetic covers the LDS latency
+        const uint32_t ksame[AHEAD] = {kv[0], kv[1], kv[2]};
         // odd:  S(j) in SB, P(j-1) in PA -> S(j+1) in SA, P(j) in PB
-        fast_step<0, 0, true, 1>(kv, vv, kpre, SB, SA, PA, PB);
+        fast_step<0, 0, true, 1, 0>(kv, vv, ksame, kpre, io, krows, vrows, rows_n, SB, SA, PA, PB);
         // even: S(j) in SA, P(j-1) in PB -> S(j+1) in SB, P(j) in PA
-        fast_step<1, 1, false, 0>(kv, vv, kpre, SA, SB, PB, PA);
+        fast_step<1, 1, HAS_V, 0, 1>(kv, vv, knext, kpre, io, krows, vrows, rows_n, SA, SB, PB, PA);
+        if (!HAS_V) {
+            // row pass: no P V stream to cover the barrier; synchronise at the end of the iteration
+            wait_vmcnt_at_most<VM_PER_ISSUE>();
+            __builtin_amdgcn_s_barrier();
+#pragma unroll
+            for (int i = 0; i < AHEAD; ++i) kpre[i] = lds_read_b128_at<0>(knext[i]);
+        }
     }
 };
 
-// s_waitcnt vmcnt(v) with the other counters left alone (gfx9 encoding: vmcnt in [3:0] and [15:14])
-template <int v>
-__device__ __forceinline__ void wait_vmcnt() {
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (v & 0xF) | ((v & 0x30) << 10));
-}
 
 template <int D, int MODE>
 __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
@@ -511,9 +541,9 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     // ONE shared array for all tile slots: with a single LDS object the alias scopes that the
     // restrict parameters give the direct-to-LDS loads are what the compiler's wait-count
     // insertion sees, and LDS reads of one slot do not wait for loads into another.
-    __shared__ __attribute__((aligned(1024))) byte lds_all[(HAS_V ? 2 : 1) * NBUF * TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) byte lds_all[(NBUF_K + (HAS_V ? NBUF_V : 0)) * TILE_BYTES];
     byte* const lds_k = lds_all;
-    byte* const lds_v = lds_all + (HAS_V ? NBUF * TILE_BYTES : 0);
+    byte* const lds_v = lds_all + (HAS_V ? NBUF_K * TILE_BYTES : 0);
 
     const int nqb = (p.n + BM - 1) / BM;
     int bh, qblk;
@@ -569,13 +599,13 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     // ---- prologue: tiles 0..2 of K and V into their slots; then rows_k = tile 3, rows_v = tile 2
     int rows_k[CH], rows_v[CH], rows_n[CH];
 #pragma unroll 1
-    for (int t = 0; t < NBUF; ++t) {
+    for (int t = 0; t < NBUF_K; ++t) {
         w.load_rows(t, rows_k);
         w.issue_tile(lds_k + t * TILE_BYTES, lds_v + (HAS_V ? t * TILE_BYTES : 0), w.K, w.V, rows_k, rows_k);
     }
     w.load_rows(2, rows_v);
     w.load_rows(3, rows_k);
-    wait_vmcnt<0>();
+    wait_vmcnt_at_most<0>();
     __builtin_amdgcn_s_barrier();
 
     f32x16 SA[2], SB[2];
@@ -595,24 +625,41 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
 
     // ---- steady state: iteration u runs half-steps 2u+1 and 2u+2 (both <= nhalf-4)
     const int npairs = nhalf >= 4 ? (nhalf - 4) / 2 : 0;
-    int kr = 1, vr = 0;            // slot of K tile u+1 / of V tile u
-    for (int u = 0; u < npairs; ++u) {
-        const int kw = vr;                             // K(u+3) -> slot (u+3)%3 == u%3
-        const int vw = vr >= 1 ? vr - 1 : vr + 2;      // V(u+2) -> slot (u+2)%3
-        w.load_rows(u + 4, rows_n);
-        w.steady_pair(lds_k + kr * TILE_BYTES, lds_v + (HAS_V ? vr * TILE_BYTES : 0),
-                      lds_k + kw * TILE_BYTES, lds_v + (HAS_V ? vw * TILE_BYTES : 0),
-                      w.K, w.V, rows_k, rows_v, SA, SB, PA, PB);
+    if (npairs > 0) {
+        const uint32_t kbase = lds_address(lds_k), vbase = lds_address(lds_v);
+        int kr = 1, vr = 0;            // slot of K tile u+1 / of V tile u
+        uint32_t kv[KK], vv[ODB], knext[AHEAD];
+        bf16x8 kpre[AHEAD];
 #pragma unroll
-        for (int i = 0; i < CH; ++i) { rows_v[i] = rows_k[i]; rows_k[i] = rows_n[i]; }
-        kr = kr == 2 ? 0 : kr + 1;
-        vr = vr == 2 ? 0 : vr + 1;
-        // everything but this iteration's own loads has landed; then all waves swap slots
-        wait_vmcnt<W::VM_PER_ISSUE>();
-        __builtin_amdgcn_s_barrier();
+        for (int kk = 0; kk < KK; ++kk) kv[kk] = kbase + kr * TILE_BYTES + w.kaddr[kk];
+#pragma unroll
+        for (int db = 0; db < ODB; ++db) vv[db] = vbase + vr * TILE_BYTES + w.vaddr[db];
+#pragma unroll
+        for (int i = 0; i < AHEAD; ++i) kpre[i] = lds_read_b128_at<0>(kv[i]);
+        for (int u = 0; u < npairs; ++u) {
+            const int kr_next = kr == NBUF_K - 1 ? 0 : kr + 1;
+            const int vr_next = vr == NBUF_V - 1 ? 0 : vr + 1;
+            const int kw = kr_next == NBUF_K - 1 ? 0 : kr_next + 1;      // K(u+3) -> slot (u+3) % 3
+            const int vw = vr_next == NBUF_V - 1 ? 0 : vr_next + 1;      // V(u+2) -> slot (u+2) % 4
+            typename W::IssueCtx io;
+            io.kwrite = lds_k + kw * TILE_BYTES;
+            io.vwrite = lds_v + (HAS_V ? vw * TILE_BYTES : 0);
+            io.next_tile = u + 4;
+#pragma unroll
+            for (int i = 0; i < AHEAD; ++i) knext[i] = kbase + kr_next * TILE_BYTES + w.kaddr[i];
+            w.steady_pair(kv, vv, knext, kpre, io, rows_k, rows_v, rows_n, SA, SB, PA, PB);
+#pragma unroll
+            for (int i = 0; i < CH; ++i) { rows_v[i] = rows_k[i]; rows_k[i] = rows_n[i]; }
+            kr = kr_next;
+            vr = vr_next;
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) kv[kk] = kbase + kr * TILE_BYTES + w.kaddr[kk];
+#pragma unroll
+            for (int db = 0; db < ODB; ++db) vv[db] = vbase + vr * TILE_BYTES + w.vaddr[db];
+        }
     }
     // ---- tail: the remaining half-steps (at most three), then the last P V product
-    wait_vmcnt<0>();
+    wait_vmcnt_at_most<0>();
     __builtin_amdgcn_s_barrier();
     int j = 2 * npairs + 1;
     if (j < nhalf) {                              // odd
@@ -624,7 +671,7 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
             w.general_step(j, lds_k, lds_v, SB, SA, PA, PB);
         }
     }
-    w.pv_all(lds_v + (HAS_V ? (((nhalf - 1) >> 1) % NBUF) * TILE_BYTES : 0), (nhalf - 1) & 1, PB);
+    w.pv_all(lds_v + (HAS_V ? (((nhalf - 1) >> 1) % NBUF_V) * TILE_BYTES : 0), (nhalf - 1) & 1, PB);
 
     // ---- epilogue: O = diag(l)^-1 acc, optional row log-sum-exp
     if (HAS_V) mfma_settle_acc(w.o_acc);

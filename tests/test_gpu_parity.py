@@ -82,10 +82,7 @@ def test_dense_attention_and_lse_match_oracle(B, H, n, d, dtype):
             Z = oracle.attention_logits(q, k_)
             m = Z.max(axis=1)
             want_lse = m + np.log(np.exp(Z - m[:, None]).sum(axis=1))
-            # the bf16 dense kernel normalises by the sum of the bf16-rounded weights it applies
-            # (relative 2^-9 per weight, averaging down over a row); fp32 mode sums in fp32
-            lse_tol = 2e-4 if dtype == torch.bfloat16 else 2e-5
-            np.testing.assert_allclose(f64(lse[b, h]), want_lse, rtol=0, atol=lse_tol * max(1.0, np.abs(want_lse).max()))
+            np.testing.assert_allclose(f64(lse[b, h]), want_lse, rtol=0, atol=2e-5 * max(1.0, np.abs(want_lse).max()))
 
 
 def test_keep_everything_equals_dense_on_gpu_and_oracle():
