@@ -40,8 +40,11 @@ namespace {
 constexpr int BM = kBlockM_bf16;
 constexpr int BN = kBlockN_bf16;
 constexpr int NTHREADS = 256;
-constexpr int NBUF_K = 3;          // LDS tile slots for K
-constexpr int NBUF_V = 4;          // and for V, whose tiles stay in use half an iteration longer
+constexpr int NBUF = 4;            // LDS tile slots for K and for V: tile t lives in slot t % NBUF, and the
+                                   // steady loop is unrolled NBUF times so that every slot is an immediate
+constexpr int NBUF_K = NBUF;
+constexpr int NBUF_V = NBUF;
+constexpr int PRO_TILES = 3;       // tiles loaded before the first half-step
 constexpr int AHEAD = 3;           // fragment reads run this many MFMA pairs ahead of their use
 constexpr float kTau = 8.0f;       // log2 of the growth allowed before the reference max is raised
 
@@ -98,6 +101,12 @@ __device__ __forceinline__ void mfma_settle_acc(f32x16 (&o)[2][N]) {
 __device__ __forceinline__ void pin(float& a) { asm volatile("" : "+v"(a)); }
 __device__ __forceinline__ void pin(float& a, float& b) { asm volatile("" : "+v"(a), "+v"(b)); }
 __device__ __forceinline__ void pin(bf16x8& a) { asm volatile("" : "+v"(a)); }
+// element pair `i` (two bf16 in one 32-bit register) of a fragment
+__device__ __forceinline__ void set_pair(bf16x8& f, int i, uint32_t w) {
+    u32x4 t = __builtin_bit_cast(u32x4, f);
+    t[i] = w;
+    f = __builtin_bit_cast(bf16x8, t);
+}
 __device__ __forceinline__ void pin(f32x16& a, f32x16& b) { asm volatile("" : "+v"(a), "+v"(b)); }
 
 // LDS fragment reads of the scheduled half-step, as inline assembly with hand-placed waits.
@@ -115,6 +124,17 @@ __device__ __forceinline__ bf16x8 lds_read_tr_pair_at(uint32_t addr) {
     asm volatile("ds_read_b64_tr_b16 %0, %2 offset:%3\n\tds_read_b64_tr_b16 %1, %2 offset:%4"
                  : "=&v"(lo), "=&v"(hi) : "v"(addr), "n"(OFF0), "n"(OFF1));
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+template <int OFF>
+__device__ __forceinline__ bf16x4 lds_read_tr_at(uint32_t addr) {
+    bf16x4 v;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=&v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+// 64-bit half `h` of a fragment
+__device__ __forceinline__ void set_half(bf16x8& f, int h, bf16x4 v) {
+    f = h == 0 ? __builtin_shufflevector(v, __builtin_shufflevector(f, f, 4, 5, 6, 7), 0, 1, 2, 3, 4, 5, 6, 7)
+               : __builtin_shufflevector(__builtin_shufflevector(f, f, 0, 1, 2, 3), v, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 template <int N>
 __device__ __forceinline__ void lds_wait_all_but(bf16x8& frag) {
@@ -161,6 +181,7 @@ struct AttnWave {
     int n, ns, ntiles, nhalf;
     bool ragged;
     uint32_t row_bytes;   // byte stride between sequence positions of K / V in global memory
+    uint32_t wave_lds;    // LDS address of this wave's first 1 KB chunk in tile slot 0 of K
     const byte* K;
     const byte* V;
     const byte* idx;      // int32 column numbers of this head
@@ -201,6 +222,11 @@ struct AttnWave {
     }
 
     // ------------------------------------------------------------------ gathers
+    // byte offset of a 16-byte piece of K/V row `row` from the head's base: both factors are
+    // below 2^24 (checked on the host), so the full-rate 24-bit multiply-add does it
+    __device__ __forceinline__ uint32_t row_offset(int row, uint32_t piece_off) const {
+        return __umul24((uint32_t)row, row_bytes) + piece_off;
+    }
     __device__ __forceinline__ void load_rows(int t, int (&dst)[CH]) const {
         t = t < ntiles ? t : ntiles - 1;          // past the end: repeat the last tile (never read back)
 #pragma unroll
@@ -221,26 +247,27 @@ struct AttnWave {
 #pragma unroll
         for (int i = 0; i < CH; ++i)
             __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(Kg + ((uint32_t)krows[i] * row_bytes + koff[i])),
+                (const __attribute__((address_space(1))) void*)(Kg + row_offset(krows[i], koff[i])),
                 (PULSECOL_LDS void*)(kslot + (wave * CH + i) * 1024), 16, 0, 0);
         if (HAS_V) {
 #pragma unroll
             for (int i = 0; i < CH; ++i)
                 __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void*)(Vg + ((uint32_t)vrows[i] * row_bytes + voff[i])),
+                    (const __attribute__((address_space(1))) void*)(Vg + row_offset(vrows[i], voff[i])),
                     (PULSECOL_LDS void*)(vslot + (wave * CH + i) * 1024), 16, 0, 0);
         }
     }
 
-    __device__ __forceinline__ void issue_k_one(int i, byte* kslot, const int (&krows)[CH]) const {
-        __builtin_amdgcn_global_load_lds(
-            (const __attribute__((address_space(1))) void*)(K + ((uint32_t)krows[i] * row_bytes + koff[i])),
-            (PULSECOL_LDS void*)(kslot + (wave * CH + i) * 1024), 16, 0, 0);
-    }
-    __device__ __forceinline__ void issue_v_one(int i, byte* vslot, const int (&vrows)[CH]) const {
-        __builtin_amdgcn_global_load_lds(
-            (const __attribute__((address_space(1))) void*)(V + ((uint32_t)vrows[i] * row_bytes + voff[i])),
-            (PULSECOL_LDS void*)(vslot + (wave * CH + i) * 1024), 16, 0, 0);
+    // One load of the scheduled half-step, written out so that the instruction order is fixed:
+    // LDS destination into m0, row offset (one VALU instruction, which also covers the wait
+    // state an m0 write needs before its use), load.
+    template <int LDS_OFF>
+    __device__ __forceinline__ void issue_one(const byte* g, int row, uint32_t piece_off) const {
+        uint32_t off;
+        asm volatile("s_add_i32 m0, %1, %2\n\tv_mad_u32_u24 %0, %3, %4, %5\n\tglobal_load_lds_dwordx4 %0, %6"
+                     : "=&v"(off)
+                     : "s"(wave_lds), "n"(LDS_OFF), "v"(row), "s"(row_bytes), "v"(piece_off), "s"(g)
+                     : "memory");   // m0 is written here and by the compiler only right in front of its own uses
     }
 
     // ------------------------------------------------------------------ fragment reads
@@ -281,24 +308,40 @@ struct AttnWave {
     // scaled, shifted logit of value i and takes exp2 of value i-1.  Value e = qb*16 + r.
     struct ExpPipe { float t[32]; float x[32]; float rs[2][2]; };
     __device__ __forceinline__ void exp_tick(int i, const f32x16 (&S)[2], bf16x8 (&P)[2][2], ExpPipe& ep) {
-        if (i >= 2 && i <= 33) {
-            const int e = i - 2, qb = e >> 4, r = e & 15;
-            ep.rs[qb][r & 1] += ep.x[e];            // two partial sums keep the add chains short
-            pin(ep.rs[qb][r & 1]);
-            if (HAS_V && (r & 1)) {
-                P[qb][r >> 3][(r & 7) - 1] = (__bf16)ep.x[e - 1];
-                P[qb][r >> 3][r & 7] = (__bf16)ep.x[e];
-                pin(P[qb][r >> 3]);
-            }
+        // A wave issues in order, one instruction at a time, so every instruction between two
+        // MFMAs counts.  Issue order inside a tick: fma (left to the compiler), then one
+        // assembler statement with add, pack, exp.  The statement names the fma result as an
+        // input so that the fma stays ahead of it: the compiler counts no wait state for an
+        // assembler statement and would otherwise pad every pair of dependent statements (tick
+        // to tick, MFMA to MFMA on one accumulator) with a no-op.  The hazard that does exist
+        // (a transcendental result needs one instruction before its first use) holds by
+        // construction: the exp closes its tick, and an fma or an MFMA opens the next.
+        const bool has_fma = i < 32, has_add = i >= 2 && i <= 33, has_exp = i >= 1 && i <= 32;
+        const int e = has_add ? i - 2 : 0, qb = e >> 4, r = e & 15;
+        const bool has_pack = HAS_V && has_add && (r & 1);
+        const int ti = has_fma ? i : 0, te = has_exp ? i - 1 : 0, xp = has_pack ? e - 1 : 0;
+        uint32_t w = 0;
+        if (has_fma) ep.t[i] = __builtin_fmaf(S[i >> 4][i & 15], c2, -mc[i >> 4]);
+        if (has_add && has_pack && has_exp) {
+            asm volatile("v_add_f32 %0, %0, %3\n\tv_cvt_pk_bf16_f32 %1, %4, %3\n\tv_exp_f32 %2, %5"
+                         : "+v"(ep.rs[qb][r & 1]), "=&v"(w), "=v"(ep.x[te])
+                         : "v"(ep.x[e]), "v"(ep.x[xp]), "v"(ep.t[te]), "v"(ep.t[ti]));
+        } else if (has_add && has_exp) {
+            asm volatile("v_add_f32 %0, %0, %2\n\tv_exp_f32 %1, %3"
+                         : "+v"(ep.rs[qb][r & 1]), "=v"(ep.x[te])
+                         : "v"(ep.x[e]), "v"(ep.t[te]), "v"(ep.t[ti]));
+        } else if (has_add && has_pack) {
+            asm volatile("v_add_f32 %0, %0, %2\n\tv_cvt_pk_bf16_f32 %1, %3, %2"
+                         : "+v"(ep.rs[qb][r & 1]), "=&v"(w)
+                         : "v"(ep.x[e]), "v"(ep.x[xp]));
+        } else if (has_add) {
+            asm volatile("v_add_f32 %0, %0, %1" : "+v"(ep.rs[qb][r & 1]) : "v"(ep.x[e]));
+        } else if (has_exp) {
+            asm volatile("v_exp_f32 %0, %1" : "=v"(ep.x[te]) : "v"(ep.t[te]), "v"(ep.t[ti]));
+        } else if (has_fma) {
+            asm volatile("" : : "v"(ep.t[ti]));
         }
-        if (i < 32) {
-            ep.t[i] = __builtin_fmaf(S[i >> 4][i & 15], c2, -mc[i >> 4]);
-            pin(ep.t[i]);
-        }
-        if (i >= 1 && i <= 32) {      // its input was formed one tick ago, not by the instruction before
-            ep.x[i - 1] = fast_exp2(ep.t[i - 1]);
-            pin(ep.x[i - 1]);
-        }
+        if (has_pack) set_pair(P[qb][r >> 3], (r & 7) >> 1, w);
     }
     __device__ __forceinline__ void exp_begin(ExpPipe& ep) {
         ep.rs[0][0] = ep.rs[0][1] = ep.rs[1][0] = ep.rs[1][1] = 0.f;
@@ -384,25 +427,19 @@ struct AttnWave {
     template <bool HAS_NEXT>
     static constexpr int frag_ops(int q) { return q < KK ? 1 : (q < NP ? 2 : (HAS_NEXT ? 1 : 0)); }
 
-    // What the first half-step of an iteration issues besides its own work: the row numbers of
-    // the tile after next and the direct-to-LDS loads of K(u+3) and V(u+2), one per MFMA pair.
-    struct IssueCtx {
-        byte* kwrite;
-        byte* vwrite;
-        int next_tile;
-    };
-
     // Fast half-step j (1 <= j <= nhalf-4): S_in = S(j), P_in = P(j-1) -> S_out = S(j+1), P_out = P(j).
-    // kv / vv are this lane's LDS addresses of the K fragments (tile slot of S(j+1), first
-    // half) and of the V fragments (tile slot of P(j-1), first half, first row group); KH / VH
-    // select the half.  kpre holds the first AHEAD K fragments, already requested; with
-    // HAS_NEXT it is refilled with requests for the following half-step (addresses knext, half
-    // NKH).  ROLE 0 = first half-step of an iteration (spreads the loads of IssueCtx over its
-    // pairs), ROLE 1 = second (holds the workgroup barrier, see steady_pair).
-    template <int KH, int VH, bool HAS_NEXT, int NKH, int ROLE>
+    // kv / vv are this lane's LDS addresses of its K fragments and V fragments inside slot 0,
+    // first half (V: first row group); KOFF / VOFF select slot and half of the K tile of
+    // S(j+1) and of the V tile of P(j-1).  kpre holds the first AHEAD K fragments, already
+    // requested; with HAS_NEXT it is refilled with requests for the following half-step
+    // (offset NKOFF).  ROLE 0 = first half-step of an iteration: besides its own work it loads
+    // the row numbers of tile next_tile and issues the direct-to-LDS loads of a K and a V tile
+    // (LDS offsets KW / VW from the wave's base), one instruction per MFMA pair.  ROLE 1 =
+    // second half-step: holds the workgroup barrier, see steady_iter.
+    template <int KOFF, int VOFF, bool HAS_NEXT, int NKOFF, int ROLE, int KW, int VW>
     __device__ __forceinline__ void fast_step(const uint32_t (&kv)[KK], const uint32_t (&vv)[ODB],
-                                              const uint32_t (&knext)[AHEAD], bf16x8 (&kpre)[AHEAD],
-                                              const IssueCtx& io, const int (&krows)[CH], const int (&vrows)[CH],
+                                              bf16x8 (&kpre)[AHEAD],
+                                              int next_tile, const int (&krows)[CH], const int (&vrows)[CH],
                                               int (&rows_n)[CH],
                                               f32x16 (&S_in)[2], f32x16 (&S_out)[2],
                                               bf16x8 (&P_in)[2][2], bf16x8 (&P_out)[2][2]) {
@@ -412,60 +449,40 @@ struct AttnWave {
         ExpPipe ep;
         exp_begin(ep);
         fence();
-        fast_pairs<KH, VH, HAS_NEXT, NKH, ROLE>(std::make_integer_sequence<int, NP>{}, kv, vv, knext, fr, ep,
-                                                io, krows, vrows, rows_n, S_in, S_out, P_in, P_out);
+        fast_pairs<KOFF, VOFF, HAS_NEXT, NKOFF, ROLE, KW, VW>(std::make_integer_sequence<int, NP>{}, kv, vv, fr, ep,
+                                                              next_tile, krows, vrows, rows_n, S_in, S_out, P_in, P_out);
         exp_end(ep, S_in, P_out);
         if (HAS_NEXT) {
 #pragma unroll
             for (int i = 0; i < AHEAD; ++i) kpre[i] = fr[NP + i];
         }
     }
-    template <int KH, int VH, bool HAS_NEXT, int NKH, int ROLE, int... Ps>
+    template <int KOFF, int VOFF, bool HAS_NEXT, int NKOFF, int ROLE, int KW, int VW, int... Ps>
     __device__ __forceinline__ void fast_pairs(std::integer_sequence<int, Ps...>,
                                                const uint32_t (&kv)[KK], const uint32_t (&vv)[ODB],
-                                               const uint32_t (&knext)[AHEAD],
                                                bf16x8 (&fr)[NP + AHEAD], ExpPipe& ep,
-                                               const IssueCtx& io, const int (&krows)[CH], const int (&vrows)[CH],
+                                               int next_tile, const int (&krows)[CH], const int (&vrows)[CH],
                                                int (&rows_n)[CH],
                                                f32x16 (&S_in)[2], f32x16 (&S_out)[2],
                                                bf16x8 (&P_in)[2][2], bf16x8 (&P_out)[2][2]) {
-        (fast_pair<Ps, KH, VH, HAS_NEXT, NKH, ROLE>(kv, vv, knext, fr, ep, io, krows, vrows, rows_n,
-                                                    S_in, S_out, P_in, P_out), ...);
+        (fast_pair<Ps, KOFF, VOFF, HAS_NEXT, NKOFF, ROLE, KW, VW>(kv, vv, fr, ep, next_tile, krows, vrows, rows_n,
+                                                                  S_in, S_out, P_in, P_out), ...);
     }
     // MFMA pair P of a fast half-step: two slots that share one A fragment.
-    template <int P, int KH, int VH, bool HAS_NEXT, int NKH, int ROLE>
+    template <int P, int KOFF, int VOFF, bool HAS_NEXT, int NKOFF, int ROLE, int KW, int VW>
     __device__ __forceinline__ void fast_pair(const uint32_t (&kv)[KK], const uint32_t (&vv)[ODB],
-                                              const uint32_t (&knext)[AHEAD],
                                               bf16x8 (&fr)[NP + AHEAD], ExpPipe& ep,
-                                              const IssueCtx& io, const int (&krows)[CH], const int (&vrows)[CH],
+                                              int next_tile, const int (&krows)[CH], const int (&vrows)[CH],
                                               int (&rows_n)[CH],
                                               f32x16 (&S_in)[2], f32x16 (&S_out)[2],
                                               bf16x8 (&P_in)[2][2], bf16x8 (&P_out)[2][2]) {
         static_assert((HAS_V ? 2 : 1) * CH + 1 <= NP, "one load instruction per MFMA pair");
-        if constexpr (ROLE == 0) {
-            if constexpr (P == 0) load_rows(io.next_tile, rows_n);
-            if constexpr (P >= 1 && P <= CH) issue_k_one(P - 1, io.kwrite, krows);
-            if constexpr (HAS_V && P > CH && P <= 2 * CH) issue_v_one(P - CH - 1, io.vwrite, vrows);
-        } else if constexpr (HAS_V && P == KK) {
-            // All K reads of this iteration are complete (their fragments have been consumed).
-            // Everything loaded before this iteration's own loads has landed; after the barrier
-            // the other waves' shares are visible too, and the slots they free may be refilled.
-            wait_vmcnt_at_most<VM_PER_ISSUE>();
-            __builtin_amdgcn_s_barrier();
-        }
-        // request the fragment used AHEAD pairs later
-        constexpr int PA = P + AHEAD;
-        if constexpr (PA < KK) {
-            fr[PA] = lds_read_b128_at<KH * HALF_BYTES>(kv[PA]);
-        } else if constexpr (PA < NP) {
-            constexpr int q = PA - KK, hf = q / ODB, db = q % ODB;
-            fr[PA] = lds_read_tr_pair_at<VH * HALF_BYTES + hf * 16 * ROW_BYTES,
-                                         VH * HALF_BYTES + hf * 16 * ROW_BYTES + 8 * ROW_BYTES>(vv[db]);
-        } else if constexpr (HAS_NEXT) {
-            fr[PA] = lds_read_b128_at<NKH * HALF_BYTES>(knext[PA - NP]);
-        }
+        // Slot layout: MFMA, then the slot's memory and scalar instructions, then its VALU work.
+        // (Measured on gfx950 with one wave per SIMD: the first non-VALU instruction after an
+        // MFMA issues for free, the same instruction in front of the MFMA delays it.)
+        constexpr int PA = P + AHEAD;       // the fragment requested during this pair
         // fragment P has landed once only the requests made after it are outstanding
-        constexpr int NEWER = frag_ops<HAS_NEXT>(P + 1) + frag_ops<HAS_NEXT>(P + 2) + frag_ops<HAS_NEXT>(P + 3);
+        constexpr int NEWER = frag_ops<HAS_NEXT>(P + 1) + frag_ops<HAS_NEXT>(P + 2);
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
             const int s = 2 * P + qb;
@@ -481,6 +498,36 @@ struct AttnWave {
                 constexpr int q = P - KK;
                 if (qb == 0) mfma_pv_after<NEWER>(o_acc[qb][q % ODB], fr[P], P_in[qb][q / ODB]);
                 else mfma_pv(o_acc[qb][q % ODB], fr[P], P_in[qb][q / ODB]);
+            }
+            fence();
+            if (qb == 0) {
+                if constexpr (ROLE == 1 && HAS_V && P == KK) {
+                    // All K reads of this iteration are complete (their fragments have been
+                    // consumed).  Everything loaded before this iteration's own loads has landed;
+                    // after the barrier the other waves' shares are visible too, and the slots
+                    // they free may be refilled.
+                    wait_vmcnt_at_most<VM_PER_ISSUE>();
+                    __builtin_amdgcn_s_barrier();
+                }
+                if constexpr (PA < KK) {
+                    fr[PA] = lds_read_b128_at<KOFF>(kv[PA]);
+                } else if constexpr (PA < NP) {
+                    constexpr int q = PA - KK, hf = q / ODB, db = q % ODB;
+                    set_half(fr[PA], 0, lds_read_tr_at<VOFF + hf * 16 * ROW_BYTES>(vv[db]));
+                } else if constexpr (HAS_NEXT) {
+                    fr[PA] = lds_read_b128_at<NKOFF>(kv[PA - NP]);
+                }
+            } else {
+                if constexpr (PA >= KK && PA < NP) {
+                    constexpr int q = PA - KK, hf = q / ODB, db = q % ODB;
+                    set_half(fr[PA], 1, lds_read_tr_at<VOFF + hf * 16 * ROW_BYTES + 8 * ROW_BYTES>(vv[db]));
+                }
+                if constexpr (ROLE == 0) {
+                    if constexpr (P == 0) load_rows(next_tile, rows_n);
+                    if constexpr (P >= 1 && P <= CH) issue_one<KW + (P - 1) * 1024>(K, krows[P - 1], koff[P - 1]);
+                    if constexpr (HAS_V && P > CH && P <= 2 * CH)
+                        issue_one<VW + (P - CH - 1) * 1024>(V, vrows[P - CH - 1], voff[P - CH - 1]);
+                }
             }
             fence();
             // this slot's share of the VALU work
@@ -501,29 +548,34 @@ struct AttnWave {
             mask_tail(j + 1, S_out);
         }
     }
-    // One steady-state iteration u: half-steps j = 2u+1 and 2u+2, which read K tile u+1
-    // (fragment addresses kv) and V tile u (vv).  The first half-step issues the loads of
-    // K(u+3) and V(u+2); the second one holds the barrier -- placed after its last K read, so
-    // that the slot of K(u+1) is free and K(u+2), V(u+1) are visible -- and then requests the
-    // first K fragments of the next iteration (addresses knext) while its P V MFMAs run.
-    __device__ __forceinline__ void steady_pair(const uint32_t (&kv)[KK], const uint32_t (&vv)[ODB],
-                                                const uint32_t (&knext)[AHEAD], bf16x8 (&kpre)[AHEAD],
-                                                const IssueCtx& io, const int (&krows)[CH], const int (&vrows)[CH],
-                                                int (&rows_n)[CH],
+    // One steady-state iteration u (U4 = u % NBUF): half-steps j = 2u+1 and 2u+2, which read K
+    // tile u+1 and V tile u.  The first half-step issues the loads of K(u+3) and V(u+2); the
+    // second one holds the barrier -- placed after its last K read, so that K(u+2), V(u+1) are
+    // visible to every wave before anything reads them -- and then requests the first K
+    // fragments of the next iteration while its P V MFMAs run.
+    template <int U4>
+    __device__ __forceinline__ void steady_iter(const uint32_t (&kv)[KK], const uint32_t (&vv)[ODB],
+                                                bf16x8 (&kpre)[AHEAD], int next_tile,
+                                                const int (&krows)[CH], const int (&vrows)[CH], int (&rows_n)[CH],
                                                 f32x16 (&SA)[2], f32x16 (&SB)[2],
                                                 bf16x8 (&PA)[2][2], bf16x8 (&PB)[2][2]) {
         static_assert(AHEAD == 3 && KK >= AHEAD, "the hand-placed LDS waits assume this look-ahead");
-        const uint32_t ksame[AHEAD] = {kv[0], kv[1], kv[2]};
+        constexpr int KR = (U4 + 1) % NBUF * TILE_BYTES;        // K(u+1)
+        constexpr int VR = U4 * TILE_BYTES;                     // V(u)
+        constexpr int KN = (U4 + 2) % NBUF * TILE_BYTES;        // K(u+2)
+        constexpr int KW = (U4 + 3) % NBUF * TILE_BYTES;        // K(u+3), from the wave's chunk base
+        constexpr int VW = (NBUF + (U4 + 2) % NBUF) * TILE_BYTES;   // V(u+2), the V slots follow the K slots
         // odd:  S(j) in SB, P(j-1) in PA -> S(j+1) in SA, P(j) in PB
-        fast_step<0, 0, true, 1, 0>(kv, vv, ksame, kpre, io, krows, vrows, rows_n, SB, SA, PA, PB);
+        fast_step<KR, VR, true, KR + HALF_BYTES, 0, KW, VW>(kv, vv, kpre, next_tile, krows, vrows, rows_n, SB, SA, PA, PB);
         // even: S(j) in SA, P(j-1) in PB -> S(j+1) in SB, P(j) in PA
-        fast_step<1, 1, HAS_V, 0, 1>(kv, vv, knext, kpre, io, krows, vrows, rows_n, SA, SB, PB, PA);
+        fast_step<KR + HALF_BYTES, VR + HALF_BYTES, HAS_V, KN, 1, KW, VW>(kv, vv, kpre, next_tile, krows, vrows, rows_n,
+                                                                         SA, SB, PB, PA);
         if (!HAS_V) {
             // row pass: no P V stream to cover the barrier; synchronise at the end of the iteration
             wait_vmcnt_at_most<VM_PER_ISSUE>();
             __builtin_amdgcn_s_barrier();
 #pragma unroll
-            for (int i = 0; i < AHEAD; ++i) kpre[i] = lds_read_b128_at<0>(knext[i]);
+            for (int i = 0; i < AHEAD; ++i) kpre[i] = lds_read_b128_at<KN>(kv[i]);
         }
     }
 };
@@ -564,6 +616,7 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     w.nhalf = 2 * w.ntiles;
     w.ragged = (p.ns & (BN - 1)) != 0;
     w.row_bytes = (uint32_t)p.td.sn * 2u;
+    w.wave_lds = __builtin_amdgcn_readfirstlane(lds_address(lds_k) + w.wave * CH * 1024);
     w.K = (const byte*)((const __bf16*)p.k + head_off);
     w.V = HAS_V ? (const byte*)((const __bf16*)p.v + head_off) : nullptr;
     w.idx = W::GATHER ? (const byte*)(p.idx + (int64_t)bh * p.ns) : nullptr;
@@ -599,7 +652,7 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     // ---- prologue: tiles 0..2 of K and V into their slots; then rows_k = tile 3, rows_v = tile 2
     int rows_k[CH], rows_v[CH], rows_n[CH];
 #pragma unroll 1
-    for (int t = 0; t < NBUF_K; ++t) {
+    for (int t = 0; t < PRO_TILES; ++t) {
         w.load_rows(t, rows_k);
         w.issue_tile(lds_k + t * TILE_BYTES, lds_v + (HAS_V ? t * TILE_BYTES : 0), w.K, w.V, rows_k, rows_k);
     }
@@ -627,36 +680,30 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     const int npairs = nhalf >= 4 ? (nhalf - 4) / 2 : 0;
     if (npairs > 0) {
         const uint32_t kbase = lds_address(lds_k), vbase = lds_address(lds_v);
-        int kr = 1, vr = 0;            // slot of K tile u+1 / of V tile u
-        uint32_t kv[KK], vv[ODB], knext[AHEAD];
+        uint32_t kv[KK], vv[ODB];      // fragment addresses inside slot 0; slots and halves are immediates
         bf16x8 kpre[AHEAD];
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) kv[kk] = kbase + kr * TILE_BYTES + w.kaddr[kk];
+        for (int kk = 0; kk < KK; ++kk) kv[kk] = kbase + w.kaddr[kk];
 #pragma unroll
-        for (int db = 0; db < ODB; ++db) vv[db] = vbase + vr * TILE_BYTES + w.vaddr[db];
+        for (int db = 0; db < ODB; ++db) vv[db] = vbase + w.vaddr[db];
 #pragma unroll
-        for (int i = 0; i < AHEAD; ++i) kpre[i] = lds_read_b128_at<0>(kv[i]);
-        for (int u = 0; u < npairs; ++u) {
-            const int kr_next = kr == NBUF_K - 1 ? 0 : kr + 1;
-            const int vr_next = vr == NBUF_V - 1 ? 0 : vr + 1;
-            const int kw = kr_next == NBUF_K - 1 ? 0 : kr_next + 1;      // K(u+3) -> slot (u+3) % 3
-            const int vw = vr_next == NBUF_V - 1 ? 0 : vr_next + 1;      // V(u+2) -> slot (u+2) % 4
-            typename W::IssueCtx io;
-            io.kwrite = lds_k + kw * TILE_BYTES;
-            io.vwrite = lds_v + (HAS_V ? vw * TILE_BYTES : 0);
-            io.next_tile = u + 4;
+        for (int i = 0; i < AHEAD; ++i) kpre[i] = lds_read_b128_at<TILE_BYTES>(kv[i]);     // K tile 1
+        // rows_k / rows_v / rows_n rotate by name: after an iteration, v <- k <- n
+        int u = 0;
+        for (; u + NBUF <= npairs; u += NBUF) {
+            w.template steady_iter<0>(kv, vv, kpre, u + 4, rows_k, rows_v, rows_n, SA, SB, PA, PB);
+            w.template steady_iter<1>(kv, vv, kpre, u + 5, rows_n, rows_k, rows_v, SA, SB, PA, PB);
+            w.template steady_iter<2>(kv, vv, kpre, u + 6, rows_v, rows_n, rows_k, SA, SB, PA, PB);
+            w.template steady_iter<3>(kv, vv, kpre, u + 7, rows_k, rows_v, rows_n, SA, SB, PA, PB);
 #pragma unroll
-            for (int i = 0; i < AHEAD; ++i) knext[i] = kbase + kr_next * TILE_BYTES + w.kaddr[i];
-            w.steady_pair(kv, vv, knext, kpre, io, rows_k, rows_v, rows_n, SA, SB, PA, PB);
-#pragma unroll
-            for (int i = 0; i < CH; ++i) { rows_v[i] = rows_k[i]; rows_k[i] = rows_n[i]; }
-            kr = kr_next;
-            vr = vr_next;
-#pragma unroll
-            for (int kk = 0; kk < KK; ++kk) kv[kk] = kbase + kr * TILE_BYTES + w.kaddr[kk];
-#pragma unroll
-            for (int db = 0; db < ODB; ++db) vv[db] = vbase + vr * TILE_BYTES + w.vaddr[db];
+            for (int i = 0; i < CH; ++i) { const int t = rows_n[i]; rows_n[i] = rows_v[i]; rows_v[i] = rows_k[i]; rows_k[i] = t; }
         }
+        if (u < npairs) w.template steady_iter<0>(kv, vv, kpre, u + 4, rows_k, rows_v, rows_n, SA, SB, PA, PB);
+        if (u + 1 < npairs) w.template steady_iter<1>(kv, vv, kpre, u + 5, rows_n, rows_k, rows_v, SA, SB, PA, PB);
+        if (u + 2 < npairs) w.template steady_iter<2>(kv, vv, kpre, u + 6, rows_v, rows_n, rows_k, SA, SB, PA, PB);
+        // The last iteration has requested fragments for a next one that does not exist: their
+        // registers must stay reserved until the data has arrived.
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kpre[0]), "+v"(kpre[1]), "+v"(kpre[2]));
     }
     // ---- tail: the remaining half-steps (at most three), then the last P V product
     wait_vmcnt_at_most<0>();

@@ -62,6 +62,7 @@ pulsecol_status check_shape(const pulsecol_shape* s, std::string* why) {
         const int64_t sn = s->stride_n ? s->stride_n : s->head_dim;
         const int64_t esize = s->dtype == PULSECOL_BF16 ? 2 : 4;
         if ((int64_t)s->seq * sn * esize >= ((int64_t)1 << 32)) { *why = "seq * stride_n exceeds 4 GiB per head"; return PULSECOL_ERR_UNSUPPORTED; }
+        if (s->seq >= (1 << 24) || sn * esize >= (1 << 24)) { *why = "seq or the row stride in bytes reaches 2^24"; return PULSECOL_ERR_UNSUPPORTED; }
     }
     const int a = elem_align(s->dtype);
     if (s->stride_b % a || s->stride_h % a || s->stride_n % a) { *why = "strides must be multiples of 16 bytes"; return PULSECOL_ERR_ALIGNMENT; }
