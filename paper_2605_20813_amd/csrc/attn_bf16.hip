@@ -195,9 +195,11 @@ struct AttnWave {
     uint32_t kaddr[KK];   // LDS byte offset (inside a tile slot, first half) of this lane's K fragment kk
     uint32_t vaddr[ODB];  // same for the first 4-row group of the V fragment of d-block db
     int lrow;
+    uint32_t lane_rows_off;   // byte offset, inside a tile's 64 column numbers, of this lane's CH consecutive ones
 
     __device__ __forceinline__ void init_addresses() {
         lrow = lane / PIECES;
+        lane_rows_off = (uint32_t)(wave * 16 + lrow * CH) * 4u;
         const int lslot = lane % PIECES;
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
@@ -227,14 +229,39 @@ struct AttnWave {
     __device__ __forceinline__ uint32_t row_offset(int row, uint32_t piece_off) const {
         return __umul24((uint32_t)row, row_bytes) + piece_off;
     }
+    // Which sequence position goes where: load instruction i of a wave fills LDS tile row
+    // (wave*CH + i)*ROWS_PER_CHUNK + lrow, and it takes position wave*16 + lrow*CH + i of the
+    // tile's 64 (K and V alike, so scores and values still meet; only tail masking has to know).
+    // A lane's CH positions are then consecutive and their row numbers come with one load.
     __device__ __forceinline__ void load_rows(int t, int (&dst)[CH]) const {
+        static_assert(CH * ROWS_PER_CHUNK == 16, "a wave fills 16 rows of a tile");
         t = t < ntiles ? t : ntiles - 1;          // past the end: repeat the last tile (never read back)
+        const bool whole = (t + 1) * BN <= ns;    // the tile lies inside the pattern (uniform)
+        if (GATHER) {
+            const uint32_t off = (uint32_t)(t * (BN * 4)) + lane_rows_off;
+            if (__builtin_expect(whole, 1)) {
+                typedef int rows_t __attribute__((ext_vector_type(CH), aligned(4)));
+                const rows_t r = *(const rows_t*)(idx + off);
 #pragma unroll
-        for (int i = 0; i < CH; ++i) {
-            int pos = t * BN + (wave * CH + i) * ROWS_PER_CHUNK + lrow;
-            pos = pos < ns ? pos : ns - 1;        // ragged tail: any valid row; masked later
-            dst[i] = GATHER ? *(const int*)(idx + (uint32_t)pos * 4u) : pos;
+                for (int i = 0; i < CH; ++i) dst[i] = r[i];
+            }
+            if (__builtin_expect(!whole, 0)) {
+#pragma unroll
+                for (int i = 0; i < CH; ++i) {
+                    uint32_t o = off + 4u * i;    // ragged tail: any valid row; masked later
+                    o = o < (uint32_t)ns * 4u ? o : (uint32_t)ns * 4u - 4u;
+                    dst[i] = *(const int*)(idx + o);
+                }
+            }
+        } else {
+            const int base = t * BN + wave * 16 + lrow * CH;
+#pragma unroll
+            for (int i = 0; i < CH; ++i) dst[i] = base + i < ns ? base + i : ns - 1;
         }
+    }
+    // position inside its tile of the key in LDS tile row `row`
+    static __device__ __forceinline__ int tile_pos(int row) {
+        return (row & ~15) + (row % ROWS_PER_CHUNK) * CH + (row & 15) / ROWS_PER_CHUNK;
     }
     // Load instruction i of a wave fills the 1 KB chunk cid = wave*CH + i of a tile slot: lane L
     // lands at chunk byte 16*L, i.e. tile row cid*ROWS_PER_CHUNK + L/PIECES, LDS piece L%PIECES,
@@ -287,10 +314,10 @@ struct AttnWave {
     // columns of the last tile that lie past ns get weight zero
     __device__ __forceinline__ void mask_tail(int j, f32x16 (&S)[2]) const {
         if (ragged && j >= nhalf - 2) {
-            const int valid = ns - (j >> 1) * BN - (j & 1) * 32;
+            const int valid = ns - (j >> 1) * BN;
 #pragma unroll
             for (int r = 0; r < 16; ++r)
-                if (acc_row(r, lh) >= valid) { S[0][r] = -INFINITY; S[1][r] = -INFINITY; }
+                if (tile_pos((j & 1) * 32 + acc_row(r, lh)) >= valid) { S[0][r] = -INFINITY; S[1][r] = -INFINITY; }
         }
     }
     // maximum over this lane's 16 values and the 16 of the lane that shares its query column
@@ -306,7 +333,7 @@ struct AttnWave {
     // P = exp2(S*c2 - mc) in EXP_TICKS small steps that can be spread over MFMA slots: tick i
     // adds value i-2 to the fp32 row sum (packing a bf16 pair after every odd value), forms the
     // scaled, shifted logit of value i and takes exp2 of value i-1.  Value e = qb*16 + r.
-    struct ExpPipe { float t[32]; float x[32]; float rs[2][2]; };
+    struct ExpPipe { float t[32]; float x[32]; float rs[2]; };
     __device__ __forceinline__ void exp_tick(int i, const f32x16 (&S)[2], bf16x8 (&P)[2][2], ExpPipe& ep) {
         // A wave issues in order, one instruction at a time, so every instruction between two
         // MFMAs counts.  Issue order inside a tick: fma (left to the compiler), then one
@@ -316,47 +343,53 @@ struct AttnWave {
         // to tick, MFMA to MFMA on one accumulator) with a no-op.  The hazard that does exist
         // (a transcendental result needs one instruction before its first use) holds by
         // construction: the exp closes its tick, and an fma or an MFMA opens the next.
-        const bool has_fma = i < 32, has_add = i >= 2 && i <= 33, has_exp = i >= 1 && i <= 32;
-        const int e = has_add ? i - 2 : 0, qb = e >> 4, r = e & 15;
-        const bool has_pack = HAS_V && has_add && (r & 1);
+        const bool has_fma = i < 32, has_val = i >= 2 && i <= 33, has_exp = i >= 1 && i <= 32;
+        const int e = has_val ? i - 2 : 0, qb = e >> 4, r = e & 15;
+        // value 0 of a query block opens its row sum (no instruction), value 1 is packed with it
+        // straight out of the sum's register
+        const bool has_add = has_val && r > 0, first_pack = HAS_V && has_val && r == 1;
+        const bool has_pack = HAS_V && has_val && (r & 1) && r > 1;
         const int ti = has_fma ? i : 0, te = has_exp ? i - 1 : 0, xp = has_pack ? e - 1 : 0;
         uint32_t w = 0;
         if (has_fma) ep.t[i] = __builtin_fmaf(S[i >> 4][i & 15], c2, -mc[i >> 4]);
-        if (has_add && has_pack && has_exp) {
+        if (has_val && r == 0) ep.rs[qb] = ep.x[e];
+        if (first_pack) {
+            asm volatile("v_cvt_pk_bf16_f32 %1, %0, %3\n\tv_add_f32 %0, %0, %3\n\tv_exp_f32 %2, %4"
+                         : "+v"(ep.rs[qb]), "=&v"(w), "=v"(ep.x[te])
+                         : "v"(ep.x[e]), "v"(ep.t[te]), "v"(ep.t[ti]));
+        } else if (has_add && has_pack && has_exp) {
             asm volatile("v_add_f32 %0, %0, %3\n\tv_cvt_pk_bf16_f32 %1, %4, %3\n\tv_exp_f32 %2, %5"
-                         : "+v"(ep.rs[qb][r & 1]), "=&v"(w), "=v"(ep.x[te])
+                         : "+v"(ep.rs[qb]), "=&v"(w), "=v"(ep.x[te])
                          : "v"(ep.x[e]), "v"(ep.x[xp]), "v"(ep.t[te]), "v"(ep.t[ti]));
         } else if (has_add && has_exp) {
             asm volatile("v_add_f32 %0, %0, %2\n\tv_exp_f32 %1, %3"
-                         : "+v"(ep.rs[qb][r & 1]), "=v"(ep.x[te])
+                         : "+v"(ep.rs[qb]), "=v"(ep.x[te])
                          : "v"(ep.x[e]), "v"(ep.t[te]), "v"(ep.t[ti]));
         } else if (has_add && has_pack) {
             asm volatile("v_add_f32 %0, %0, %2\n\tv_cvt_pk_bf16_f32 %1, %3, %2"
-                         : "+v"(ep.rs[qb][r & 1]), "=&v"(w)
+                         : "+v"(ep.rs[qb]), "=&v"(w)
                          : "v"(ep.x[e]), "v"(ep.x[xp]));
         } else if (has_add) {
-            asm volatile("v_add_f32 %0, %0, %1" : "+v"(ep.rs[qb][r & 1]) : "v"(ep.x[e]));
+            asm volatile("v_add_f32 %0, %0, %1" : "+v"(ep.rs[qb]) : "v"(ep.x[e]));
         } else if (has_exp) {
             asm volatile("v_exp_f32 %0, %1" : "=v"(ep.x[te]) : "v"(ep.t[te]), "v"(ep.t[ti]));
         } else if (has_fma) {
             asm volatile("" : : "v"(ep.t[ti]));
         }
-        if (has_pack) set_pair(P[qb][r >> 3], (r & 7) >> 1, w);
+        if (has_pack || first_pack) set_pair(P[qb][r >> 3], (r & 7) >> 1, w);
     }
     __device__ __forceinline__ void exp_begin(ExpPipe& ep) {
-        ep.rs[0][0] = ep.rs[0][1] = ep.rs[1][0] = ep.rs[1][1] = 0.f;
+        ep.rs[0] = ep.rs[1] = 0.f;
     }
     // Close a half-tile: accept the row sums, or -- if some lane's sum says that its weights
     // outgrew the reference (or is not a number: first half-tile, reference still -inf) -- fix
     // the reference first.  Every MFMA that adds P(j-1) to the accumulator has been issued.
     __device__ __forceinline__ void exp_end(ExpPipe& ep, const f32x16 (&S)[2], bf16x8 (&P)[2][2]) {
         const float limit = __builtin_amdgcn_exp2f(kTau);
-        ep.rs[0][0] += ep.rs[0][1];
-        ep.rs[1][0] += ep.rs[1][1];
-        const bool bad = !(ep.rs[0][0] <= limit) || !(ep.rs[1][0] <= limit);
+        const bool bad = !(ep.rs[0] <= limit) || !(ep.rs[1] <= limit);
         if (__builtin_expect(__ballot(bad) != 0ull, 0)) fix_reference(ep, S, P);
-        l_run[0] += ep.rs[0][0];
-        l_run[1] += ep.rs[1][0];
+        l_run[0] += ep.rs[0];
+        l_run[1] += ep.rs[1];
     }
     // Slow path: true maximum of the half-tile per query, reference moved up by a whole number
     // of log2 units, l and the accumulator scaled by that exact power of two, P recomputed.
@@ -389,7 +422,7 @@ struct AttnWave {
                         P[qb][r >> 3][(r & 7) + 1] = (__bf16)x1;
                     }
                 }
-                ep.rs[qb][0] = rs;
+                ep.rs[qb] = rs;
             }
         }
     }
