@@ -64,12 +64,14 @@ typedef enum { PULSECOL_BF16 = 0, PULSECOL_F32 = 1 } pulsecol_dtype;
 typedef struct {
     int32_t batch;      /* >= 1 */
     int32_t heads;      /* >= 1 (multi-head attention: K and V have as many heads as Q)          */
-    int32_t seq;        /* n >= 1                                                               */
+    int32_t seq;        /* n >= 1; bf16: n < 2^24                                                */
     int32_t head_dim;   /* d_h: 64 or 128                                                        */
     int32_t dtype;      /* pulsecol_dtype: storage type of Q, K, V, O.  bf16: bf16 MFMA with fp32 */
                         /* accumulation and fp32 softmax; f32: fp32 throughout.                  */
     int32_t group_size; /* queries per group (Sec. 3.3); 0 = the whole head is one group (U = 1) */
-    int64_t stride_b;   /* element strides of batch, head and sequence; 0 = packed               */
+    int64_t stride_b;   /* element strides of batch, head and sequence; 0 = packed.  Multiples of 16 bytes;
+                         * bf16: the sequence stride is below 2^24 bytes and one head spans less than
+                         * 4 GiB (seq * stride_n), else PULSECOL_ERR_UNSUPPORTED                  */
     int64_t stride_h;
     int64_t stride_n;
     float scale;        /* logit scale; 0 = 1/sqrt(head_dim) (Sec. 3.1, logits equation)         */

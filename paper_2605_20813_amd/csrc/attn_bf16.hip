@@ -458,6 +458,12 @@ struct AttnWave {
     // LDS operations that the read of fragment q of a scheduled half-step issues: one for a K
     // fragment (q < KK, or q >= NP: the next half-step's first K fragments), two for a V fragment.
     template <bool HAS_NEXT>
+    static constexpr int newer_ops(int p) {
+        int c = 0;
+        for (int i = 1; i < AHEAD; ++i) c += frag_ops<HAS_NEXT>(p + i);
+        return c;
+    }
+    template <bool HAS_NEXT>
     static constexpr int frag_ops(int q) { return q < KK ? 1 : (q < NP ? 2 : (HAS_NEXT ? 1 : 0)); }
 
     // Fast half-step j (1 <= j <= nhalf-4): S_in = S(j), P_in = P(j-1) -> S_out = S(j+1), P_out = P(j).
@@ -515,7 +521,7 @@ struct AttnWave {
         // MFMA issues for free, the same instruction in front of the MFMA delays it.)
         constexpr int PA = P + AHEAD;       // the fragment requested during this pair
         // fragment P has landed once only the requests made after it are outstanding
-        constexpr int NEWER = frag_ops<HAS_NEXT>(P + 1) + frag_ops<HAS_NEXT>(P + 2);
+        constexpr int NEWER = newer_ops<HAS_NEXT>(P);
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
             const int s = 2 * P + qb;
@@ -592,7 +598,7 @@ struct AttnWave {
                                                 const int (&krows)[CH], const int (&vrows)[CH], int (&rows_n)[CH],
                                                 f32x16 (&SA)[2], f32x16 (&SB)[2],
                                                 bf16x8 (&PA)[2][2], bf16x8 (&PB)[2][2]) {
-        static_assert(AHEAD == 3 && KK >= AHEAD, "the hand-placed LDS waits assume this look-ahead");
+        static_assert(KK >= AHEAD, "the first fragments of a half-step are K fragments");
         constexpr int KR = (U4 + 1) % NBUF * TILE_BYTES;        // K(u+1)
         constexpr int VR = U4 * TILE_BYTES;                     // V(u)
         constexpr int KN = (U4 + 2) % NBUF * TILE_BYTES;        // K(u+2)
@@ -736,6 +742,7 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
         if (u + 2 < npairs) w.template steady_iter<2>(kv, vv, kpre, u + 6, rows_v, rows_n, rows_k, SA, SB, PA, PB);
         // The last iteration has requested fragments for a next one that does not exist: their
         // registers must stay reserved until the data has arrived.
+        static_assert(AHEAD == 3, "one operand per prefetched fragment");
         asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kpre[0]), "+v"(kpre[1]), "+v"(kpre[2]));
     }
     // ---- tail: the remaining half-steps (at most three), then the last P V product
