@@ -38,6 +38,9 @@ def parse():
     ap.add_argument("--cpu-rows", type=int, default=32768,
                     help="query rows of one head the CPU oracle is timed on (in calls of 2048 rows)")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-probes", action="store_true", help="skip the MFMA-only / copy roofline probes")
+    ap.add_argument("--cold-steps", type=int, default=8,
+                    help="extra attention launches timed with a 1 GiB buffer overwritten before each (caches evicted)")
     ap.add_argument("--copy-gib", type=float, default=0.0,
                     help="also launch one plain device copy of this many GiB (the known-size kernel that "
                          "calibrates the FETCH_SIZE / WRITE_SIZE counters in a rocprofv3 --pmc run)")
@@ -104,7 +107,26 @@ def main():
     t1 = time.perf_counter()
     total_ms = (t1 - t0) * 1e3
     ms_per_step = total_ms / steps
-    attn_ms = sum(e0.elapsed_time(e1) for e0, e1 in events) / len(events)
+    per_launch = sorted(e0.elapsed_time(e1) for e0, e1 in events)
+    attn_ms = sum(per_launch) / len(per_launch)
+    attn_ms_median = per_launch[len(per_launch) // 2]
+    attn_ms_min = per_launch[0]
+
+    # ---- cold regime: L2 and the 256 MB memory-side cache evicted before every launch
+    attn_ms_cold = None
+    if a.cold_steps > 0:
+        flush = torch.empty(2**30 // 4, dtype=torch.float32, device=dev)
+        cold = []
+        for _ in range(a.cold_steps):
+            flush.fill_(1.0)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            ctx.attn(Q, K, V, idx, O=O)
+            e1.record()
+            cold.append((e0, e1))
+        torch.cuda.synchronize()
+        attn_ms_cold = sum(e0.elapsed_time(e1) for e0, e1 in cold) / len(cold)
+        del flush
 
     # ---- the pieces, each timed alone with events on the launch stream
     def timed(fn, reps):
@@ -147,6 +169,9 @@ def main():
         "config": {"workload": w.name, "batch": B, "heads": H, "seq": n, "head_dim": d, "keep_ratio": keep,
                    "k": k, "refresh_steps": refresh, "block_m": block_m, "block_n": block_n},
         "attn_ms": round(attn_ms, 4),
+        "attn_ms_median": round(attn_ms_median, 4),
+        "attn_ms_min": round(attn_ms_min, 4),
+        "attn_ms_cold": None if attn_ms_cold is None else round(attn_ms_cold, 4),
         "select_ms": round(select_ms, 4),
         "topk_ms": round(topk_ms, 4),
         "dense_ms": None if dense_ms is None else round(dense_ms, 4),
@@ -162,10 +187,31 @@ def main():
         "paper_context": "paper: 1.95x end-to-end over FlashAttention at 64K/1024 steps, keep 20%, whole model, RTX PRO 6000",
     }
 
+    if not a.no_probes:
+        out["probes"] = roofline_probes(achieved, dense_ms and dense_flop / (dense_ms * 1e-3) * 1e-12)
     if not a.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w, Qh, Kh, Vh, k, a.cpu_rows)
     print(json.dumps(out), flush=True)
     ctx.close()
+
+
+def roofline_probes(kept_tflops, dense_tflops):
+    """What the simplest kernels reach on this machine (stand-alone program, child process): an
+    MFMA-only loop with constant and with random operands, and a 1 GiB copy."""
+    import subprocess
+    exe = os.path.join(ROOT, "paper_2605_20813_amd", "roofline_probe")
+    if not os.path.exists(exe):
+        return {"error": "paper_2605_20813_amd/roofline_probe is not built"}
+    try:
+        r = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, timeout=120)
+        p = json.loads(r.stdout.strip().splitlines()[-1])
+    except Exception as e:       # a probe that does not run is reported, it never stops the benchmark
+        return {"error": f"{type(e).__name__}: {e}"}
+    ceil = p["mfma_only_tflops_random_operands"]
+    p["attn_frac_of_mfma_only_random_operands"] = round(kept_tflops / ceil, 4)
+    if dense_tflops:
+        p["dense_frac_of_mfma_only_random_operands"] = round(dense_tflops / ceil, 4)
+    return p
 
 
 def cpu_baseline(w, Qh, Kh, Vh, k, rows):

@@ -1,4 +1,5 @@
-"""Compile csrc/*.hip for gfx950 and link libpulsecol.so next to this file.
+"""Compile csrc/*.hip for gfx950 and link libpulsecol.so next to this file (plus the
+stand-alone probe/roofline_probe).
 
 Usage: ``python -m paper_2605_20813_amd.build`` (cross-compiles without a GPU).
 """
@@ -16,6 +17,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libpulsecol.so")
+PROBE_SRC = os.path.join(HERE, "probe", "roofline_probe.hip")
+PROBE_PATH = os.path.join(HERE, "roofline_probe")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
@@ -60,6 +63,9 @@ def build(verbose: bool = False) -> str:
             if verbose and out.strip():
                 print(out)
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH, *objs])
+    # the stand-alone roofline probe that bench.py starts as a child process
+    _run([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+          "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-o", PROBE_PATH, PROBE_SRC])
     return LIB_PATH
 
 
