@@ -39,6 +39,7 @@ def parse():
                     help="query rows of one head the CPU oracle is timed on (in calls of 2048 rows)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-probes", action="store_true", help="skip the MFMA-only / copy roofline probes")
+    ap.add_argument("--no-32k", action="store_true", help="skip the short side measurement at 32K context")
     ap.add_argument("--cold-steps", type=int, default=8,
                     help="extra attention launches timed with a 1 GiB buffer overwritten before each (caches evicted)")
     ap.add_argument("--copy-gib", type=float, default=0.0,
@@ -143,7 +144,11 @@ def main():
     select_ms = timed(lambda: ctx.select(Q, K, keep, refresh=True, idx_out=idx), 2)
     scores = torch.empty(B, H, 1, n, dtype=torch.float32, device=dev)
     ctx.scores(Q, K, scores_out=scores)
+    scores_ms = timed(lambda: ctx.scores(Q, K, scores_out=scores), 2)
     topk_ms = timed(lambda: ctx.topk(scores, k, idx_out=idx), 5)
+    # top-k is the memory-bound stage of select: four histogram passes and one compaction pass
+    # over the fp32 score rows, k int32 indices written
+    topk_bytes = B * H * (5 * 4 * n + 4 * k)
     dense_ms = timed(lambda: ctx.attn_dense(Q, K, V, O=O), a.dense_steps) if a.dense_steps > 0 else None
     ctx.select(Q, K, keep, refresh=True, idx_out=idx)
     torch.cuda.synchronize()
@@ -173,7 +178,9 @@ def main():
         "attn_ms_min": round(attn_ms_min, 4),
         "attn_ms_cold": None if attn_ms_cold is None else round(attn_ms_cold, 4),
         "select_ms": round(select_ms, 4),
+        "scores_ms": round(scores_ms, 4),
         "topk_ms": round(topk_ms, 4),
+        "topk_gbps": round(topk_bytes / (topk_ms * 1e-3) * 1e-9, 1),
         "dense_ms": None if dense_ms is None else round(dense_ms, 4),
         "speedup_vs_dense": None if dense_ms is None else round(dense_ms / ms_per_step, 3),
         "kept_tflops": round(achieved, 2),
@@ -187,12 +194,50 @@ def main():
         "paper_context": "paper: 1.95x end-to-end over FlashAttention at 64K/1024 steps, keep 20%, whole model, RTX PRO 6000",
     }
 
+    ctx.close()
+    del Q, K, V, O, scores, idx
+    torch.cuda.empty_cache()
+    if not a.no_32k and a.workload == "llada_64k":
+        out["context_32k"] = side_config(pc, wl, torch, dev, "llada_32k")
     if not a.no_probes:
         out["probes"] = roofline_probes(achieved, dense_ms and dense_flop / (dense_ms * 1e-3) * 1e-12)
     if not a.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w, Qh, Kh, Vh, k, a.cpu_rows)
     print(json.dumps(out), flush=True)
+
+
+def side_config(pc, wl, torch, dev, name):
+    """The same kernels at the other context length the metric names: per keep ratio the
+    column-sparse attention launch alone (20 launches), beside one select and the dense launch."""
+    w = wl.WORKLOADS[name]
+    B, H, n, d = w.batch, w.heads, w.seq, w.head_dim
+    Q, K, V = (t.to(dev) for t in wl.make_qkv(w))
+    O = torch.empty_like(Q)
+    ctx = pc.Context(B, H, n, d, w.torch_dtype)
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    res = {"workload": name, "seq": n, "dense_ms": round(timed(lambda: ctx.attn_dense(Q, K, V, O=O), 4), 4), "keep": {}}
+    res["dense_kernel_tflops"] = round(4.0 * B * H * float(n) * n * d / (res["dense_ms"] * 1e-3) * 1e-12, 2)
+    for keep in w.keep_ratios:
+        k = pc.num_keep(n, keep)
+        idx = torch.empty(B, H, 1, k, dtype=torch.int32, device=dev)
+        select_ms = timed(lambda: ctx.select(Q, K, keep, refresh=True, idx_out=idx), 1)
+        attn_ms = timed(lambda: ctx.attn(Q, K, V, idx, O=O), 20)
+        res["keep"][str(keep)] = {"k": k, "attn_ms": round(attn_ms, 4), "select_ms": round(select_ms, 4),
+                                  "kept_tflops": round(4.0 * B * H * n * k * d / (attn_ms * 1e-3) * 1e-12, 2),
+                                  "speedup_vs_dense_launch": round(res["dense_ms"] / attn_ms, 2)}
     ctx.close()
+    return res
 
 
 def roofline_probes(kept_tflops, dense_tflops):
