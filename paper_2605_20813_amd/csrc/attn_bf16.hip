@@ -760,16 +760,28 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     }
     w.pv_all(lds_v + (HAS_V ? (((nhalf - 1) >> 1) % NBUF_V) * TILE_BYTES : 0), (nhalf - 1) & 1, PB);
 
-    // ---- epilogue: O = diag(l)^-1 acc, optional row log-sum-exp
+    // ---- epilogue: O = diag(l)^-1 acc, optional row log-sum-exp.
+    // In the accumulator a lane holds one query row in 8-byte runs: stored directly, every
+    // instruction would touch 64 different rows.  Each wave turns its 64 x D tile around in
+    // its own piece of LDS (16-byte pieces XOR-swizzled by row against bank conflicts) and
+    // writes whole rows, 16 bytes per lane.
     if (HAS_V) mfma_settle_acc(w.o_acc);
+    float l_tot[2];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
-        const float l_tot = half_sum(w.l_run[qb]);
+        l_tot[qb] = half_sum(w.l_run[qb]);
         const int row = q0 + qb * 32 + w.lq;
-        if (row >= n) continue;
-        if (HAS_V) {
-            const float inv = 1.0f / l_tot;
-            __bf16* dst = (__bf16*)p.o + head_off + (int64_t)row * p.td.sn;
+        if (p.lse != nullptr && w.lh == 0 && row < n)
+            p.lse[(int64_t)bh * n + row] = (w.mc[qb] + fast_log2(l_tot[qb])) * (p.lse_base2 ? 1.0f : kLn2);
+    }
+    if (HAS_V) {
+        constexpr int PIECES = W::PIECES, ROW_BYTES = W::ROW_BYTES, RPC = W::ROWS_PER_CHUNK;
+        __builtin_amdgcn_s_barrier();        // every wave has finished reading K and V tiles
+        byte* const stage = lds_all + w.wave * 64 * ROW_BYTES;
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            const float inv = 1.0f / l_tot[qb];
+            const int r = qb * 32 + w.lq;
 #pragma unroll
             for (int db = 0; db < ODB; ++db)
 #pragma unroll
@@ -777,11 +789,17 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
                     bf16x4 o4;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(w.o_acc[qb][db][r4 * 4 + e] * inv);
-                    *(bf16x4*)(dst + db * 32 + 8 * r4 + 4 * w.lh) = o4;
+                    *(bf16x4*)(stage + r * ROW_BYTES + (((db * 4 + r4) ^ (r & (PIECES - 1))) << 4) + 8 * w.lh) = o4;
                 }
         }
-        if (p.lse != nullptr && w.lh == 0)
-            p.lse[(int64_t)bh * n + row] = (w.mc[qb] + fast_log2(l_tot)) * (p.lse_base2 ? 1.0f : kLn2);
+        byte* const obase = (byte*)((__bf16*)p.o + head_off);
+        const int lrow = w.lane / PIECES, lpiece = w.lane % PIECES;
+#pragma unroll
+        for (int t = 0; t < 64 / RPC; ++t) {
+            const int r = t * RPC + lrow;
+            const u32x4 v = *(const u32x4*)(stage + r * ROW_BYTES + ((lpiece ^ (r & (PIECES - 1))) << 4));
+            if (q0 + r < n) *(u32x4*)(obase + (int64_t)(q0 + r) * p.td.sn * 2 + lpiece * 16) = v;
+        }
     }
 }
 
