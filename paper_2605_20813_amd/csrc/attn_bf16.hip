@@ -182,6 +182,7 @@ struct AttnWave {
     bool ragged;
     uint32_t row_bytes;   // byte stride between sequence positions of K / V in global memory
     uint32_t wave_lds;    // LDS address of this wave's first 1 KB chunk in tile slot 0 of K
+    uint32_t dma_off;     // global byte offset of the load whose first half has been issued
     const byte* K;
     const byte* V;
     const byte* idx;      // int32 column numbers of this head
@@ -285,16 +286,21 @@ struct AttnWave {
         }
     }
 
-    // One load of the scheduled half-step, written out so that the instruction order is fixed:
-    // LDS destination into m0, row offset (one VALU instruction, which also covers the wait
-    // state an m0 write needs before its use), load.
+    // One load of the scheduled half-step in two parts, so that no slot gets more than two
+    // instructions on top of its own: LDS destination into m0 and the row offset (one VALU
+    // instruction, which also covers the wait state an m0 write needs before its use) behind
+    // the second MFMA of a pair, the load itself behind the first MFMA of the next pair.
     template <int LDS_OFF>
-    __device__ __forceinline__ void issue_one(const byte* g, int row, uint32_t piece_off) const {
+    __device__ __forceinline__ uint32_t issue_addr(int row, uint32_t piece_off) const {
         uint32_t off;
-        asm volatile("s_add_i32 m0, %1, %2\n\tv_mad_u32_u24 %0, %3, %4, %5\n\tglobal_load_lds_dwordx4 %0, %6"
-                     : "=&v"(off)
-                     : "s"(wave_lds), "n"(LDS_OFF), "v"(row), "s"(row_bytes), "v"(piece_off), "s"(g)
-                     : "memory");   // m0 is written here and by the compiler only right in front of its own uses
+        asm volatile("s_add_i32 m0, %1, %2\n\tv_mad_u32_u24 %0, %3, %4, %5"
+                     : "=v"(off) : "s"(wave_lds), "n"(LDS_OFF), "v"(row), "s"(row_bytes), "v"(piece_off));
+        return off;
+    }
+    // m0 is written by issue_addr and, in compiler-generated code, only right in front of the
+    // compiler's own uses: nothing touches it between the two halves of a load
+    __device__ __forceinline__ void issue_load(const byte* g, uint32_t off) const {
+        asm volatile("global_load_lds_dwordx4 %0, %1" : : "v"(off), "s"(g) : "memory");
     }
 
     // ------------------------------------------------------------------ fragment reads
@@ -382,11 +388,16 @@ struct AttnWave {
         ep.rs[0] = ep.rs[1] = 0.f;
     }
     // Close a half-tile: accept the row sums, or -- if some lane's sum says that its weights
-    // outgrew the reference (or is not a number: first half-tile, reference still -inf) -- fix
-    // the reference first.  Every MFMA that adds P(j-1) to the accumulator has been issued.
+    // outgrew the reference -- fix the reference first.  Every MFMA that adds P(j-1) to the
+    // accumulator has been issued.  SCHEDULED half-steps see finite logits and a finite
+    // reference, so their sums are numbers and one compare serves both query blocks; the general
+    // half-step also meets -inf - (-inf) (first half-tile with masked columns) and tests each
+    // sum in the NaN-catching form.
+    template <bool SCHEDULED>
     __device__ __forceinline__ void exp_end(ExpPipe& ep, const f32x16 (&S)[2], bf16x8 (&P)[2][2]) {
         const float limit = __builtin_amdgcn_exp2f(kTau);
-        const bool bad = !(ep.rs[0] <= limit) || !(ep.rs[1] <= limit);
+        const bool bad = SCHEDULED ? fmaxf(ep.rs[0], ep.rs[1]) > limit
+                                   : !(ep.rs[0] <= limit) || !(ep.rs[1] <= limit);
         if (__builtin_expect(__ballot(bad) != 0ull, 0)) fix_reference(ep, S, P);
         l_run[0] += ep.rs[0];
         l_run[1] += ep.rs[1];
@@ -431,7 +442,7 @@ struct AttnWave {
         exp_begin(ep);
 #pragma unroll
         for (int i = 0; i < EXP_TICKS; ++i) exp_tick(i, S, P, ep);
-        exp_end(ep, S, P);
+        exp_end<false>(ep, S, P);
     }
 
     // ------------------------------------------------------------------ half-steps
@@ -490,7 +501,7 @@ struct AttnWave {
         fence();
         fast_pairs<KOFF, VOFF, HAS_NEXT, NKOFF, ROLE, KW, VW>(std::make_integer_sequence<int, NP>{}, kv, vv, fr, ep,
                                                               next_tile, krows, vrows, rows_n, S_in, S_out, P_in, P_out);
-        exp_end(ep, S_in, P_out);
+        exp_end<true>(ep, S_in, P_out);
         if (HAS_NEXT) {
 #pragma unroll
             for (int i = 0; i < AHEAD; ++i) kpre[i] = fr[NP + i];
@@ -515,7 +526,7 @@ struct AttnWave {
                                               int (&rows_n)[CH],
                                               f32x16 (&S_in)[2], f32x16 (&S_out)[2],
                                               bf16x8 (&P_in)[2][2], bf16x8 (&P_out)[2][2]) {
-        static_assert((HAS_V ? 2 : 1) * CH + 1 <= NP, "one load instruction per MFMA pair");
+        static_assert((HAS_V ? 2 : 1) * CH + 2 <= NP, "one load instruction per MFMA pair");
         // Slot layout: MFMA, then the slot's memory and scalar instructions, then its VALU work.
         // (Measured on gfx950 with one wave per SIMD: the first non-VALU instruction after an
         // MFMA issues for free, the same instruction in front of the MFMA delays it.)
@@ -548,6 +559,10 @@ struct AttnWave {
                     wait_vmcnt_at_most<VM_PER_ISSUE>();
                     __builtin_amdgcn_s_barrier();
                 }
+                if constexpr (ROLE == 0) {
+                    if constexpr (P >= 2 && P <= CH + 1) issue_load(K, dma_off);
+                    if constexpr (HAS_V && P > CH + 1 && P <= 2 * CH + 1) issue_load(V, dma_off);
+                }
                 if constexpr (PA < KK) {
                     fr[PA] = lds_read_b128_at<KOFF>(kv[PA]);
                 } else if constexpr (PA < NP) {
@@ -563,9 +578,9 @@ struct AttnWave {
                 }
                 if constexpr (ROLE == 0) {
                     if constexpr (P == 0) load_rows(next_tile, rows_n);
-                    if constexpr (P >= 1 && P <= CH) issue_one<KW + (P - 1) * 1024>(K, krows[P - 1], koff[P - 1]);
+                    if constexpr (P >= 1 && P <= CH) dma_off = issue_addr<KW + (P - 1) * 1024>(krows[P - 1], koff[P - 1]);
                     if constexpr (HAS_V && P > CH && P <= 2 * CH)
-                        issue_one<VW + (P - CH - 1) * 1024>(V, vrows[P - CH - 1], voff[P - CH - 1]);
+                        dma_off = issue_addr<VW + (P - CH - 1) * 1024>(vrows[P - CH - 1], voff[P - CH - 1]);
                 }
             }
             fence();
