@@ -170,10 +170,31 @@ struct AttnWave {
     static constexpr int NS = 2 * NP;                    // MFMA slots of a half-step
     static constexpr int EXP_TICKS = 34;                 // 32 values through a 3-stage pipeline
     // exp ticks finished before slot s (slot NS = end of the half-step)
-    static constexpr int exp_ticks_before(int s) { return ceil_div(EXP_TICKS * s, NS); }
-    // direct-to-LDS loads per steady-state issue point (the row-number loads are issued before
-    // them, so "all but the newest VM_PER_ISSUE" covers every load of earlier iterations)
-    static constexpr int VM_PER_ISSUE = CH + (HAS_V ? CH : 0);
+    // ticks issued before slot s: spread over all slots but the last one, so that the row sums
+    // are complete (and their check can be computed) one slot before the half-step ends
+    static constexpr int exp_ticks_before(int s) {
+        const int t = ceil_div(EXP_TICKS * s, NS - 1);
+        return t < EXP_TICKS ? t : EXP_TICKS;
+    }
+    // Load schedule of an iteration, one instruction pair (address, load) per entry, spread out
+    // so that the vector memory pipe sees a steady trickle instead of a burst: first half-step,
+    // K load j: address behind the second MFMA of pair 1 + j*LOAD_STRIDE, load behind the first
+    // MFMA of the next pair; second half-step, V load j: the same at pair j*LOAD_STRIDE.
+    static constexpr int LOAD_STRIDE = (NP - 2) / CH;
+    static constexpr int k_addr_pair(int j) { return 1 + j * LOAD_STRIDE; }
+    static constexpr int v_addr_pair(int j) { return j * LOAD_STRIDE; }
+    // index of the load whose address / load instruction sits in pair p, or -1
+    static constexpr int k_addr_at(int p) { return (p >= 1 && (p - 1) % LOAD_STRIDE == 0 && (p - 1) / LOAD_STRIDE < CH) ? (p - 1) / LOAD_STRIDE : -1; }
+    static constexpr int v_addr_at(int p) { return (p % LOAD_STRIDE == 0 && p / LOAD_STRIDE < CH) ? p / LOAD_STRIDE : -1; }
+    // V loads issued before the barrier of the second half-step (it sits in pair KK, in front of
+    // that pair's load)
+    static constexpr int v_loads_before_barrier() {
+        int c = 0;
+        for (int j = 0; j < CH; ++j) c += (v_addr_pair(j) + 1 < KK) ? 1 : 0;
+        return c;
+    }
+    // loads of the running iteration in flight at its barrier: everything older has to be complete
+    static constexpr int VM_PER_ISSUE = CH + (HAS_V ? v_loads_before_barrier() : 0);
 
     // lane geometry
     int lane, wave, lq, lh;
@@ -260,6 +281,40 @@ struct AttnWave {
             for (int i = 0; i < CH; ++i) dst[i] = base + i < ns ? base + i : ns - 1;
         }
     }
+    // The same for the scheduled half-steps, with loads the compiler does not see: it would
+    // otherwise wait for ALL outstanding vector memory operations (the direct-to-LDS loads
+    // included) in front of the first use.  The row numbers are used one iteration later; the
+    // wait in front of the running iteration's barrier already covers them (they are older
+    // than every direct-to-LDS load that wait leaves in flight).
+    __device__ __forceinline__ void load_rows_async(int t, int (&dst)[CH]) const {
+        if (!GATHER) { load_rows(t, dst); return; }
+        t = t < ntiles ? t : ntiles - 1;
+        const bool whole = (t + 1) * BN <= ns;
+        const uint32_t off = (uint32_t)(t * (BN * 4)) + lane_rows_off;
+        if (__builtin_expect(whole, 1)) {
+            if constexpr (CH == 4) {
+                u32x4 r;
+                asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(r) : "v"(off), "s"(idx));
+#pragma unroll
+                for (int i = 0; i < CH; ++i) dst[i] = (int)r[i];
+            } else {
+                static_assert(CH == 2 || CH == 4, "row numbers per lane and tile");
+                typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                u32x2 r;
+                asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(r) : "v"(off), "s"(idx));
+#pragma unroll
+                for (int i = 0; i < CH; ++i) dst[i] = (int)r[i];
+            }
+        }
+        if (__builtin_expect(!whole, 0)) {
+#pragma unroll
+            for (int i = 0; i < CH; ++i) {
+                uint32_t o = off + 4u * i;
+                o = o < (uint32_t)ns * 4u ? o : (uint32_t)ns * 4u - 4u;
+                asm volatile("global_load_dword %0, %1, %2" : "=v"(dst[i]) : "v"(o), "s"(idx));
+            }
+        }
+    }
     // position inside its tile of the key in LDS tile row `row`
     static __device__ __forceinline__ int tile_pos(int row) {
         return (row & ~15) + (row % ROWS_PER_CHUNK) * CH + (row & 15) / ROWS_PER_CHUNK;
@@ -339,7 +394,7 @@ struct AttnWave {
     // P = exp2(S*c2 - mc) in EXP_TICKS small steps that can be spread over MFMA slots: tick i
     // adds value i-2 to the fp32 row sum (packing a bf16 pair after every odd value), forms the
     // scaled, shifted logit of value i and takes exp2 of value i-1.  Value e = qb*16 + r.
-    struct ExpPipe { float t[32]; float x[32]; float rs[2]; };
+    struct ExpPipe { float t[32]; float x[32]; float rs[2]; uint64_t bad; };
     __device__ __forceinline__ void exp_tick(int i, const f32x16 (&S)[2], bf16x8 (&P)[2][2], ExpPipe& ep) {
         // A wave issues in order, one instruction at a time, so every instruction between two
         // MFMAs counts.  Issue order inside a tick: fma (left to the compiler), then one
@@ -395,10 +450,11 @@ struct AttnWave {
     // sum in the NaN-catching form.
     template <bool SCHEDULED>
     __device__ __forceinline__ void exp_end(ExpPipe& ep, const f32x16 (&S)[2], bf16x8 (&P)[2][2]) {
-        const float limit = __builtin_amdgcn_exp2f(kTau);
-        const bool bad = SCHEDULED ? fmaxf(ep.rs[0], ep.rs[1]) > limit
-                                   : !(ep.rs[0] <= limit) || !(ep.rs[1] <= limit);
-        if (__builtin_expect(__ballot(bad) != 0ull, 0)) fix_reference(ep, S, P);
+        if (!SCHEDULED) {
+            const float limit = __builtin_amdgcn_exp2f(kTau);
+            ep.bad = __ballot(!(ep.rs[0] <= limit) || !(ep.rs[1] <= limit));
+        }
+        if (__builtin_expect(ep.bad != 0ull, 0)) fix_reference(ep, S, P);
         l_run[0] += ep.rs[0];
         l_run[1] += ep.rs[1];
     }
@@ -526,7 +582,7 @@ struct AttnWave {
                                               int (&rows_n)[CH],
                                               f32x16 (&S_in)[2], f32x16 (&S_out)[2],
                                               bf16x8 (&P_in)[2][2], bf16x8 (&P_out)[2][2]) {
-        static_assert((HAS_V ? 2 : 1) * CH + 2 <= NP, "one load instruction per MFMA pair");
+        static_assert(LOAD_STRIDE >= 1 && k_addr_pair(CH - 1) + 1 < NP && v_addr_pair(CH - 1) + 1 < NP, "load schedule fits the half-step");
         // Slot layout: MFMA, then the slot's memory and scalar instructions, then its VALU work.
         // (Measured on gfx950 with one wave per SIMD: the first non-VALU instruction after an
         // MFMA issues for free, the same instruction in front of the MFMA delays it.)
@@ -559,9 +615,11 @@ struct AttnWave {
                     wait_vmcnt_at_most<VM_PER_ISSUE>();
                     __builtin_amdgcn_s_barrier();
                 }
-                if constexpr (ROLE == 0) {
-                    if constexpr (P >= 2 && P <= CH + 1) issue_load(K, dma_off);
-                    if constexpr (HAS_V && P > CH + 1 && P <= 2 * CH + 1) issue_load(V, dma_off);
+                if constexpr (ROLE == 0 && P >= 1) {
+                    if constexpr (k_addr_at(P - 1) >= 0) issue_load(K, dma_off);
+                }
+                if constexpr (ROLE == 1 && HAS_V && P >= 1) {
+                    if constexpr (v_addr_at(P - 1) >= 0) issue_load(V, dma_off);
                 }
                 if constexpr (PA < KK) {
                     fr[PA] = lds_read_b128_at<KOFF>(kv[PA]);
@@ -577,16 +635,21 @@ struct AttnWave {
                     set_half(fr[PA], 1, lds_read_tr_at<VOFF + hf * 16 * ROW_BYTES + 8 * ROW_BYTES>(vv[db]));
                 }
                 if constexpr (ROLE == 0) {
-                    if constexpr (P == 0) load_rows(next_tile, rows_n);
-                    if constexpr (P >= 1 && P <= CH) dma_off = issue_addr<KW + (P - 1) * 1024>(krows[P - 1], koff[P - 1]);
-                    if constexpr (HAS_V && P > CH && P <= 2 * CH)
-                        dma_off = issue_addr<VW + (P - CH - 1) * 1024>(vrows[P - CH - 1], voff[P - CH - 1]);
+                    if constexpr (P == 0) load_rows_async(next_tile, rows_n);
+                    constexpr int j = k_addr_at(P);
+                    if constexpr (j >= 0) dma_off = issue_addr<KW + j * 1024>(krows[j], koff[j]);
+                }
+                if constexpr (ROLE == 1 && HAS_V) {
+                    constexpr int j = v_addr_at(P);
+                    if constexpr (j >= 0) dma_off = issue_addr<VW + j * 1024>(vrows[j], voff[j]);
                 }
             }
             fence();
             // this slot's share of the VALU work
 #pragma unroll
             for (int i = exp_ticks_before(s); i < exp_ticks_before(s + 1); ++i) exp_tick(i, S_in, P_out, ep);
+            // the row sums are complete one slot early: compare now, branch after the last MFMA
+            if (s == NS - 2) ep.bad = __ballot(fmaxf(ep.rs[0], ep.rs[1]) > __builtin_amdgcn_exp2f(kTau));
             fence();
         }
     }
@@ -760,8 +823,19 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
         static_assert(AHEAD == 3, "one operand per prefetched fragment");
         asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kpre[0]), "+v"(kpre[1]), "+v"(kpre[2]));
     }
-    // ---- tail: the remaining half-steps (at most three), then the last P V product
-    wait_vmcnt_at_most<0>();
+    // ---- tail: the remaining half-steps (at most three), then the last P V product.
+    // The wait names the row-number registers: loads into them that nobody reads any more are
+    // still in flight, and the registers must not be handed to other values before they land.
+    static_assert(CH == 2 || CH == 4, "row numbers per lane and tile");
+    if constexpr (CH == 4)
+        asm volatile("s_waitcnt vmcnt(0)"
+                     : "+v"(rows_k[0]), "+v"(rows_k[1]), "+v"(rows_k[2]), "+v"(rows_k[3]),
+                       "+v"(rows_v[0]), "+v"(rows_v[1]), "+v"(rows_v[2]), "+v"(rows_v[3]),
+                       "+v"(rows_n[0]), "+v"(rows_n[1]), "+v"(rows_n[2]), "+v"(rows_n[3]) : : "memory");
+    else
+        asm volatile("s_waitcnt vmcnt(0)"
+                     : "+v"(rows_k[0]), "+v"(rows_k[1]), "+v"(rows_v[0]), "+v"(rows_v[1]),
+                       "+v"(rows_n[0]), "+v"(rows_n[1]) : : "memory");
     __builtin_amdgcn_s_barrier();
     int j = 2 * npairs + 1;
     if (j < nhalf) {                              // odd
