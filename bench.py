@@ -34,7 +34,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llada_64k")
     ap.add_argument("--keep", type=float, default=None)
-    ap.add_argument("--dense-steps", type=int, default=6, help="dense-baseline launches timed beside the run")
+    ap.add_argument("--dense-steps", type=int, default=32, help="dense-baseline launches timed beside the run")
     ap.add_argument("--cpu-rows", type=int, default=32768,
                     help="query rows of one head the CPU oracle is timed on (in calls of 2048 rows)")
     ap.add_argument("--no-cpu", action="store_true")
@@ -183,6 +183,10 @@ def main():
         "topk_gbps": round(topk_bytes / (topk_ms * 1e-3) * 1e-9, 1),
         "dense_ms": None if dense_ms is None else round(dense_ms, 4),
         "speedup_vs_dense": None if dense_ms is None else round(dense_ms / ms_per_step, 3),
+        # the whole schedule of one layer: every sparse step and select run for real; the dense side
+        # is `dense-steps` identical launches scaled to the same number of steps
+        "schedule_total_ms": round(total_ms, 1),
+        "dense_schedule_total_ms_scaled": None if dense_ms is None else round(dense_ms * steps, 1),
         "kept_tflops": round(achieved, 2),
         "dense_equivalent_tflops": round(dense_flop / (attn_ms * 1e-3) * 1e-12, 2),
         "dense_kernel_tflops": None if dense_ms is None else round(dense_flop / (dense_ms * 1e-3) * 1e-12, 2),
