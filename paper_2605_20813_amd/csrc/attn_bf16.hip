@@ -736,7 +736,9 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     w.wave_lds = __builtin_amdgcn_readfirstlane(lds_address(lds_k) + w.wave * CH * 1024);
     w.K = (const byte*)((const __bf16*)p.k + head_off);
     w.V = HAS_V ? (const byte*)((const __bf16*)p.v + head_off) : nullptr;
-    w.idx = W::GATHER ? (const byte*)(p.idx + (int64_t)bh * p.ns) : nullptr;
+    // the column set of this query block's group (Sec. 3.3: one set per query group)
+    const int group = p.groups > 1 ? (qblk * BM) / p.group_size : 0;
+    w.idx = W::GATHER ? (const byte*)(p.idx + ((int64_t)bh * p.groups + group) * p.ns) : nullptr;
     w.c2 = p.scale * kLog2e;                 // exp(z*scale) = exp2(z*c2)
     w.mc[0] = w.mc[1] = -INFINITY;
     w.l_run[0] = w.l_run[1] = 0.f;

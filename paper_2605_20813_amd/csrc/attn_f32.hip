@@ -38,7 +38,9 @@ __global__ void __launch_bounds__(NTHREADS) attn_f32_kernel(AttnParams p) {
     const float* __restrict__ Q = (const float*)p.q + head_off;
     const float* __restrict__ K = (const float*)p.k + head_off;
     const float* __restrict__ V = HAS_V ? (const float*)p.v + head_off : nullptr;
-    const int32_t* __restrict__ idx = GATHER ? p.idx + (int64_t)bh * p.ns : nullptr;
+    // the column set of this query block's group (Sec. 3.3: one set per query group)
+    const int group = p.groups > 1 ? (qblk * BM) / p.group_size : 0;
+    const int32_t* __restrict__ idx = GATHER ? p.idx + ((int64_t)bh * p.groups + group) * p.ns : nullptr;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;

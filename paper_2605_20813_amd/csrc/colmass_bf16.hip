@@ -1,5 +1,7 @@
-// Column softmax mass, bf16 inputs (Sec. 3.3, score equation, one group per head):
-//   s_j = (1/n) sum_i exp(z_ij - lse_i),  z_ij = q_i . k_j * scale,
+// Column softmax mass, bf16 inputs (Sec. 3.3, score equation):
+//   s_{u,j} = (1/|G_u|) sum_{i in G_u} exp(z_ij - lse_i),  z_ij = q_i . k_j * scale,
+// for the query groups G_u of a head (consecutive runs of group_size rows; one group = the
+// whole head on the hot path),
 // with the row log-sum-exp lse_i produced by the row pass (attn_bf16.hip, lse-only mode) and
 // handed over in log2 units, so that p_ij = exp2(z_ij * scale * log2(e) - lse2_i).
 //
@@ -7,8 +9,8 @@
 // in registers as the MFMA A operand and streams every 64-row Q tile of the head through
 // double-buffered LDS as the B operand.  In S^T[key][query] a lane owns one query column, so
 // exp2(z*c - lse_i*log2e) needs one per-lane scalar per query block, and the column sums are
-// plain per-lane, per-register accumulators; lanes are combined once, after the last tile,
-// in a fixed butterfly order.  P never leaves fp32 and there are no floating-point atomics:
+// plain per-lane, per-register accumulators; lanes are combined once per group, after its last
+// tile, in a fixed butterfly order.  P never leaves fp32 and there are no floating-point atomics:
 // the result is bit-identical from run to run.
 #include "pulsecol_device.h"
 #include "pulsecol_kernels.h"
@@ -135,23 +137,33 @@ __global__ void __launch_bounds__(NTHREADS) colmass_bf16_kernel(ScoreParams p) {
                 for (int r = 0; r < 16; ++r) { acc_long[kb][r] += acc_short[kb][r]; acc_short[kb][r] = 0.f; }
         }
 
+        // ---- last tile of a query group: combine the 32 query-column lanes of each half (fixed
+        // butterfly), divide by the group's size, store the group's score row, start over
+        const int rows_done = (t + 1) * QT;
+        const bool group_end = t + 1 == ntiles || (p.groups > 1 && rows_done % p.group_size == 0);
+        if (group_end) {
+            const int u = p.groups > 1 ? (t * QT) / p.group_size : 0;
+            const int g_first = p.groups > 1 ? u * p.group_size : 0;
+            const int g_rows = (rows_done < n ? rows_done : n) - g_first;
+            const float inv = 1.0f / (float)g_rows;
+            float* __restrict__ out = p.scores + ((int64_t)bh * p.groups + u) * n;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    float v = acc_long[kb][r] + acc_short[kb][r];
+#pragma unroll
+                    for (int m = 1; m < 32; m <<= 1) v += __shfl_xor(v, m, 64);
+                    const int key = key0 + kb * 32 + acc_row(r, lh);
+                    if (lq == 0 && key < n) out[key] = v * inv;
+                    acc_long[kb][r] = 0.f;
+                    acc_short[kb][r] = 0.f;
+                }
+        }
+
         if (t + 1 < ntiles) commit(buf ^ 1);
         __syncthreads();
     }
-
-    // ---- combine the 32 query-column lanes of each half (fixed butterfly), scale by 1/n, store
-    const float inv_n = 1.0f / (float)n;
-    float* __restrict__ out = p.scores + (int64_t)bh * n;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            float v = acc_long[kb][r] + acc_short[kb][r];
-#pragma unroll
-            for (int m = 1; m < 32; m <<= 1) v += __shfl_xor(v, m, 64);
-            const int key = key0 + kb * 32 + acc_row(r, lh);
-            if (lq == 0 && key < n) out[key] = v * inv_n;
-        }
 }
 
 template <int D>

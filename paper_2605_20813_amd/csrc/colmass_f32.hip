@@ -1,5 +1,5 @@
-// Column softmax mass, fp32 inputs (Sec. 3.3, score equation, one group per head):
-//   s_j = (1/n) sum_i exp2(z_ij * scale * log2(e) - lse2_i)
+// Column softmax mass, fp32 inputs (Sec. 3.3, score equation, per query group G_u of a head):
+//   s_{u,j} = (1/|G_u|) sum_{i in G_u} exp2(z_ij * scale * log2(e) - lse2_i)
 // with lse2_i = log2 sum_j exp(z_ij * scale) from the row pass (attn_f32.hip, lse-only mode).
 //
 // K-stationary like the bf16 kernel, on v_mfma_f32_32x32x2_f32: a workgroup owns 128 key
@@ -101,17 +101,27 @@ __global__ void __launch_bounds__(NTHREADS) colmass_f32_kernel(ScoreParams p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) { acc_long[r] += acc_short[r]; acc_short[r] = 0.f; }
         }
-    }
-
-    const float inv_n = 1.0f / (float)n;
-    float* __restrict__ out = p.scores + (int64_t)bh * n;
+        // ---- last tile of a query group: combine lanes (fixed butterfly), divide by the group's
+        // size, store the group's score row, start over
+        const int rows_done = (t + 1) * QT;
+        const bool group_end = t + 1 == ntiles || (p.groups > 1 && rows_done % p.group_size == 0);
+        if (group_end) {
+            const int u = p.groups > 1 ? (t * QT) / p.group_size : 0;
+            const int g_first = p.groups > 1 ? u * p.group_size : 0;
+            const int g_rows = (rows_done < n ? rows_done : n) - g_first;
+            const float inv = 1.0f / (float)g_rows;
+            float* __restrict__ out = p.scores + ((int64_t)bh * p.groups + u) * n;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        float v = acc_long[r] + acc_short[r];
+            for (int r = 0; r < 16; ++r) {
+                float v = acc_long[r] + acc_short[r];
 #pragma unroll
-        for (int m = 1; m < 32; m <<= 1) v += __shfl_xor(v, m, 64);
-        const int key = key0 + acc_row(r, lh);
-        if (lq == 0 && key < n) out[key] = v * inv_n;
+                for (int m = 1; m < 32; m <<= 1) v += __shfl_xor(v, m, 64);
+                const int key = key0 + acc_row(r, lh);
+                if (lq == 0 && key < n) out[key] = v * inv;
+                acc_long[r] = 0.f;
+                acc_short[r] = 0.f;
+            }
+        }
     }
 }
 

@@ -55,7 +55,14 @@ pulsecol_status check_shape(const pulsecol_shape* s, std::string* why) {
     if (s->stride_b < 0 || s->stride_h < 0 || s->stride_n < 0) { *why = "strides must be >= 0"; return PULSECOL_ERR_INVALID_ARG; }
     if (s->dtype != PULSECOL_BF16 && s->dtype != PULSECOL_F32) { *why = "dtype must be PULSECOL_BF16 or PULSECOL_F32"; return PULSECOL_ERR_UNSUPPORTED; }
     if (s->head_dim != 64 && s->head_dim != 128) { *why = "head_dim must be 64 or 128"; return PULSECOL_ERR_UNSUPPORTED; }
-    if (s->group_size != 0 && s->group_size < s->seq) { *why = "per-group column sets (0 < group_size < seq) are not built yet"; return PULSECOL_ERR_UNSUPPORTED; }
+    if (s->group_size != 0 && s->group_size < s->seq) {
+        // a query block of the attention kernels reads ONE column set: groups are whole query blocks
+        const int bm = s->dtype == PULSECOL_BF16 ? pulsecol::kBlockM_bf16 : pulsecol::kBlockM_f32;
+        if (s->group_size % bm != 0) {
+            *why = "group_size must be 0, >= seq, or a multiple of the query block (256 rows for bf16, 128 for f32)";
+            return PULSECOL_ERR_UNSUPPORTED;
+        }
+    }
     if ((int64_t)s->batch * s->heads > (1 << 20)) { *why = "batch*heads too large"; return PULSECOL_ERR_UNSUPPORTED; }
     if (s->stride_n != 0 && s->stride_n < s->head_dim) { *why = "stride_n smaller than head_dim"; return PULSECOL_ERR_INVALID_ARG; }
     {   // the kernels address a head's K/V rows with 32-bit byte offsets
@@ -89,6 +96,7 @@ pulsecol::AttnParams attn_params(const pulsecol_ctx* c, const void* Q, const voi
     p.q = Q; p.k = K; p.v = V; p.o = O; p.idx = idx; p.lse = lse; p.lse_base2 = lse_base2;
     p.td = c->td;
     p.batch = c->shape.batch; p.heads = c->shape.heads; p.n = c->shape.seq; p.ns = ns;
+    p.groups = c->groups; p.group_size = c->shape.group_size;
     p.scale = c->scale;
     return p;
 }
@@ -114,6 +122,7 @@ pulsecol_status run_scores(pulsecol_ctx* ctx, const void* Q, const void* K, floa
     pulsecol::ScoreParams sp{};
     sp.q = Q; sp.k = K; sp.lse = ctx->lse; sp.scores = out; sp.td = ctx->td;
     sp.batch = ctx->shape.batch; sp.heads = ctx->shape.heads; sp.n = ctx->shape.seq; sp.scale = ctx->scale;
+    sp.groups = ctx->groups; sp.group_size = ctx->shape.group_size;
     e = ctx->shape.dtype == PULSECOL_BF16 ? pulsecol::launch_colmass_bf16(sp, ctx->shape.head_dim, s)
                                           : pulsecol::launch_colmass_f32(sp, ctx->shape.head_dim, s);
     if (e != hipSuccess) return fail_hip(ctx, e, "column-mass kernel");
@@ -153,7 +162,8 @@ pulsecol_status pulsecol_create(pulsecol_ctx** out, const pulsecol_shape* shape,
     if (!c) return fail(nullptr, PULSECOL_ERR_OOM, "pulsecol_create: host allocation failed");
     c->shape = *shape;
     c->device = device;
-    c->groups = 1;
+    c->groups = (shape->group_size == 0 || shape->group_size >= shape->seq)
+                    ? 1 : (shape->seq + shape->group_size - 1) / shape->group_size;
     c->scale = shape->scale > 0.f ? shape->scale : 1.0f / std::sqrt((float)shape->head_dim);
     c->td.sn = shape->stride_n ? shape->stride_n : shape->head_dim;
     c->td.sh = shape->stride_h ? shape->stride_h : (int64_t)shape->seq * c->td.sn;

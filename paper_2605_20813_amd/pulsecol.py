@@ -163,7 +163,11 @@ class Context:
 
     @property
     def groups(self) -> int:
-        return 1
+        """U: query groups per head (Sec. 3.3); 1 when the whole head is one group."""
+        s = self.shape
+        if s.group_size == 0 or s.group_size >= s.seq:
+            return 1
+        return (s.seq + s.group_size - 1) // s.group_size
 
     def tile_shape(self):
         bm, bn = c_int32(), c_int32()
