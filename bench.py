@@ -40,6 +40,7 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-probes", action="store_true", help="skip the MFMA-only / copy roofline probes")
     ap.add_argument("--no-32k", action="store_true", help="skip the short side measurement at 32K context")
+    ap.add_argument("--no-groups", action="store_true", help="skip the short side measurement with group-wise column sets")
     ap.add_argument("--cold-steps", type=int, default=8,
                     help="extra attention launches timed with a 1 GiB buffer overwritten before each (caches evicted)")
     ap.add_argument("--copy-gib", type=float, default=0.0,
@@ -203,6 +204,8 @@ def main():
     torch.cuda.empty_cache()
     if not a.no_32k and a.workload == "llada_64k":
         out["context_32k"] = side_config(pc, wl, torch, dev, "llada_32k")
+    if not a.no_groups and a.workload == "llada_64k":
+        out["groupwise"] = groupwise_config(pc, wl, torch, dev, w, keep)
     if not a.no_probes:
         out["probes"] = roofline_probes(achieved, dense_ms and dense_flop / (dense_ms * 1e-3) * 1e-12)
     if not a.no_cpu:
@@ -240,6 +243,48 @@ def side_config(pc, wl, torch, dev, name):
         res["keep"][str(keep)] = {"k": k, "attn_ms": round(attn_ms, 4), "select_ms": round(select_ms, 4),
                                   "kept_tflops": round(4.0 * B * H * n * k * d / (attn_ms * 1e-3) * 1e-12, 2),
                                   "speedup_vs_dense_launch": round(res["dense_ms"] / attn_ms, 2)}
+    ctx.close()
+    return res
+
+
+def groupwise_config(pc, wl, torch, dev, w, keep):
+    """The paper's own pattern format at the headline shape: one column set per query group,
+    groups = query blocks of 256 rows.  The score pass writes [B,H,U,n] fp32, top-k runs over
+    B*H*U rows (the memory-bound stage), and the attention gathers are no longer shared between
+    the query blocks of a head."""
+    B, H, n, d = w.batch, w.heads, w.seq, w.head_dim
+    G = 256
+    Q, K, V = (t.to(dev) for t in wl.make_qkv(w))
+    O = torch.empty_like(Q)
+    ctx = pc.Context(B, H, n, d, w.torch_dtype, group_size=G)
+    U = ctx.groups
+    k = pc.num_keep(n, keep)
+    idx = torch.empty(B, H, U, k, dtype=torch.int32, device=dev)
+    scores = torch.empty(B, H, U, n, dtype=torch.float32, device=dev)
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    scores_ms = timed(lambda: ctx.scores(Q, K, scores_out=scores), 2)
+    topk_ms = timed(lambda: ctx.topk(scores, k, idx_out=idx), 3)
+    select_ms = timed(lambda: ctx.select(Q, K, keep, refresh=True, idx_out=idx), 1)
+    attn_ms = timed(lambda: ctx.attn(Q, K, V, idx, O=O), 10)
+    topk_bytes = B * H * U * (5 * 4 * n + 4 * k)
+    gather_bytes = B * H * U * 2 * k * d * 2 + 2 * B * H * n * d * 2      # K and V rows per group, Q, O
+    res = {"group_size": G, "groups_per_head": U, "k": k,
+           "scores_ms": round(scores_ms, 3), "topk_ms": round(topk_ms, 3),
+           "topk_gbps": round(topk_bytes / (topk_ms * 1e-3) * 1e-9, 1),
+           "select_ms": round(select_ms, 3), "attn_ms": round(attn_ms, 4),
+           "kept_tflops": round(4.0 * B * H * n * k * d / (attn_ms * 1e-3) * 1e-12, 2),
+           "attn_requested_gbps": round(gather_bytes / (attn_ms * 1e-3) * 1e-9, 1)}
     ctx.close()
     return res
 

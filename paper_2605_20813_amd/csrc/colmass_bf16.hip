@@ -6,12 +6,13 @@
 // handed over in log2 units, so that p_ij = exp2(z_ij * scale * log2(e) - lse2_i).
 //
 // K-stationary: a workgroup owns 256 key columns (4 waves x 64); each wave keeps its K rows
-// in registers as the MFMA A operand and streams every 64-row Q tile of the head through
-// double-buffered LDS as the B operand.  In S^T[key][query] a lane owns one query column, so
-// exp2(z*c - lse_i*log2e) needs one per-lane scalar per query block, and the column sums are
-// plain per-lane, per-register accumulators; lanes are combined once per group, after its last
-// tile, in a fixed butterfly order.  P never leaves fp32 and there are no floating-point atomics:
-// the result is bit-identical from run to run.
+// in registers as the MFMA B operand and streams every 64-row Q tile of the head through
+// double-buffered LDS as the A operand.  In S[query][key] a lane owns one key column and its
+// 16 registers are 16 query rows, so the column sum is an in-lane sum (four interleaved partial
+// sums, each a short and a long accumulator) and the two half-waves meet once per group.
+// exp2(z*c - lse_i*log2e) takes lse_i per register row, read from LDS four at a time.
+// P never leaves fp32 and there are no floating-point atomics: the result is bit-identical
+// from run to run.
 #include "pulsecol_device.h"
 #include "pulsecol_kernels.h"
 
@@ -32,7 +33,7 @@ __global__ void __launch_bounds__(NTHREADS) colmass_bf16_kernel(ScoreParams p) {
     constexpr int TILE_BYTES = QT * ROW_BYTES;
 
     __shared__ __attribute__((aligned(16))) unsigned char lds_q[2][TILE_BYTES];
-    __shared__ float lds_lse[2][QT];
+    __shared__ __attribute__((aligned(16))) float lds_lse[2][QT];
 
     const int n = p.n;
     const int nkb = (n + KEYS_PER_WG - 1) / KEYS_PER_WG;
@@ -49,7 +50,7 @@ __global__ void __launch_bounds__(NTHREADS) colmass_bf16_kernel(ScoreParams p) {
     const int lq = lane & 31, lh = lane >> 5;
     const int key0 = kblk * KEYS_PER_WG + wave * 64;
 
-    // ---- stationary K fragments: A operand, [key lq][d = kk*16 + 8*lh .. +7]
+    // ---- stationary K fragments: B operand, [key lq][d = kk*16 + 8*lh .. +7]
     bf16x8 kf[2][KK];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
@@ -92,17 +93,14 @@ __global__ void __launch_bounds__(NTHREADS) colmass_bf16_kernel(ScoreParams p) {
     __syncthreads();
 
     const float c2 = p.scale * kLog2e;
-    f32x16 acc_short[2], acc_long[2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { acc_short[kb][r] = 0.f; acc_long[kb][r] = 0.f; }
+    // per key block kb, this lane's key column; four interleaved partial sums keep the add chains independent
+    float acc_short[2][4] = {}, acc_long[2][4] = {};
 
     for (int t = 0; t < ntiles; ++t) {
         const int buf = t & 1;
         if (t + 1 < ntiles) fetch(t + 1);
 
-        f32x16 s[2][2];   // [kb][qb]
+        f32x16 s[2][2];   // [kb][qb]: S[query rows of block qb][key lq of block kb]
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -117,28 +115,32 @@ __global__ void __launch_bounds__(NTHREADS) colmass_bf16_kernel(ScoreParams p) {
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk) {
                 const bf16x8 qfrag = *(const bf16x8*)(rowp + (((2 * kk + lh) ^ sw) << 4));
-                s[0][qb] = mfma_bf16(kf[0][kk], qfrag, s[0][qb]);
-                s[1][qb] = mfma_bf16(kf[1][kk], qfrag, s[1][qb]);
+                s[0][qb] = mfma_bf16(qfrag, kf[0][kk], s[0][qb]);
+                s[1][qb] = mfma_bf16(qfrag, kf[1][kk], s[1][qb]);
             }
         }
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
-            const float l2 = lds_lse[buf][qb * 32 + lq];
+            // register r holds query row qb*32 + 8*(r/4) + 4*lh + r%4: four consecutive rows per r/4
+            f32x4 l2[4];
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+            for (int g = 0; g < 4; ++g) l2[g] = *(const f32x4*)(&lds_lse[buf][qb * 32 + 8 * g + 4 * lh]);
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    acc_short[kb][r] += fast_exp2(__builtin_fmaf(s[kb][qb][r], c2, -l2));
+                    acc_short[kb][r & 3] += fast_exp2(__builtin_fmaf(s[kb][qb][r], c2, -l2[r >> 2][r & 3]));
+            }
         }
         if ((t % FLUSH) == FLUSH - 1) {
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) { acc_long[kb][r] += acc_short[kb][r]; acc_short[kb][r] = 0.f; }
+                for (int c = 0; c < 4; ++c) { acc_long[kb][c] += acc_short[kb][c]; acc_short[kb][c] = 0.f; }
         }
 
-        // ---- last tile of a query group: combine the 32 query-column lanes of each half (fixed
-        // butterfly), divide by the group's size, store the group's score row, start over
+        // ---- last tile of a query group: add the two half-waves (they hold the same key
+        // columns, other query rows), divide by the group's size, store the group's score row
         const int rows_done = (t + 1) * QT;
         const bool group_end = t + 1 == ntiles || (p.groups > 1 && rows_done % p.group_size == 0);
         if (group_end) {
@@ -148,17 +150,14 @@ __global__ void __launch_bounds__(NTHREADS) colmass_bf16_kernel(ScoreParams p) {
             const float inv = 1.0f / (float)g_rows;
             float* __restrict__ out = p.scores + ((int64_t)bh * p.groups + u) * n;
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+            for (int kb = 0; kb < 2; ++kb) {
+                const float v = half_sum(((acc_long[kb][0] + acc_short[kb][0]) + (acc_long[kb][1] + acc_short[kb][1])) +
+                                         ((acc_long[kb][2] + acc_short[kb][2]) + (acc_long[kb][3] + acc_short[kb][3])));
+                const int key = key0 + kb * 32 + lq;
+                if (lh == 0 && key < n) out[key] = v * inv;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    float v = acc_long[kb][r] + acc_short[kb][r];
-#pragma unroll
-                    for (int m = 1; m < 32; m <<= 1) v += __shfl_xor(v, m, 64);
-                    const int key = key0 + kb * 32 + acc_row(r, lh);
-                    if (lq == 0 && key < n) out[key] = v * inv;
-                    acc_long[kb][r] = 0.f;
-                    acc_short[kb][r] = 0.f;
-                }
+                for (int c = 0; c < 4; ++c) { acc_long[kb][c] = 0.f; acc_short[kb][c] = 0.f; }
+            }
         }
 
         if (t + 1 < ntiles) commit(buf ^ 1);
