@@ -151,6 +151,8 @@ def main():
     # over the fp32 score rows, k int32 indices written
     topk_bytes = B * H * (5 * 4 * n + 4 * k)
     dense_ms = timed(lambda: ctx.attn_dense(Q, K, V, O=O), a.dense_steps) if a.dense_steps > 0 else None
+    # a refresh step that keeps the dense output: dense attention + column pass + top-k in one call
+    refresh_dense_ms = timed(lambda: ctx.refresh_dense(Q, K, V, keep, O=O, idx_out=idx), 2)
     ctx.select(Q, K, keep, refresh=True, idx_out=idx)
     torch.cuda.synchronize()
 
@@ -183,6 +185,7 @@ def main():
         "topk_ms": round(topk_ms, 4),
         "topk_gbps": round(topk_bytes / (topk_ms * 1e-3) * 1e-9, 1),
         "dense_ms": None if dense_ms is None else round(dense_ms, 4),
+        "refresh_dense_ms": round(refresh_dense_ms, 4),
         "speedup_vs_dense": None if dense_ms is None else round(dense_ms / ms_per_step, 3),
         # the whole schedule of one layer: every sparse step and select run for real; the dense side
         # is `dense-steps` identical launches scaled to the same number of steps

@@ -134,6 +134,15 @@ PULSECOL_API pulsecol_status pulsecol_attn(pulsecol_ctx* ctx, const void* Q, con
 PULSECOL_API pulsecol_status pulsecol_attn_dense(pulsecol_ctx* ctx, const void* Q, const void* K, const void* V,
                                     void* O, float* lse_out, void* stream);
 
+/* Refresh step that keeps the dense output (Sec. 3.3: at an identification or refresh step the
+ * method "computes full attention" and collects the attention matrix): O = softmax(Q K^T *
+ * scale) V as pulsecol_attn_dense, and idx_out / the cached pattern as
+ * pulsecol_select(refresh != 0) on the same Q, K.  The row log-sum-exp comes out of the dense
+ * pass itself, so the seq x seq logits are formed three times instead of four.  Same argument
+ * rules as the two calls it replaces. */
+PULSECOL_API pulsecol_status pulsecol_refresh_dense(pulsecol_ctx* ctx, const void* Q, const void* K, const void* V,
+                                       double keep_ratio, void* O, int32_t* idx_out, void* stream);
+
 /* Refresh schedule (Sec. 3.3, schedule equation), host only: T_win = max(1, floor(eta*T));
  * R == 1 -> {1}; else tau_r = 1 + floor((r-1)(T_win-1)/(R-1)).  Writes R 1-based steps to
  * steps_out and returns R, or -1 on T < 1, R < 1, eta outside (0, 1] or a NULL pointer. */

@@ -114,18 +114,37 @@ pulsecol_status check_ptrs(pulsecol_ctx* ctx, std::initializer_list<const void*>
     return PULSECOL_OK;
 }
 
-// scores of the current Q, K into `out` (two launches: row pass, column pass)
-pulsecol_status run_scores(pulsecol_ctx* ctx, const void* Q, const void* K, float* out, hipStream_t s) {
-    pulsecol::AttnParams ap = attn_params(ctx, Q, K, nullptr, nullptr, nullptr, ctx->shape.seq, ctx->lse, 1);
-    hipError_t e = launch_attn(ctx, ap, pulsecol::kLseOnly, s);
-    if (e != hipSuccess) return fail_hip(ctx, e, "row log-sum-exp kernel");
+// column pass of the scoring stage: ctx->lse (log2 units) must hold the row log-sum-exp of Q, K
+pulsecol_status run_colmass(pulsecol_ctx* ctx, const void* Q, const void* K, float* out, hipStream_t s) {
     pulsecol::ScoreParams sp{};
     sp.q = Q; sp.k = K; sp.lse = ctx->lse; sp.scores = out; sp.td = ctx->td;
     sp.batch = ctx->shape.batch; sp.heads = ctx->shape.heads; sp.n = ctx->shape.seq; sp.scale = ctx->scale;
     sp.groups = ctx->groups; sp.group_size = ctx->shape.group_size;
-    e = ctx->shape.dtype == PULSECOL_BF16 ? pulsecol::launch_colmass_bf16(sp, ctx->shape.head_dim, s)
-                                          : pulsecol::launch_colmass_f32(sp, ctx->shape.head_dim, s);
+    const hipError_t e = ctx->shape.dtype == PULSECOL_BF16 ? pulsecol::launch_colmass_bf16(sp, ctx->shape.head_dim, s)
+                                                           : pulsecol::launch_colmass_f32(sp, ctx->shape.head_dim, s);
     if (e != hipSuccess) return fail_hip(ctx, e, "column-mass kernel");
+    return PULSECOL_OK;
+}
+
+// scores of the current Q, K into `out` (two launches: row pass, column pass)
+pulsecol_status run_scores(pulsecol_ctx* ctx, const void* Q, const void* K, float* out, hipStream_t s) {
+    pulsecol::AttnParams ap = attn_params(ctx, Q, K, nullptr, nullptr, nullptr, ctx->shape.seq, ctx->lse, 1);
+    const hipError_t e = launch_attn(ctx, ap, pulsecol::kLseOnly, s);
+    if (e != hipSuccess) return fail_hip(ctx, e, "row log-sum-exp kernel");
+    return run_colmass(ctx, Q, K, out, s);
+}
+
+// top-k of ctx->scores into idx_out, and into the context's cache
+pulsecol_status run_topk(pulsecol_ctx* ctx, const float* scores, int32_t k, int32_t* out, hipStream_t s);
+
+pulsecol_status select_from_scores(pulsecol_ctx* ctx, int32_t k, int32_t* idx_out, hipStream_t s, const char* who) {
+    pulsecol_status st = run_topk(ctx, ctx->scores, k, idx_out, s);
+    if (st != PULSECOL_OK) return st;
+    ctx->cached_k = 0;
+    const size_t idx_bytes = (size_t)ctx->shape.batch * ctx->shape.heads * ctx->groups * (size_t)k * sizeof(int32_t);
+    const hipError_t e = hipMemcpyAsync(ctx->cached_idx, idx_out, idx_bytes, hipMemcpyDeviceToDevice, s);
+    if (e != hipSuccess) return fail_hip(ctx, e, (std::string(who) + ": caching the pattern").c_str());
+    ctx->cached_k = k;
     return PULSECOL_OK;
 }
 
@@ -245,13 +264,27 @@ pulsecol_status pulsecol_select(pulsecol_ctx* ctx, const void* Q, const void* K,
     if (guard.err != hipSuccess) return fail_hip(ctx, guard.err, "pulsecol_select: hipSetDevice");
     st = run_scores(ctx, Q, K, ctx->scores, s);
     if (st != PULSECOL_OK) return st;
-    st = run_topk(ctx, ctx->scores, k, idx_out, s);
+    return select_from_scores(ctx, k, idx_out, s, "pulsecol_select");
+}
+
+pulsecol_status pulsecol_refresh_dense(pulsecol_ctx* ctx, const void* Q, const void* K, const void* V,
+                                       double keep_ratio, void* O, int32_t* idx_out, void* stream) {
+    if (!ctx) return fail(nullptr, PULSECOL_ERR_INVALID_ARG, "pulsecol_refresh_dense: ctx is NULL");
+    if (!idx_out) return fail(ctx, PULSECOL_ERR_INVALID_ARG, "pulsecol_refresh_dense: idx_out is NULL");
+    const int32_t k = pulsecol_num_keep(ctx->shape.seq, keep_ratio);
+    if (k < 0) return fail(ctx, PULSECOL_ERR_INVALID_ARG, "pulsecol_refresh_dense: keep_ratio must be in (0, 1]");
+    pulsecol_status st = check_ptrs(ctx, {Q, K, V, O}, "pulsecol_refresh_dense");
     if (st != PULSECOL_OK) return st;
-    ctx->cached_k = 0;
-    const hipError_t e = hipMemcpyAsync(ctx->cached_idx, idx_out, idx_bytes, hipMemcpyDeviceToDevice, s);
-    if (e != hipSuccess) return fail_hip(ctx, e, "pulsecol_select: caching the pattern");
-    ctx->cached_k = k;
-    return PULSECOL_OK;
+    DeviceGuard guard(ctx->device);
+    if (guard.err != hipSuccess) return fail_hip(ctx, guard.err, "pulsecol_refresh_dense: hipSetDevice");
+    hipStream_t s = (hipStream_t)stream;
+    // dense attention that leaves the row log-sum-exp (log2 units) where the column pass reads it
+    const pulsecol::AttnParams p = attn_params(ctx, Q, K, V, O, nullptr, ctx->shape.seq, ctx->lse, 1);
+    const hipError_t e = launch_attn(ctx, p, pulsecol::kDense, s);
+    if (e != hipSuccess) return fail_hip(ctx, e, "dense attention kernel");
+    st = run_colmass(ctx, Q, K, ctx->scores, s);
+    if (st != PULSECOL_OK) return st;
+    return select_from_scores(ctx, k, idx_out, s, "pulsecol_refresh_dense");
 }
 
 pulsecol_status pulsecol_attn(pulsecol_ctx* ctx, const void* Q, const void* K, const void* V, const int32_t* idx,

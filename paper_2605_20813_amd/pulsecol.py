@@ -22,6 +22,7 @@ BF16, F32 = 0, 1
 EXPORTS = (
     "pulsecol_validate_shape", "pulsecol_create", "pulsecol_destroy", "pulsecol_num_keep",
     "pulsecol_select", "pulsecol_scores", "pulsecol_topk", "pulsecol_attn", "pulsecol_attn_dense",
+    "pulsecol_refresh_dense",
     "pulsecol_refresh_schedule", "pulsecol_attn_tile_shape", "pulsecol_status_str", "pulsecol_last_error",
 )
 
@@ -59,6 +60,7 @@ def lib() -> ctypes.CDLL:
         L.pulsecol_topk.argtypes = [c_void_p, c_void_p, c_int32, c_void_p, c_void_p]
         L.pulsecol_attn.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_void_p]
         L.pulsecol_attn_dense.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+        L.pulsecol_refresh_dense.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_double, c_void_p, c_void_p, c_void_p]
         L.pulsecol_refresh_schedule.argtypes = [c_int32, c_double, c_int32, POINTER(c_int32)]
         L.pulsecol_refresh_schedule.restype = c_int32
         L.pulsecol_attn_tile_shape.argtypes = [c_void_p, POINTER(c_int32), POINTER(c_int32)]
@@ -221,6 +223,24 @@ class Context:
             self._check_tensor(O, "O")
         self._check(lib().pulsecol_attn(self._h, _ptr(Q), _ptr(K), _ptr(V), _ptr(idx), idx.shape[3], _ptr(O), _stream()))
         return O
+
+    def refresh_dense(self, Q, K, V, keep_ratio: float, O=None, idx_out=None):
+        """Dense output and the new pattern of a refresh step in one call; returns (O, idx)."""
+        for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):
+            self._check_tensor(t, nm)
+        s = self.shape
+        k = num_keep(s.seq, keep_ratio)
+        if k < 0:
+            raise PulseColError(ERR_INVALID_ARG, "keep_ratio must be in (0, 1]")
+        if O is None:
+            O = torch.empty_like(Q)
+        else:
+            self._check_tensor(O, "O")
+        if idx_out is None:
+            idx_out = torch.empty(s.batch, s.heads, self.groups, k, dtype=torch.int32, device=self.device)
+        self._check(lib().pulsecol_refresh_dense(self._h, _ptr(Q), _ptr(K), _ptr(V), keep_ratio, _ptr(O),
+                                                 _ptr(idx_out), _stream()))
+        return O, idx_out
 
     def attn_dense(self, Q, K, V, O=None, lse_out=None):
         for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):

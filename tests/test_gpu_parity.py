@@ -295,3 +295,28 @@ def test_error_paths_on_device():
         assert torch.isfinite(O.float()).all()
     with pytest.raises(pc.PulseColError):
         pc.Context(1, 2, 256, 128, torch.bfloat16, device=99)
+
+
+# ---------------------------------------------------------------------------------------
+# refresh step that keeps the dense output
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n,d,dtype,keep", [(1000, 128, torch.bfloat16, 0.1), (700, 64, torch.bfloat16, 0.2),
+                                            (333, 128, torch.float32, 0.25)])
+def test_refresh_dense_gives_dense_output_and_the_select_pattern(n, d, dtype, keep):
+    B, H = 1, 3
+    say(f"refresh_dense case n={n} d={d} {dtype} keep={keep}")
+    Q, K, V = rand_qkv(B, H, n, d, dtype, seed=8000 + n)
+    K[:, :, 3::11] *= 2.5
+    k = oracle.num_keep(n, keep)
+    with pc.Context(B, H, n, d, dtype) as ctx:
+        q, k_, v = Q.to(DEV), K.to(DEV), V.to(DEV)
+        O, idx = ctx.refresh_dense(q, k_, v, keep)
+        cached = ctx.select(None, None, keep, refresh=False)
+        Od = ctx.attn_dense(q, k_, v)
+        torch.cuda.synchronize()
+    assert torch.equal(O, Od)                   # the same kernel with one more output
+    assert torch.equal(idx, cached)             # the pattern is cached like select's
+    for h in range(H):
+        qh, kh, vh = f64(Q[0, h]), f64(K[0, h]), f64(V[0, h])
+        assert_close(O[0, h], oracle.dense_attention(qh, kh, vh), kind_of(dtype), f"refresh_dense O head {h}")
+        assert_idx_matches(idx[0, h, 0].cpu().numpy(), oracle.column_scores(qh, kh)[0], k, f"refresh_dense idx head {h}")
