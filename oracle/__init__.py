@@ -12,6 +12,8 @@ from .pulsecol_oracle import (  # noqa: F401
     dense_attention,
     num_keep,
     refresh_schedule,
+    refresh_schedule_power,
+    refresh_schedule_random,
     row_softmax,
     select_columns,
     sparse_attention_masked,

@@ -247,3 +247,42 @@ def refresh_schedule(T: int, eta: float, R: int) -> list[int]:
     if R == 1:
         return [1]
     return [1 + ((r - 1) * (T_win - 1)) // (R - 1) for r in range(1, R + 1)]
+
+
+def refresh_schedule_power(T: int, eta: float, R: int) -> list[int]:
+    """Power-based placement of the refresh steps (appendix, ablation on the refresh
+    schedule): normalised positions (i/(R-1))^2, i = 0..R-1, inside the same early window of
+    T_win = floor(eta T) steps, mapped to 1-based steps like the default schedule:
+    tau_i = 1 + floor((i/(R-1))^2 (T_win-1)).  Exact rational arithmetic.
+    """
+    if T < 1 or R < 1 or not (0.0 < eta <= 1.0):
+        raise ValueError("need T >= 1, R >= 1, 0 < eta <= 1")
+    T_win = max(1, _floor_of_product(eta, T))
+    if R == 1:
+        return [1]
+    return [1 + int(Fraction(i * i, (R - 1) * (R - 1)) * (T_win - 1)) for i in range(R)]
+
+
+def refresh_schedule_random(T: int, eta: float, R: int, uniforms) -> list[int]:
+    """Random placement (same appendix): R distinct refresh steps drawn uniformly from the
+    window 1..T_win, returned ascending.  Step 1 always belongs to the set (a pattern must
+    exist before the first sparse step); the other R-1 steps are a uniform draw without
+    replacement from 2..T_win, taken from the caller's uniforms u_0..u_{R-2} in [0, 1) by a
+    partial Fisher-Yates shuffle: at draw i the pool position i + floor(u_i (m - i)) is swapped
+    to the front, m = T_win - 1.
+    """
+    if T < 1 or R < 1 or not (0.0 < eta <= 1.0):
+        raise ValueError("need T >= 1, R >= 1, 0 < eta <= 1")
+    T_win = max(1, _floor_of_product(eta, T))
+    m = T_win - 1
+    if R - 1 > m:
+        raise ValueError("the window holds fewer than R steps")
+    u = [float(x) for x in uniforms]
+    if len(u) < R - 1 or any(not (0.0 <= x < 1.0) for x in u[:R - 1]):
+        raise ValueError("need R-1 uniforms in [0, 1)")
+    pool = list(range(2, T_win + 1))
+    for i in range(R - 1):
+        j = i + int(math.floor(u[i] * (m - i)))
+        pool[i], pool[j] = pool[j], pool[i]
+    return sorted([1] + pool[:R - 1])
+

@@ -213,6 +213,40 @@ def pin_schedule(o):
         assert all(a <= b for a, b in zip(tau, tau[1:])) and max(tau) <= T_win
 
 
+def pin_schedule_variants(o):
+    with open(os.path.join(GOLDEN, "schedule_variants.json")) as f:
+        g = json.load(f)
+    for c in g["power"]:
+        assert o.refresh_schedule_power(c["T"], c["eta"], c["R"]) == c["tau"], c
+    for c in g["random"]:
+        assert o.refresh_schedule_random(c["T"], c["eta"], c["R"], c["uniforms"]) == c["tau"], c
+    # power: same end points as the default schedule, non-decreasing, gaps that grow (refreshes
+    # concentrated at the beginning of the window)
+    for T, eta, R in ((1000, .3, 16), (500, .5, 9), (200, 1.0, 5)):
+        tau = o.refresh_schedule_power(T, eta, R)
+        uni = o.refresh_schedule(T, eta, R)
+        assert len(tau) == R and tau[0] == uni[0] == 1 and tau[-1] == uni[-1]
+        gaps = [b - a for a, b in zip(tau, tau[1:])]
+        assert all(g >= 0 for g in gaps) and all(b >= a - 1 for a, b in zip(gaps, gaps[1:]))
+        assert all(p <= u for p, u in zip(tau, uni))            # never later than the uniform placement
+    # random: R distinct steps inside the window, step 1 among them; every other step of the
+    # window is drawn equally often (exhaustive over a grid of uniforms on a tiny window)
+    rng = np.random.default_rng(5)
+    for T, eta, R in ((100, .3, 8), (64, .5, 32), (40, 1.0, 2)):
+        T_win = max(1, math.floor(Fraction(repr(eta)) * T))
+        tau = o.refresh_schedule_random(T, eta, R, rng.random(R - 1).tolist())
+        assert len(tau) == R == len(set(tau)) and tau == sorted(tau) and tau[0] == 1 and tau[-1] <= T_win
+    counts = {}
+    grid = [(a + .5) / 12 for a in range(12)]
+    for u0 in grid:
+        for u1 in grid:
+            for s_ in o.refresh_schedule_random(10, .5, 3, [u0, u1])[1:]:
+                counts[s_] = counts.get(s_, 0) + 1
+    assert sorted(counts) == [2, 3, 4, 5] and len(set(counts.values())) == 1
+    with pytest.raises(ValueError):
+        o.refresh_schedule_random(10, .3, 5, [.1, .2, .3, .4])     # window of 3 steps cannot hold 5
+
+
 def pin_planted_columns_selected(o):
     w = wl.WORKLOADS["tiny"]
     for h in range(w.heads):
@@ -224,7 +258,7 @@ def pin_planted_columns_selected(o):
 
 PINS = [pin_closed_form, pin_dense_matches_library, pin_scores_invariants, pin_topk_bruteforce,
         pin_topk_order_and_ties, pin_sparse_attention_properties, pin_scale_override, pin_num_keep,
-        pin_schedule, pin_planted_columns_selected]
+        pin_schedule, pin_schedule_variants, pin_planted_columns_selected]
 
 
 @pytest.mark.parametrize("pin", PINS, ids=lambda p: p.__name__)
@@ -323,6 +357,38 @@ def _schedule_window_not_minus_one(T, eta, R):
     return [1 + ((r - 1) * T_win) // (R - 1) for r in range(1, R + 1)]
 
 
+def _power_linear(T, eta, R):
+    T_win = max(1, _floor_of_product(eta, T))
+    if R == 1:
+        return [1]
+    return [1 + int(Fraction(i, R - 1) * (T_win - 1)) for i in range(R)]
+
+
+def _power_whole_window(T, eta, R):
+    T_win = max(1, _floor_of_product(eta, T))
+    if R == 1:
+        return [1]
+    return [1 + int(Fraction(i * i, (R - 1) * (R - 1)) * T_win) for i in range(R)]
+
+
+def _random_with_replacement(T, eta, R, uniforms):
+    T_win = max(1, _floor_of_product(eta, T))
+    m = T_win - 1
+    if R - 1 > m:
+        raise ValueError
+    return sorted([1] + [2 + int(math.floor(float(u) * m)) for u in list(uniforms)[:R - 1]])
+
+
+def _random_without_first_step(T, eta, R, uniforms):
+    T_win = max(1, _floor_of_product(eta, T))
+    pool = list(range(1, T_win + 1))
+    u = [float(x) for x in uniforms] + [0.5]
+    for i in range(R):
+        j = i + int(math.floor(u[i] * (T_win - i)))
+        pool[i], pool[j] = pool[j], pool[i]
+    return sorted(pool[:R])
+
+
 def _num_keep_ceil(n, keep_ratio):
     if n < 1 or not (0.0 < keep_ratio <= 1.0):
         raise ValueError
@@ -342,6 +408,10 @@ MUTANTS = {
     "schedule_zero_based": dict(refresh_schedule=_schedule_zero_based),
     "schedule_full_window": dict(refresh_schedule=_schedule_window_not_minus_one),
     "num_keep_ceil": dict(num_keep=_num_keep_ceil),
+    "power_schedule_linear": dict(refresh_schedule_power=_power_linear),
+    "power_schedule_whole_window": dict(refresh_schedule_power=_power_whole_window),
+    "random_schedule_with_replacement": dict(refresh_schedule_random=_random_with_replacement),
+    "random_schedule_without_first_step": dict(refresh_schedule_random=_random_without_first_step),
 }
 
 
