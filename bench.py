@@ -40,6 +40,7 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-probes", action="store_true", help="skip the MFMA-only / copy roofline probes")
     ap.add_argument("--no-32k", action="store_true", help="skip the short side measurement at 32K context")
+    ap.add_argument("--no-layers", action="store_true", help="skip the short multi-layer schedule run")
     ap.add_argument("--no-groups", action="store_true", help="skip the short side measurement with group-wise column sets")
     ap.add_argument("--cold-steps", type=int, default=8,
                     help="extra attention launches timed with a 1 GiB buffer overwritten before each (caches evicted)")
@@ -207,6 +208,8 @@ def main():
     torch.cuda.empty_cache()
     if not a.no_32k and a.workload == "llada_64k":
         out["context_32k"] = side_config(pc, wl, torch, dev, "llada_32k")
+    if not a.no_layers and a.workload == "llada_64k":
+        out["multilayer"] = multilayer_run(pc, wl, torch, dev, w, keep)
     if not a.no_groups and a.workload == "llada_64k":
         out["groupwise"] = groupwise_config(pc, wl, torch, dev, w, keep)
     if not a.no_probes:
@@ -248,6 +251,30 @@ def side_config(pc, wl, torch, dev, name):
                                   "speedup_vs_dense_launch": round(res["dense_ms"] / attn_ms, 2)}
     ctx.close()
     return res
+
+
+def multilayer_run(pc, wl, torch, dev, w, keep):
+    """A short run of the schedule driver: 4 layers (each with its own cached pattern), 32
+    denoising steps, refreshes placed by the schedule equation in a window of eta = 0.5 with
+    R = 4 -- every select and every attention launch runs for real; all layers see the same
+    synthetic Q, K, V."""
+    from paper_2605_20813_amd import schedule as sch
+    B, H, n, d = w.batch, w.heads, w.seq, w.head_dim
+    L, T, eta, R = 4, 32, 0.5, 4
+    steps = sch.refresh_steps(T, eta, R)
+    Q, K, V = (t.to(dev) for t in wl.make_qkv(w))
+    out = [torch.empty_like(Q) for _ in range(L)]
+    qkv = [(Q, K, V)] * L
+    with sch.LayerStack(L, B, H, n, d, w.torch_dtype, keep, steps) as stack:
+        stack.step(0, qkv, out)                     # warm-up (also allocates the index tensors)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        selects = sum(stack.step(t, qkv, out) for t in range(T))
+        torch.cuda.synchronize()
+        total_ms = (time.perf_counter() - t0) * 1e3
+    return {"layers": L, "steps": T, "eta": eta, "R": R, "kind": "uniform", "refresh_steps": steps,
+            "selects_run": selects, "total_ms": round(total_ms, 1),
+            "ms_per_layer_step": round(total_ms / (L * T), 4)}
 
 
 def groupwise_config(pc, wl, torch, dev, w, keep):

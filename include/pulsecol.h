@@ -148,6 +148,21 @@ PULSECOL_API pulsecol_status pulsecol_refresh_dense(pulsecol_ctx* ctx, const voi
  * steps_out and returns R, or -1 on T < 1, R < 1, eta outside (0, 1] or a NULL pointer. */
 PULSECOL_API int32_t pulsecol_refresh_schedule(int32_t T, double eta, int32_t R, int32_t* steps_out);
 
+/* The two alternative placements of the appendix's ablation on the refresh schedule, same
+ * window T_win and budget R, host only, 1-based steps, ascending.
+ *   power:  normalised positions (i/(R-1))^2, i = 0..R-1: tau_i = 1 + floor(i^2 (T_win-1) / (R-1)^2)
+ *           (refreshes concentrated at the beginning of the window; steps may repeat).
+ *   random: R distinct steps of the window: step 1 (a pattern must exist before the first
+ *           sparse step) and R-1 steps drawn without replacement from 2..T_win by a partial
+ *           Fisher-Yates shuffle that consumes uniforms[0..R-2], each in [0, 1): draw i takes
+ *           pool position i + floor(uniforms[i] * (T_win-1 - i)).  The caller owns the random
+ *           numbers, so a schedule is reproducible from them.
+ * Return R, or -1 on the argument errors of pulsecol_refresh_schedule, a uniform outside
+ * [0, 1), or (random) a window with fewer than R steps. */
+PULSECOL_API int32_t pulsecol_refresh_schedule_power(int32_t T, double eta, int32_t R, int32_t* steps_out);
+PULSECOL_API int32_t pulsecol_refresh_schedule_random(int32_t T, double eta, int32_t R, const double* uniforms,
+                                         int32_t* steps_out);
+
 /* Launch geometry of the sparse kernel for this context (for reports): query rows per
  * workgroup (B_M) and gathered columns per tile (B_N).  Host only. */
 PULSECOL_API pulsecol_status pulsecol_attn_tile_shape(const pulsecol_ctx* ctx, int32_t* block_m, int32_t* block_n);

@@ -4,10 +4,12 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <new>
 #include <string>
+#include <vector>
 
 #include "pulsecol_kernels.h"
 
@@ -321,6 +323,37 @@ int32_t pulsecol_refresh_schedule(int32_t T, double eta, int32_t R, int32_t* ste
     if (t_win < 1) t_win = 1;
     if (R == 1) { steps_out[0] = 1; return 1; }
     for (int64_t r = 1; r <= R; ++r) steps_out[r - 1] = (int32_t)(1 + ((r - 1) * (t_win - 1)) / (R - 1));
+    return R;
+}
+
+int32_t pulsecol_refresh_schedule_power(int32_t T, double eta, int32_t R, int32_t* steps_out) {
+    if (T < 1 || R < 1 || !(eta > 0.0) || !(eta <= 1.0) || !steps_out) return -1;
+    int64_t t_win = floor_product(eta, T);
+    if (t_win < 1) t_win = 1;
+    if (R == 1) { steps_out[0] = 1; return 1; }
+    const int64_t den = (int64_t)(R - 1) * (R - 1);
+    for (int64_t i = 0; i < R; ++i) steps_out[i] = (int32_t)(1 + (i * i * (t_win - 1)) / den);
+    return R;
+}
+
+int32_t pulsecol_refresh_schedule_random(int32_t T, double eta, int32_t R, const double* uniforms, int32_t* steps_out) {
+    if (T < 1 || R < 1 || !(eta > 0.0) || !(eta <= 1.0) || !steps_out) return -1;
+    int64_t t_win = floor_product(eta, T);
+    if (t_win < 1) t_win = 1;
+    const int64_t m = t_win - 1;
+    if (R - 1 > m) return -1;
+    if (R > 1 && !uniforms) return -1;
+    for (int32_t i = 0; i + 1 < R; ++i)
+        if (!(uniforms[i] >= 0.0) || !(uniforms[i] < 1.0)) return -1;
+    std::vector<int32_t> pool((size_t)m);
+    for (int64_t i = 0; i < m; ++i) pool[(size_t)i] = (int32_t)(i + 2);
+    for (int64_t i = 0; i + 1 < R; ++i) {
+        const int64_t j = i + (int64_t)std::floor(uniforms[i] * (double)(m - i));
+        std::swap(pool[(size_t)i], pool[(size_t)j]);
+    }
+    steps_out[0] = 1;
+    for (int32_t i = 0; i + 1 < R; ++i) steps_out[i + 1] = pool[(size_t)i];
+    std::sort(steps_out + 1, steps_out + R);
     return R;
 }
 

@@ -23,7 +23,8 @@ EXPORTS = (
     "pulsecol_validate_shape", "pulsecol_create", "pulsecol_destroy", "pulsecol_num_keep",
     "pulsecol_select", "pulsecol_scores", "pulsecol_topk", "pulsecol_attn", "pulsecol_attn_dense",
     "pulsecol_refresh_dense",
-    "pulsecol_refresh_schedule", "pulsecol_attn_tile_shape", "pulsecol_status_str", "pulsecol_last_error",
+    "pulsecol_refresh_schedule", "pulsecol_refresh_schedule_power", "pulsecol_refresh_schedule_random",
+    "pulsecol_attn_tile_shape", "pulsecol_status_str", "pulsecol_last_error",
 )
 
 
@@ -63,6 +64,10 @@ def lib() -> ctypes.CDLL:
         L.pulsecol_refresh_dense.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_double, c_void_p, c_void_p, c_void_p]
         L.pulsecol_refresh_schedule.argtypes = [c_int32, c_double, c_int32, POINTER(c_int32)]
         L.pulsecol_refresh_schedule.restype = c_int32
+        L.pulsecol_refresh_schedule_power.argtypes = [c_int32, c_double, c_int32, POINTER(c_int32)]
+        L.pulsecol_refresh_schedule_power.restype = c_int32
+        L.pulsecol_refresh_schedule_random.argtypes = [c_int32, c_double, c_int32, POINTER(c_double), POINTER(c_int32)]
+        L.pulsecol_refresh_schedule_random.restype = c_int32
         L.pulsecol_attn_tile_shape.argtypes = [c_void_p, POINTER(c_int32), POINTER(c_int32)]
         L.pulsecol_status_str.argtypes = [c_int]
         L.pulsecol_status_str.restype = c_char_p
@@ -97,6 +102,26 @@ def refresh_schedule(T: int, eta: float, R: int):
     r = lib().pulsecol_refresh_schedule(T, eta, R, buf)
     if r < 0:
         raise PulseColError(ERR_INVALID_ARG, "pulsecol_refresh_schedule: bad arguments")
+    return list(buf[:r])
+
+
+def refresh_schedule_power(T: int, eta: float, R: int):
+    buf = (c_int32 * max(R, 1))()
+    r = lib().pulsecol_refresh_schedule_power(T, eta, R, buf)
+    if r < 0:
+        raise PulseColError(ERR_INVALID_ARG, "pulsecol_refresh_schedule_power: bad arguments")
+    return list(buf[:r])
+
+
+def refresh_schedule_random(T: int, eta: float, R: int, uniforms):
+    u = [float(x) for x in uniforms]
+    buf = (c_int32 * max(R, 1))()
+    ubuf = (c_double * max(len(u), 1))(*u)
+    if len(u) < R - 1:
+        raise PulseColError(ERR_INVALID_ARG, "pulsecol_refresh_schedule_random: need R-1 uniforms")
+    r = lib().pulsecol_refresh_schedule_random(T, eta, R, ubuf, buf)
+    if r < 0:
+        raise PulseColError(ERR_INVALID_ARG, "pulsecol_refresh_schedule_random: bad arguments")
     return list(buf[:r])
 
 

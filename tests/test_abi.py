@@ -7,6 +7,7 @@ import json
 import os
 import re
 
+import numpy as np
 import pytest
 import torch
 
@@ -91,6 +92,38 @@ def test_refresh_schedule_matches_golden_and_oracle():
         pc.refresh_schedule(0, .3, 4)
     with pytest.raises(pc.PulseColError):
         pc.refresh_schedule(10, 1.5, 4)
+
+
+def test_schedule_variants_match_golden_and_oracle():
+    with open(os.path.join(ROOT, "tests", "golden", "schedule_variants.json")) as f:
+        g = json.load(f)
+    for c in g["power"]:
+        assert pc.refresh_schedule_power(c["T"], c["eta"], c["R"]) == c["tau"]
+    for c in g["random"]:
+        assert pc.refresh_schedule_random(c["T"], c["eta"], c["R"], c["uniforms"]) == c["tau"]
+    rng = np.random.default_rng(11)
+    for T, eta, R in ((100, .5, 7), (1000, .3, 16), (17, 1.0, 17), (50, .1, 3), (100, .29, 5), (1024, .3, 64)):
+        assert pc.refresh_schedule_power(T, eta, R) == oracle.refresh_schedule_power(T, eta, R)
+        u = rng.random(R - 1).tolist()
+        assert pc.refresh_schedule_random(T, eta, R, u) == oracle.refresh_schedule_random(T, eta, R, u)
+    for bad in ((10, .3, 5, [.1, .2, .3, .4]), (10, 1.0, 3, [.5, 1.0]), (10, 1.0, 3, [-.1, .2]), (0, .5, 2, [.5])):
+        with pytest.raises(pc.PulseColError):
+            pc.refresh_schedule_random(*bad)
+    with pytest.raises(pc.PulseColError):
+        pc.refresh_schedule_power(10, 0.0, 3)
+
+
+def test_schedule_driver_steps():
+    from paper_2605_20813_amd import schedule as sch
+    assert sch.refresh_steps(1024, .3, 4) == [0, 102, 204, 306]
+    assert sch.refresh_steps(110, .3, 3) == [0, 16, 32]
+    assert sch.refresh_steps(100, .3, 4, "power") == [0, 3, 12, 29]
+    assert sch.refresh_steps(20, .5, 4, "random", [0.0, 0.5, 0.99]) == [0, 1, 6, 9]
+    assert sch.refresh_steps(128, .3, 8, "power") == [0, 3, 6, 12, 18, 27, 37]      # a repeated step counts once
+    with pytest.raises(ValueError):
+        sch.refresh_steps(10, .5, 2, "random")
+    with pytest.raises(ValueError):
+        sch.refresh_steps(10, .5, 2, "sometimes")
 
 
 def test_null_context_calls_fail_cleanly():

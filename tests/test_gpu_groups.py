@@ -133,3 +133,40 @@ def test_groups_differ_from_one_set_per_head():
         torch.cuda.synchronize()
     assert set(idx[0, 0, 0].tolist()) == set(cols_a.tolist())
     assert set(idx[0, 0, 1].tolist()) == set(cols_b.tolist())
+
+
+def test_layer_stack_follows_the_schedule():
+    """Three layers, eight steps, refresh at steps 0 and 3: every layer's output at every step
+    equals what the single calls give, and the pattern only changes at refresh steps."""
+    from paper_2605_20813_amd import schedule as sch
+    B, H, n, d, keep, L, T = 1, 2, 512, 128, 0.2, 3, 8
+    say("layer stack case")
+    steps = sch.refresh_steps(T, 0.5, 2)
+    assert steps == [0, 3]
+    g = torch.Generator(device="cpu")
+    g.manual_seed(123)
+    base = [tuple(torch.randn(B, H, n, d, generator=g).to(torch.bfloat16).to(DEV) for _ in range(3)) for _ in range(L)]
+    out = [torch.empty(B, H, n, d, dtype=torch.bfloat16, device=DEV) for _ in range(L)]
+    with sch.LayerStack(L, B, H, n, d, torch.bfloat16, keep, steps) as stack, \
+            pc.Context(B, H, n, d, torch.bfloat16) as ref:
+        patterns = [None] * L
+        for t in range(T):
+            # the activations drift a little from step to step
+            qkv = [tuple((x.float() * (1.0 + 0.01 * t)).to(torch.bfloat16) for x in base[l]) for l in range(L)]
+            assert stack.step(t, qkv, out) == (L if t in steps else 0)
+            for l in range(L):
+                Q, K, V = qkv[l]
+                if t in steps:
+                    patterns[l] = ref.select(Q, K, keep).clone()
+                assert torch.equal(stack.idx[l], patterns[l])
+                assert torch.equal(out[l], ref.attn(Q, K, V, patterns[l]))
+        torch.cuda.synchronize()
+    # dense output at refresh steps
+    with sch.LayerStack(1, B, H, n, d, torch.bfloat16, keep, [0], dense_at_refresh=True) as stack, \
+            pc.Context(B, H, n, d, torch.bfloat16) as ref:
+        Q, K, V = base[0]
+        stack.step(0, [base[0]], out[:1])
+        assert torch.equal(out[0], ref.attn_dense(Q, K, V))
+        stack.step(1, [base[0]], out[:1])
+        assert torch.equal(out[0], ref.attn(Q, K, V, stack.idx[0]))
+        torch.cuda.synchronize()
