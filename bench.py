@@ -211,7 +211,7 @@ def main():
     if not a.no_layers and a.workload == "llada_64k":
         out["multilayer"] = multilayer_run(pc, wl, torch, dev, w, keep)
     if not a.no_groups and a.workload == "llada_64k":
-        out["groupwise"] = groupwise_config(pc, wl, torch, dev, w, keep)
+        out["groupwise"] = [groupwise_config(pc, wl, torch, dev, w, keep, G) for G in (256, 128)]
     if not a.no_probes:
         out["probes"] = roofline_probes(achieved, dense_ms and dense_flop / (dense_ms * 1e-3) * 1e-12)
     if not a.no_cpu:
@@ -277,13 +277,12 @@ def multilayer_run(pc, wl, torch, dev, w, keep):
             "ms_per_layer_step": round(total_ms / (L * T), 4)}
 
 
-def groupwise_config(pc, wl, torch, dev, w, keep):
-    """The paper's own pattern format at the headline shape: one column set per query group,
-    groups = query blocks of 256 rows.  The score pass writes [B,H,U,n] fp32, top-k runs over
-    B*H*U rows (the memory-bound stage), and the attention gathers are no longer shared between
-    the query blocks of a head."""
+def groupwise_config(pc, wl, torch, dev, w, keep, G):
+    """The paper's own pattern format at the headline shape: one column set per query group of
+    G rows (256: the main kernel's query block; 128: the paper's largest group size, small-group
+    kernel).  The score pass writes [B,H,U,n] fp32, top-k runs over B*H*U rows (the memory-bound
+    stage), and the attention gathers are no longer shared between the query blocks of a head."""
     B, H, n, d = w.batch, w.heads, w.seq, w.head_dim
-    G = 256
     Q, K, V = (t.to(dev) for t in wl.make_qkv(w))
     O = torch.empty_like(Q)
     ctx = pc.Context(B, H, n, d, w.torch_dtype, group_size=G)
@@ -306,7 +305,7 @@ def groupwise_config(pc, wl, torch, dev, w, keep):
     scores_ms = timed(lambda: ctx.scores(Q, K, scores_out=scores), 2)
     topk_ms = timed(lambda: ctx.topk(scores, k, idx_out=idx), 3)
     select_ms = timed(lambda: ctx.select(Q, K, keep, refresh=True, idx_out=idx), 1)
-    attn_ms = timed(lambda: ctx.attn(Q, K, V, idx, O=O), 10)
+    attn_ms = timed(lambda: ctx.attn(Q, K, V, idx, O=O), 10 if G >= 256 else 4)
     topk_bytes = B * H * U * (5 * 4 * n + 4 * k)
     gather_bytes = B * H * U * 2 * k * d * 2 + 2 * B * H * n * d * 2      # K and V rows per group, Q, O
     res = {"group_size": G, "groups_per_head": U, "k": k,
@@ -316,6 +315,8 @@ def groupwise_config(pc, wl, torch, dev, w, keep):
            "kept_tflops": round(4.0 * B * H * n * k * d / (attn_ms * 1e-3) * 1e-12, 2),
            "attn_requested_gbps": round(gather_bytes / (attn_ms * 1e-3) * 1e-9, 1)}
     ctx.close()
+    del Q, K, V, O, idx, scores
+    torch.cuda.empty_cache()
     return res
 
 

@@ -70,9 +70,9 @@ typedef struct {
                         /* accumulation and fp32 softmax; f32: fp32 throughout.                  */
     int32_t group_size; /* queries per group (Sec. 3.3); 0 or >= seq: the whole head is one group
                          * (U = 1).  Otherwise U = ceil(seq / group_size) groups of consecutive
-                         * rows, and group_size must be a multiple of the attention kernel's query
-                         * block (pulsecol_attn_tile_shape: 256 rows for bf16, 128 for f32), else
-                         * PULSECOL_ERR_UNSUPPORTED                                                */
+                         * rows; bf16: a multiple of 32 (multiples of 256 run in the main kernel,
+                         * smaller ones -- the paper's 32 / 64 / 128 -- in the small-group kernel),
+                         * f32: a multiple of 128; else PULSECOL_ERR_UNSUPPORTED                  */
     int64_t stride_b;   /* element strides of batch, head and sequence; 0 = packed.  Multiples of 16 bytes;
                          * bf16: the sequence stride is below 2^24 bytes and one head spans less than
                          * 4 GiB (seq * stride_n), else PULSECOL_ERR_UNSUPPORTED                  */

@@ -131,32 +131,34 @@ __global__ void __launch_bounds__(NTHREADS) colmass_bf16_kernel(ScoreParams p) {
                 for (int r = 0; r < 16; ++r)
                     acc_short[kb][r & 3] += fast_exp2(__builtin_fmaf(s[kb][qb][r], c2, -l2[r >> 2][r & 3]));
             }
-        }
-        if ((t % FLUSH) == FLUSH - 1) {
+            if (qb == 1 && (t % FLUSH) == FLUSH - 1) {
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+                for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int c = 0; c < 4; ++c) { acc_long[kb][c] += acc_short[kb][c]; acc_short[kb][c] = 0.f; }
-        }
+                    for (int c = 0; c < 4; ++c) { acc_long[kb][c] += acc_short[kb][c]; acc_short[kb][c] = 0.f; }
+            }
 
-        // ---- last tile of a query group: add the two half-waves (they hold the same key
-        // columns, other query rows), divide by the group's size, store the group's score row
-        const int rows_done = (t + 1) * QT;
-        const bool group_end = t + 1 == ntiles || (p.groups > 1 && rows_done % p.group_size == 0);
-        if (group_end) {
-            const int u = p.groups > 1 ? (t * QT) / p.group_size : 0;
-            const int g_first = p.groups > 1 ? u * p.group_size : 0;
-            const int g_rows = (rows_done < n ? rows_done : n) - g_first;
-            const float inv = 1.0f / (float)g_rows;
-            float* __restrict__ out = p.scores + ((int64_t)bh * p.groups + u) * n;
+            // ---- last rows of a query group (groups are multiples of 32 rows): add the two
+            // half-waves (they hold the same key columns, other query rows), divide by the
+            // group's size, store the group's score row, start over
+            const int rows_done = t * QT + (qb + 1) * 32;
+            const bool group_end = (qb == 1 && t + 1 == ntiles) || (p.groups > 1 && rows_done < n && rows_done % p.group_size == 0);
+            if (group_end) {
+                const int rows_seen = rows_done < n ? rows_done : n;
+                const int u = p.groups > 1 ? (rows_seen - 1) / p.group_size : 0;
+                const int g_first = p.groups > 1 ? u * p.group_size : 0;
+                const int g_rows = rows_seen - g_first;
+                const float inv = 1.0f / (float)g_rows;
+                float* __restrict__ out = p.scores + ((int64_t)bh * p.groups + u) * n;
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                const float v = half_sum(((acc_long[kb][0] + acc_short[kb][0]) + (acc_long[kb][1] + acc_short[kb][1])) +
-                                         ((acc_long[kb][2] + acc_short[kb][2]) + (acc_long[kb][3] + acc_short[kb][3])));
-                const int key = key0 + kb * 32 + lq;
-                if (lh == 0 && key < n) out[key] = v * inv;
+                for (int kb = 0; kb < 2; ++kb) {
+                    const float v = half_sum(((acc_long[kb][0] + acc_short[kb][0]) + (acc_long[kb][1] + acc_short[kb][1])) +
+                                             ((acc_long[kb][2] + acc_short[kb][2]) + (acc_long[kb][3] + acc_short[kb][3])));
+                    const int key = key0 + kb * 32 + lq;
+                    if (lh == 0 && key < n) out[key] = v * inv;
 #pragma unroll
-                for (int c = 0; c < 4; ++c) { acc_long[kb][c] = 0.f; acc_short[kb][c] = 0.f; }
+                    for (int c = 0; c < 4; ++c) { acc_long[kb][c] = 0.f; acc_short[kb][c] = 0.f; }
+                }
             }
         }
 

@@ -59,9 +59,10 @@ pulsecol_status check_shape(const pulsecol_shape* s, std::string* why) {
     if (s->head_dim != 64 && s->head_dim != 128) { *why = "head_dim must be 64 or 128"; return PULSECOL_ERR_UNSUPPORTED; }
     if (s->group_size != 0 && s->group_size < s->seq) {
         // a query block of the attention kernels reads ONE column set: groups are whole query blocks
-        const int bm = s->dtype == PULSECOL_BF16 ? pulsecol::kBlockM_bf16 : pulsecol::kBlockM_f32;
-        if (s->group_size % bm != 0) {
-            *why = "group_size must be 0, >= seq, or a multiple of the query block (256 rows for bf16, 128 for f32)";
+        // (bf16: 256 rows in the main kernel, 128 / 64 / 32 in the small-group kernel; f32: 128)
+        const int unit = s->dtype == PULSECOL_BF16 ? 32 : pulsecol::kBlockM_f32;
+        if (s->group_size % unit != 0) {
+            *why = "group_size must be 0, >= seq, or a multiple of 32 rows (bf16) / 128 rows (f32)";
             return PULSECOL_ERR_UNSUPPORTED;
         }
     }
@@ -103,7 +104,18 @@ pulsecol::AttnParams attn_params(const pulsecol_ctx* c, const void* Q, const voi
     return p;
 }
 
+// query rows per workgroup of the column-sparse kernel this context uses: the largest block
+// that divides the group size
+int sparse_block_m(const pulsecol_ctx* c) {
+    if (c->shape.dtype != PULSECOL_BF16) return pulsecol::kBlockM_f32;
+    if (c->groups == 1) return pulsecol::kBlockM_bf16;
+    for (int bm : {256, 128, 64}) if (c->shape.group_size % bm == 0) return bm;
+    return 32;
+}
+
 hipError_t launch_attn(const pulsecol_ctx* c, const pulsecol::AttnParams& p, pulsecol::AttnMode mode, hipStream_t s) {
+    if (mode == pulsecol::kSparse && c->shape.dtype == PULSECOL_BF16 && sparse_block_m(c) < pulsecol::kBlockM_bf16)
+        return pulsecol::launch_attn_bf16_group(p, c->shape.head_dim, sparse_block_m(c), s);
     return c->shape.dtype == PULSECOL_BF16 ? pulsecol::launch_attn_bf16(p, c->shape.head_dim, mode, s)
                                            : pulsecol::launch_attn_f32(p, c->shape.head_dim, mode, s);
 }
@@ -360,8 +372,8 @@ int32_t pulsecol_refresh_schedule_random(int32_t T, double eta, int32_t R, const
 pulsecol_status pulsecol_attn_tile_shape(const pulsecol_ctx* ctx, int32_t* block_m, int32_t* block_n) {
     if (!ctx || !block_m || !block_n) return fail(nullptr, PULSECOL_ERR_INVALID_ARG, "pulsecol_attn_tile_shape: NULL pointer");
     const bool bf = ctx->shape.dtype == PULSECOL_BF16;
-    *block_m = bf ? pulsecol::kBlockM_bf16 : pulsecol::kBlockM_f32;
-    *block_n = bf ? pulsecol::kBlockN_bf16 : pulsecol::kBlockN_f32;
+    *block_m = sparse_block_m(ctx);
+    *block_n = !bf ? pulsecol::kBlockN_f32 : (*block_m < pulsecol::kBlockM_bf16 ? 32 : pulsecol::kBlockN_bf16);
     return PULSECOL_OK;
 }
 

@@ -52,6 +52,8 @@ constexpr int kBlockM_f32 = 128;    // 4 waves x 32
 constexpr int kBlockN_f32 = 32;
 
 hipError_t launch_attn_bf16(const AttnParams& p, int head_dim, AttnMode mode, hipStream_t s);
+// column-sparse attention with query blocks of block_m = 32, 64 or 128 rows (small query groups)
+hipError_t launch_attn_bf16_group(const AttnParams& p, int head_dim, int block_m, hipStream_t s);
 hipError_t launch_attn_f32(const AttnParams& p, int head_dim, AttnMode mode, hipStream_t s);
 hipError_t launch_colmass_bf16(const ScoreParams& p, int head_dim, hipStream_t s);
 hipError_t launch_colmass_f32(const ScoreParams& p, int head_dim, hipStream_t s);

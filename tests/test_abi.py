@@ -46,8 +46,10 @@ def test_status_strings():
     (dict(head_dim=96), pc.ERR_UNSUPPORTED),
     (dict(head_dim=256), pc.ERR_UNSUPPORTED),
     (dict(group_size=-1), pc.ERR_INVALID_ARG),
-    (dict(group_size=32), pc.ERR_UNSUPPORTED),          # groups must be whole query blocks (256 rows, bf16)
-    (dict(group_size=384), pc.ERR_UNSUPPORTED),
+    (dict(group_size=32), pc.OK),                       # the paper's group sizes: small-group kernel
+    (dict(group_size=384), pc.OK),
+    (dict(group_size=48), pc.ERR_UNSUPPORTED),          # groups are whole blocks of 32 queries
+    (dict(group_size=64, dtype=pc.F32), pc.ERR_UNSUPPORTED),   # f32 query blocks are 128 rows
     (dict(group_size=512), pc.OK),                      # 8 groups of two query blocks
     (dict(group_size=4096), pc.OK),                     # one group covering every query == per head
     (dict(strides=(0, 0, 100)), pc.ERR_INVALID_ARG),    # stride_n < head_dim

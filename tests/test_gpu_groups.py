@@ -38,6 +38,12 @@ GROUP_CASES = [
     (1, 3, 800, 64, torch.bfloat16, 256),       # head_dim 64, ragged
     (1, 2, 500, 64, torch.float32, 128),        # fp32 mode: 4 groups, last ragged
     (1, 1, 384, 128, torch.float32, 256),       # fp32 mode, groups of two query blocks
+    (1, 2, 1000, 128, torch.bfloat16, 128),     # the paper's group sizes: small-group kernel
+    (1, 2, 600, 128, torch.bfloat16, 64),
+    (1, 2, 500, 128, torch.bfloat16, 32),       # 16 groups, the last one of 20 rows
+    (1, 2, 300, 64, torch.bfloat16, 32),        # head_dim 64
+    (1, 1, 1000, 64, torch.bfloat16, 384),      # 3 blocks of 128 per group
+    (1, 1, 980, 128, torch.bfloat16, 96),       # blocks of 32; the last tile's second half is empty
 ]
 
 
@@ -82,7 +88,8 @@ def test_group_attention_matches_oracle(B, H, n, d, dtype, G):
 
 
 @pytest.mark.parametrize("n,d,dtype,G,keep", [
-    (1000, 128, torch.bfloat16, 256, 0.1), (768, 64, torch.bfloat16, 256, 0.25), (500, 64, torch.float32, 128, 0.2)])
+    (1000, 128, torch.bfloat16, 256, 0.1), (768, 64, torch.bfloat16, 256, 0.25), (500, 64, torch.float32, 128, 0.2),
+    (700, 128, torch.bfloat16, 128, 0.15), (400, 128, torch.bfloat16, 32, 0.2)])
 def test_group_select_then_attention(n, d, dtype, G, keep):
     B, H = 1, 2
     say(f"group select case n={n} d={d} {dtype} G={G} keep={keep}")
