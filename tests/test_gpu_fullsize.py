@@ -114,3 +114,39 @@ def test_full_size_sampled(name, keep, oracle_select_head):
             assert (row[1:] > row[:-1]).all() and row[0] >= 0 and row[-1] < n
             assert set(wl.heavy_columns(w, 0, hh).tolist()) <= set(row.tolist())
         assert (sc.sum(dim=-1) - 1.0).abs().max().item() < 1e-4
+
+
+@pytest.mark.parametrize("name,G,keep", [("llada_16k", 128, 0.10), ("llada_16k", 256, 0.10), ("llada_32k", 32, 0.05)])
+def test_full_size_groupwise_sampled_groups(name, G, keep):
+    """Group-wise sets at workload size: the oracle computes a few whole groups (their scores
+    are the mean of G softmax rows, cheap even at long context) and checks the GPU's scores,
+    its selection and its attention output on exactly those groups."""
+    w = wl.WORKLOADS[name]
+    n, H = w.seq, w.heads
+    k = oracle.num_keep(n, keep)
+    U = -(-n // G)
+    say(f"{name} G={G} keep={keep}: generating {H} heads x {n}")
+    Q, K, V = wl.make_qkv(w)
+    with pc.Context(w.batch, H, n, w.head_dim, w.torch_dtype, group_size=G) as ctx:
+        q, k_, v = Q.to(DEV), K.to(DEV), V.to(DEV)
+        say("GPU select + scores + attn")
+        sc = ctx.scores(q, k_)
+        idx = ctx.select(q, k_, keep)
+        O = ctx.attn(q, k_, v, idx)
+        torch.cuda.synchronize()
+        assert sc.shape == (1, H, U, n) and idx.shape == (1, H, U, k)
+        assert (sc.sum(dim=-1) - 1.0).abs().max().item() < 1e-4
+    flips = 0
+    for h, u in ((0, 0), (3, U // 2), (H - 1, U - 1), (17, 1)):
+        lo, hi = u * G, min((u + 1) * G, n)
+        say(f"oracle: head {h} group {u} (rows {lo}..{hi - 1})")
+        qg, kh, vh = f64(Q[0, h, lo:hi]), f64(K[0, h]), f64(V[0, h])
+        s64 = oracle.column_scores(qg, kh)[0]                    # the group's rows as one group
+        rel = np.abs(f64(sc[0, h, u]) - s64) / s64
+        assert rel.max() < 2e-5, f"scores head {h} group {u}: {rel.max():.3e}"
+        row = idx[0, h, u].cpu().numpy()
+        flips += assert_idx_matches(row, s64, k, f"{name} head {h} group {u}")
+        # the attention of the GPU's validated set, rows of this group only
+        want = oracle.sparse_attention_masked(qg, kh, vh, row)
+        assert_close(O[0, h, lo:hi], want, "bf16", f"{name} attn head {h} group {u}")
+    say(f"ok, near-tie flips {flips}")
