@@ -211,6 +211,8 @@ def main():
     if not a.no_layers and a.workload == "llada_64k":
         out["multilayer"] = multilayer_run(pc, wl, torch, dev, w, keep)
     if not a.no_groups and a.workload == "llada_64k":
+        out["gqa"] = gqa_config(pc, wl, torch, dev, w, keep)
+    if not a.no_groups and a.workload == "llada_64k":
         out["groupwise"] = [groupwise_config(pc, wl, torch, dev, w, keep, G) for G in (256, 128)]
     if not a.no_probes:
         out["probes"] = roofline_probes(achieved, dense_ms and dense_flop / (dense_ms * 1e-3) * 1e-12)
@@ -275,6 +277,40 @@ def multilayer_run(pc, wl, torch, dev, w, keep):
     return {"layers": L, "steps": T, "eta": eta, "R": R, "kind": "uniform", "refresh_steps": steps,
             "selects_run": selects, "total_ms": round(total_ms, 1),
             "ms_per_layer_step": round(total_ms / (L * T), 4)}
+
+
+def gqa_config(pc, wl, torch, dev, w, keep):
+    """Grouped-query layout at the headline shape: 32 query heads on 8 K/V heads (the workload's
+    first 8 K/V heads), one pattern per query head."""
+    B, H, n, d = w.batch, w.heads, w.seq, w.head_dim
+    Hkv = 8
+    Q, K, V = (t.to(dev) for t in wl.make_qkv(w))
+    K, V = K[:, :Hkv].contiguous(), V[:, :Hkv].contiguous()
+    O = torch.empty_like(Q)
+    ctx = pc.Context(B, H, n, d, w.torch_dtype, kv_heads=Hkv)
+    k = pc.num_keep(n, keep)
+    idx = torch.empty(B, H, 1, k, dtype=torch.int32, device=dev)
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    select_ms = timed(lambda: ctx.select(Q, K, keep, refresh=True, idx_out=idx), 1)
+    attn_ms = timed(lambda: ctx.attn(Q, K, V, idx, O=O), 20)
+    dense_ms = timed(lambda: ctx.attn_dense(Q, K, V, O=O), 3)
+    ctx.close()
+    res = {"heads": H, "kv_heads": Hkv, "k": k, "select_ms": round(select_ms, 3), "attn_ms": round(attn_ms, 4),
+           "dense_ms": round(dense_ms, 3), "kept_tflops": round(4.0 * B * H * n * k * d / (attn_ms * 1e-3) * 1e-12, 2)}
+    del Q, K, V, O, idx
+    torch.cuda.empty_cache()
+    return res
 
 
 def groupwise_config(pc, wl, torch, dev, w, keep, G):

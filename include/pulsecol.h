@@ -63,7 +63,7 @@ typedef enum { PULSECOL_BF16 = 0, PULSECOL_F32 = 1 } pulsecol_dtype;
  * Sec. 3.1: per step, layer and head, Q, K, V are n x d_h with n = prompt + generation length. */
 typedef struct {
     int32_t batch;      /* >= 1 */
-    int32_t heads;      /* >= 1 (multi-head attention: K and V have as many heads as Q)          */
+    int32_t heads;      /* >= 1: heads of Q and O (K and V: see kv_heads)                         */
     int32_t seq;        /* n >= 1; bf16: n < 2^24                                                */
     int32_t head_dim;   /* d_h: 64 or 128                                                        */
     int32_t dtype;      /* pulsecol_dtype: storage type of Q, K, V, O.  bf16: bf16 MFMA with fp32 */
@@ -79,6 +79,13 @@ typedef struct {
     int64_t stride_h;
     int64_t stride_n;
     float scale;        /* logit scale; 0 = 1/sqrt(head_dim) (Sec. 3.1, logits equation)         */
+    int32_t kv_heads;   /* heads of K and V; 0 = heads (multi-head attention).  Otherwise grouped-
+                         * query attention: heads % kv_heads == 0, K and V are [B, kv_heads, n, d]
+                         * and query head h reads K/V head h / (heads / kv_heads).  Patterns stay
+                         * per query head.                                                        */
+    int64_t kv_stride_b; /* element strides of K and V (0 = packed [B, kv_heads, n, d]; with       */
+    int64_t kv_stride_h; /* kv_heads == 0 and all three 0: the strides of Q).  Same alignment and  */
+    int64_t kv_stride_n; /* size rules as stride_b/h/n                                             */
 } pulsecol_shape;
 
 /* Host-only check of a shape against the rules above.  Touches no device. */

@@ -719,6 +719,8 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     if (!xcd_tile(blockIdx.x, nqb, p.batch * p.heads, &bh, &qblk)) return;
     const int b = bh / p.heads, h = bh - b * p.heads;
     const int64_t head_off = (int64_t)b * p.td.sb + (int64_t)h * p.td.sh;
+    // grouped-query layout: query head h reads K/V head h / (heads / kv_heads)
+    const int64_t kv_off = (int64_t)b * p.td_kv.sb + (int64_t)(h / (p.heads / p.kv_heads)) * p.td_kv.sh;
     const __bf16* __restrict__ Q = (const __bf16*)p.q + head_off;
 
     W w;
@@ -732,10 +734,10 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     w.ntiles = (p.ns + BN - 1) / BN;
     w.nhalf = 2 * w.ntiles;
     w.ragged = (p.ns & (BN - 1)) != 0;
-    w.row_bytes = (uint32_t)p.td.sn * 2u;
+    w.row_bytes = (uint32_t)p.td_kv.sn * 2u;
     w.wave_lds = __builtin_amdgcn_readfirstlane(lds_address(lds_k) + w.wave * CH * 1024);
-    w.K = (const byte*)((const __bf16*)p.k + head_off);
-    w.V = HAS_V ? (const byte*)((const __bf16*)p.v + head_off) : nullptr;
+    w.K = (const byte*)((const __bf16*)p.k + kv_off);
+    w.V = HAS_V ? (const byte*)((const __bf16*)p.v + kv_off) : nullptr;
     // the column set of this query block's group (Sec. 3.3: one set per query group)
     const int group = p.groups > 1 ? (qblk * BM) / p.group_size : 0;
     w.idx = W::GATHER ? (const byte*)(p.idx + ((int64_t)bh * p.groups + group) * p.ns) : nullptr;

@@ -38,9 +38,11 @@ __global__ void __launch_bounds__(64 * NW) attn_bf16_group_kernel(AttnParams p) 
     if (!xcd_tile(blockIdx.x, nqb, p.batch * p.heads, &bh, &qblk)) return;
     const int b = bh / p.heads, h = bh - b * p.heads;
     const int64_t head_off = (int64_t)b * p.td.sb + (int64_t)h * p.td.sh;
+    // grouped-query layout: query head h reads K/V head h / (heads / kv_heads)
+    const int64_t kv_off = (int64_t)b * p.td_kv.sb + (int64_t)(h / (p.heads / p.kv_heads)) * p.td_kv.sh;
     const __bf16* __restrict__ Q = (const __bf16*)p.q + head_off;
-    const __bf16* __restrict__ K = (const __bf16*)p.k + head_off;
-    const __bf16* __restrict__ V = (const __bf16*)p.v + head_off;
+    const __bf16* __restrict__ K = (const __bf16*)p.k + kv_off;
+    const __bf16* __restrict__ V = (const __bf16*)p.v + kv_off;
     // the column set of this query block's group; group_size is a multiple of BM
     const int group = p.groups > 1 ? (qblk * BM) / p.group_size : 0;
     const int32_t* __restrict__ idx = p.idx + ((int64_t)bh * p.groups + group) * p.ns;
@@ -82,7 +84,7 @@ __global__ void __launch_bounds__(64 * NW) attn_bf16_group_kernel(AttnParams p) 
 #pragma unroll
         for (int j = 0; j < CH; ++j) {
             const int piece = (tid + NTHREADS * j) % PIECES;
-            const int64_t off = (int64_t)next_row[j] * p.td.sn + piece * 8;
+            const int64_t off = (int64_t)next_row[j] * p.td_kv.sn + piece * 8;
             stage_k[j] = *(const u32x4*)(K + off);
             stage_v[j] = *(const u32x4*)(V + off);
         }

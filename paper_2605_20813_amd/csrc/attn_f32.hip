@@ -35,9 +35,11 @@ __global__ void __launch_bounds__(NTHREADS) attn_f32_kernel(AttnParams p) {
     if (!xcd_tile(blockIdx.x, nqb, p.batch * p.heads, &bh, &qblk)) return;
     const int b = bh / p.heads, h = bh - b * p.heads;
     const int64_t head_off = (int64_t)b * p.td.sb + (int64_t)h * p.td.sh;
+    // grouped-query layout: query head h reads K/V head h / (heads / kv_heads)
+    const int64_t kv_off = (int64_t)b * p.td_kv.sb + (int64_t)(h / (p.heads / p.kv_heads)) * p.td_kv.sh;
     const float* __restrict__ Q = (const float*)p.q + head_off;
-    const float* __restrict__ K = (const float*)p.k + head_off;
-    const float* __restrict__ V = HAS_V ? (const float*)p.v + head_off : nullptr;
+    const float* __restrict__ K = (const float*)p.k + kv_off;
+    const float* __restrict__ V = HAS_V ? (const float*)p.v + kv_off : nullptr;
     // the column set of this query block's group (Sec. 3.3: one set per query group)
     const int group = p.groups > 1 ? (qblk * BM) / p.group_size : 0;
     const int32_t* __restrict__ idx = GATHER ? p.idx + ((int64_t)bh * p.groups + group) * p.ns : nullptr;
@@ -67,7 +69,7 @@ __global__ void __launch_bounds__(NTHREADS) attn_f32_kernel(AttnParams p) {
             int pos = t * BN + c / PIECES;
             pos = pos < ns ? pos : ns - 1;
             const int row = GATHER ? idx[pos] : pos;
-            const int64_t off = (int64_t)row * p.td.sn + (c % PIECES) * 4;
+            const int64_t off = (int64_t)row * p.td_kv.sn + (c % PIECES) * 4;
             stage_k[j] = *(const f32x4*)(K + off);
             if (HAS_V) stage_v[j] = *(const f32x4*)(V + off);
         }

@@ -41,8 +41,10 @@ __global__ void __launch_bounds__(NTHREADS) colmass_bf16_kernel(ScoreParams p) {
     if (!xcd_tile(blockIdx.x, nkb, p.batch * p.heads, &bh, &kblk)) return;
     const int b = bh / p.heads, h = bh - b * p.heads;
     const int64_t head_off = (int64_t)b * p.td.sb + (int64_t)h * p.td.sh;
+    // grouped-query layout: query head h reads K/V head h / (heads / kv_heads)
+    const int64_t kv_off = (int64_t)b * p.td_kv.sb + (int64_t)(h / (p.heads / p.kv_heads)) * p.td_kv.sh;
     const __bf16* __restrict__ Q = (const __bf16*)p.q + head_off;
-    const __bf16* __restrict__ K = (const __bf16*)p.k + head_off;
+    const __bf16* __restrict__ K = (const __bf16*)p.k + kv_off;
     const float* __restrict__ lse = p.lse + (int64_t)bh * n;
 
     const int tid = threadIdx.x;
@@ -56,7 +58,7 @@ __global__ void __launch_bounds__(NTHREADS) colmass_bf16_kernel(ScoreParams p) {
     for (int kb = 0; kb < 2; ++kb) {
         int row = key0 + kb * 32 + lq;
         row = row < n ? row : n - 1;
-        const __bf16* src = K + (int64_t)row * p.td.sn + 8 * lh;
+        const __bf16* src = K + (int64_t)row * p.td_kv.sn + 8 * lh;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) kf[kb][kk] = *(const bf16x8*)(src + kk * 16);
     }

@@ -33,8 +33,10 @@ __global__ void __launch_bounds__(NTHREADS) colmass_f32_kernel(ScoreParams p) {
     if (!xcd_tile(blockIdx.x, nkb, p.batch * p.heads, &bh, &kblk)) return;
     const int b = bh / p.heads, h = bh - b * p.heads;
     const int64_t head_off = (int64_t)b * p.td.sb + (int64_t)h * p.td.sh;
+    // grouped-query layout: query head h reads K/V head h / (heads / kv_heads)
+    const int64_t kv_off = (int64_t)b * p.td_kv.sb + (int64_t)(h / (p.heads / p.kv_heads)) * p.td_kv.sh;
     const float* __restrict__ Q = (const float*)p.q + head_off;
-    const float* __restrict__ K = (const float*)p.k + head_off;
+    const float* __restrict__ K = (const float*)p.k + kv_off;
     const float* __restrict__ lse = p.lse + (int64_t)bh * n;
 
     const int tid = threadIdx.x;
@@ -46,7 +48,7 @@ __global__ void __launch_bounds__(NTHREADS) colmass_f32_kernel(ScoreParams p) {
     {
         int row = key0 + lq;
         row = row < n ? row : n - 1;
-        const float* src = K + (int64_t)row * p.td.sn + lh;
+        const float* src = K + (int64_t)row * p.td_kv.sn + lh;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) kf[kk] = src[2 * kk];
     }

@@ -18,7 +18,9 @@ struct pulsecol_ctx {
     int device = 0;
     int groups = 1;                 // U
     float scale = 0.f;
-    pulsecol::TensorDesc td{};
+    pulsecol::TensorDesc td{};      // Q, O
+    pulsecol::TensorDesc td_kv{};   // K, V
+    int kv_heads = 1;
     float* lse = nullptr;           // [B*H, n]   row log-sum-exp, log2 units
     float* scores = nullptr;        // [B*H*U, n]
     int32_t* cached_idx = nullptr;  // [B*H*U, cached_k]
@@ -49,6 +51,15 @@ int64_t floor_product(double ratio, int64_t count) {
     return (int64_t)std::floor(ratio * (double)count + 1e-9);
 }
 
+// K/V strides: explicit, else (multi-head, nothing given) those of Q, else packed [B, kv_heads, n, d]
+bool kv_follows_q(const pulsecol_shape* s) {
+    return (s->kv_heads == 0 || s->kv_heads == s->heads) && s->kv_stride_b == 0 && s->kv_stride_h == 0 && s->kv_stride_n == 0;
+}
+int64_t kv_row_stride(const pulsecol_shape* s) {
+    if (s->kv_stride_n) return s->kv_stride_n;
+    return kv_follows_q(s) && s->stride_n ? s->stride_n : s->head_dim;
+}
+
 pulsecol_status check_shape(const pulsecol_shape* s, std::string* why) {
     if (!s) { *why = "shape is NULL"; return PULSECOL_ERR_INVALID_ARG; }
     if (s->batch < 1 || s->heads < 1 || s->seq < 1) { *why = "batch, heads and seq must be >= 1"; return PULSECOL_ERR_INVALID_ARG; }
@@ -68,14 +79,23 @@ pulsecol_status check_shape(const pulsecol_shape* s, std::string* why) {
     }
     if ((int64_t)s->batch * s->heads > (1 << 20)) { *why = "batch*heads too large"; return PULSECOL_ERR_UNSUPPORTED; }
     if (s->stride_n != 0 && s->stride_n < s->head_dim) { *why = "stride_n smaller than head_dim"; return PULSECOL_ERR_INVALID_ARG; }
+    if (s->kv_heads < 0 || (s->kv_heads > 0 && (s->kv_heads > s->heads || s->heads % s->kv_heads != 0))) {
+        *why = "kv_heads must be 0 or a divisor of heads";
+        return PULSECOL_ERR_INVALID_ARG;
+    }
+    if (s->kv_stride_b < 0 || s->kv_stride_h < 0 || s->kv_stride_n < 0) { *why = "strides must be >= 0"; return PULSECOL_ERR_INVALID_ARG; }
+    if (s->kv_stride_n != 0 && s->kv_stride_n < s->head_dim) { *why = "kv_stride_n smaller than head_dim"; return PULSECOL_ERR_INVALID_ARG; }
     {   // the kernels address a head's K/V rows with 32-bit byte offsets
-        const int64_t sn = s->stride_n ? s->stride_n : s->head_dim;
+        const int64_t sn = kv_row_stride(s);
         const int64_t esize = s->dtype == PULSECOL_BF16 ? 2 : 4;
-        if ((int64_t)s->seq * sn * esize >= ((int64_t)1 << 32)) { *why = "seq * stride_n exceeds 4 GiB per head"; return PULSECOL_ERR_UNSUPPORTED; }
-        if (s->seq >= (1 << 24) || sn * esize >= (1 << 24)) { *why = "seq or the row stride in bytes reaches 2^24"; return PULSECOL_ERR_UNSUPPORTED; }
+        if ((int64_t)s->seq * sn * esize >= ((int64_t)1 << 32)) { *why = "seq * stride_n of K/V exceeds 4 GiB per head"; return PULSECOL_ERR_UNSUPPORTED; }
+        if (s->seq >= (1 << 24) || sn * esize >= (1 << 24)) { *why = "seq or the K/V row stride in bytes reaches 2^24"; return PULSECOL_ERR_UNSUPPORTED; }
     }
     const int a = elem_align(s->dtype);
-    if (s->stride_b % a || s->stride_h % a || s->stride_n % a) { *why = "strides must be multiples of 16 bytes"; return PULSECOL_ERR_ALIGNMENT; }
+    if (s->stride_b % a || s->stride_h % a || s->stride_n % a || s->kv_stride_b % a || s->kv_stride_h % a || s->kv_stride_n % a) {
+        *why = "strides must be multiples of 16 bytes";
+        return PULSECOL_ERR_ALIGNMENT;
+    }
     return PULSECOL_OK;
 }
 
@@ -97,7 +117,7 @@ pulsecol::AttnParams attn_params(const pulsecol_ctx* c, const void* Q, const voi
                                  const int32_t* idx, int32_t ns, float* lse, int lse_base2) {
     pulsecol::AttnParams p{};
     p.q = Q; p.k = K; p.v = V; p.o = O; p.idx = idx; p.lse = lse; p.lse_base2 = lse_base2;
-    p.td = c->td;
+    p.td = c->td; p.td_kv = c->td_kv; p.kv_heads = c->kv_heads;
     p.batch = c->shape.batch; p.heads = c->shape.heads; p.n = c->shape.seq; p.ns = ns;
     p.groups = c->groups; p.group_size = c->shape.group_size;
     p.scale = c->scale;
@@ -131,7 +151,7 @@ pulsecol_status check_ptrs(pulsecol_ctx* ctx, std::initializer_list<const void*>
 // column pass of the scoring stage: ctx->lse (log2 units) must hold the row log-sum-exp of Q, K
 pulsecol_status run_colmass(pulsecol_ctx* ctx, const void* Q, const void* K, float* out, hipStream_t s) {
     pulsecol::ScoreParams sp{};
-    sp.q = Q; sp.k = K; sp.lse = ctx->lse; sp.scores = out; sp.td = ctx->td;
+    sp.q = Q; sp.k = K; sp.lse = ctx->lse; sp.scores = out; sp.td = ctx->td; sp.td_kv = ctx->td_kv; sp.kv_heads = ctx->kv_heads;
     sp.batch = ctx->shape.batch; sp.heads = ctx->shape.heads; sp.n = ctx->shape.seq; sp.scale = ctx->scale;
     sp.groups = ctx->groups; sp.group_size = ctx->shape.group_size;
     const hipError_t e = ctx->shape.dtype == PULSECOL_BF16 ? pulsecol::launch_colmass_bf16(sp, ctx->shape.head_dim, s)
@@ -201,6 +221,14 @@ pulsecol_status pulsecol_create(pulsecol_ctx** out, const pulsecol_shape* shape,
     c->td.sn = shape->stride_n ? shape->stride_n : shape->head_dim;
     c->td.sh = shape->stride_h ? shape->stride_h : (int64_t)shape->seq * c->td.sn;
     c->td.sb = shape->stride_b ? shape->stride_b : (int64_t)shape->heads * c->td.sh;
+    c->kv_heads = shape->kv_heads ? shape->kv_heads : shape->heads;
+    if (kv_follows_q(shape)) {
+        c->td_kv = c->td;
+    } else {
+        c->td_kv.sn = shape->kv_stride_n ? shape->kv_stride_n : shape->head_dim;
+        c->td_kv.sh = shape->kv_stride_h ? shape->kv_stride_h : (int64_t)shape->seq * c->td_kv.sn;
+        c->td_kv.sb = shape->kv_stride_b ? shape->kv_stride_b : (int64_t)c->kv_heads * c->td_kv.sh;
+    }
 
     DeviceGuard guard(device);
     if (guard.err != hipSuccess) { delete c; return fail_hip(nullptr, guard.err, "pulsecol_create: hipSetDevice"); }

@@ -18,7 +18,9 @@ struct AttnParams {
     const int32_t* idx;      // [B*H*groups, ns] (one column set per query group) or nullptr for dense
     float* lse;              // optional [B*H, n] row log-sum-exp of the scaled logits
     int32_t lse_base2;       // 0: natural log; 1: log2 units (what the column-mass pass consumes)
-    TensorDesc td;
+    TensorDesc td;           // Q and O: [B, heads, n, D]
+    TensorDesc td_kv;        // K and V: [B, kv_heads, n, D]; query head h reads K/V head h / (heads / kv_heads)
+    int32_t kv_heads;
     int32_t batch, heads, n, ns;   // ns = columns attended per row (dense: n)
     int32_t groups;          // U query groups per head (1 = the whole head)
     int32_t group_size;      // rows per group, a multiple of the kernel's query block (unused when U = 1)
@@ -30,7 +32,9 @@ struct ScoreParams {
     const void* k;
     const float* lse;        // [B*H, n], log2 units: log2 sum_j exp(z_ij)
     float* scores;           // [B*H*groups, n]
-    TensorDesc td;
+    TensorDesc td;           // Q: [B, heads, n, D]
+    TensorDesc td_kv;        // K: [B, kv_heads, n, D]; query head h reads K head h / (heads / kv_heads)
+    int32_t kv_heads;
     int32_t batch, heads, n;
     int32_t groups;          // U query groups per head (1 = the whole head)
     int32_t group_size;      // rows per group, a multiple of the kernel's query tile (unused when U = 1)

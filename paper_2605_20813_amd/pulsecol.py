@@ -32,7 +32,8 @@ class Shape(ctypes.Structure):
     _fields_ = [("batch", c_int32), ("heads", c_int32), ("seq", c_int32), ("head_dim", c_int32),
                 ("dtype", c_int32), ("group_size", c_int32),
                 ("stride_b", c_int64), ("stride_h", c_int64), ("stride_n", c_int64),
-                ("scale", c_float)]
+                ("scale", c_float), ("kv_heads", c_int32),
+                ("kv_stride_b", c_int64), ("kv_stride_h", c_int64), ("kv_stride_n", c_int64)]
 
 
 class PulseColError(RuntimeError):
@@ -85,8 +86,9 @@ def _dtype_code(dtype) -> int:
     raise ValueError(f"unsupported dtype {dtype}")
 
 
-def make_shape(batch, heads, seq, head_dim, dtype, group_size=0, strides=(0, 0, 0), scale=0.0) -> Shape:
-    return Shape(batch, heads, seq, head_dim, _dtype_code(dtype), group_size, *strides, scale)
+def make_shape(batch, heads, seq, head_dim, dtype, group_size=0, strides=(0, 0, 0), scale=0.0,
+               kv_heads=0, kv_strides=(0, 0, 0)) -> Shape:
+    return Shape(batch, heads, seq, head_dim, _dtype_code(dtype), group_size, *strides, scale, kv_heads, *kv_strides)
 
 
 def validate_shape(shape: Shape) -> int:
@@ -144,8 +146,9 @@ def _stream():
 class Context:
     """Owns one pulsecol_ctx.  Tensors are [B, H, n, d] on the context's device."""
 
-    def __init__(self, batch, heads, seq, head_dim, dtype, group_size=0, strides=(0, 0, 0), scale=0.0, device=0):
-        self.shape = make_shape(batch, heads, seq, head_dim, dtype, group_size, strides, scale)
+    def __init__(self, batch, heads, seq, head_dim, dtype, group_size=0, strides=(0, 0, 0), scale=0.0, device=0,
+                 kv_heads=0, kv_strides=(0, 0, 0)):
+        self.shape = make_shape(batch, heads, seq, head_dim, dtype, group_size, strides, scale, kv_heads, kv_strides)
         self.torch_dtype = torch.bfloat16 if self.shape.dtype == BF16 else torch.float32
         self.device = torch.device("cuda", device)
         self._h = c_void_p()
@@ -178,13 +181,19 @@ class Context:
             raise PulseColError(st, last_error(self._h))
 
     def _check_tensor(self, t, name):
+        """Shape and strides of a tensor argument; K and V follow the K/V head count and strides."""
         s = self.shape
         if t.device != self.device or t.dtype != self.torch_dtype:
             raise ValueError(f"{name}: expected {self.torch_dtype} on {self.device}")
-        if tuple(t.shape) != (s.batch, s.heads, s.seq, s.head_dim):
-            raise ValueError(f"{name}: expected shape {(s.batch, s.heads, s.seq, s.head_dim)}, got {tuple(t.shape)}")
-        want = (s.stride_b or s.heads * (s.stride_h or s.seq * (s.stride_n or s.head_dim)),
-                s.stride_h or s.seq * (s.stride_n or s.head_dim), s.stride_n or s.head_dim, 1)
+        kv = name in ("K", "V")
+        kv_follows_q = s.kv_heads in (0, s.heads) and not (s.kv_stride_b or s.kv_stride_h or s.kv_stride_n)
+        if kv and not kv_follows_q:
+            heads, sb, sh, sn = s.kv_heads or s.heads, s.kv_stride_b, s.kv_stride_h, s.kv_stride_n
+        else:
+            heads, sb, sh, sn = s.heads, s.stride_b, s.stride_h, s.stride_n
+        if tuple(t.shape) != (s.batch, heads, s.seq, s.head_dim):
+            raise ValueError(f"{name}: expected shape {(s.batch, heads, s.seq, s.head_dim)}, got {tuple(t.shape)}")
+        want = (sb or heads * (sh or s.seq * (sn or s.head_dim)), sh or s.seq * (sn or s.head_dim), sn or s.head_dim, 1)
         if tuple(t.stride()) != want:
             raise ValueError(f"{name}: strides {tuple(t.stride())} do not match the context's {want}")
 

@@ -51,6 +51,12 @@ def test_status_strings():
     (dict(group_size=48), pc.ERR_UNSUPPORTED),          # groups are whole blocks of 32 queries
     (dict(group_size=64, dtype=pc.F32), pc.ERR_UNSUPPORTED),   # f32 query blocks are 128 rows
     (dict(group_size=512), pc.OK),                      # 8 groups of two query blocks
+    (dict(kv_heads=8), pc.OK),                          # grouped-query layout: 4 query heads per K/V head
+    (dict(kv_heads=5), pc.ERR_INVALID_ARG),             # not a divisor of heads
+    (dict(kv_heads=64), pc.ERR_INVALID_ARG),
+    (dict(kv_heads=-1), pc.ERR_INVALID_ARG),
+    (dict(kv_heads=8, kv_strides=(0, 0, 100)), pc.ERR_INVALID_ARG),    # K/V row stride below head_dim
+    (dict(kv_heads=8, kv_strides=(0, 0, 132)), pc.ERR_ALIGNMENT),
     (dict(group_size=4096), pc.OK),                     # one group covering every query == per head
     (dict(strides=(0, 0, 100)), pc.ERR_INVALID_ARG),    # stride_n < head_dim
     (dict(strides=(0, 0, 132)), pc.ERR_ALIGNMENT),      # not a multiple of 8 bf16 elements
