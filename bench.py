@@ -53,8 +53,8 @@ def parse():
 def main():
     a = parse()
     if a.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (every head is independent; sharding by head needs no "
-              "collective and is described in DESIGN.md); --gpus must be 1", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU (every head is independent: sharding by head needs no "
+              "collective); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
 
     import torch

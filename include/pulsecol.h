@@ -11,7 +11,8 @@
  *   - dense attention softmax(Q K^T / sqrt(d)) V (Sec. 3.1), the baseline being beaten.
  *
  * Conventions common to every call
- *   - Q, K, V, O are DEVICE pointers to [batch, heads, seq, head_dim] tensors whose last
+ *   - Q, K, V, O are DEVICE pointers to [batch, heads, seq, head_dim] tensors (K and V:
+ *     [batch, kv_heads, seq, head_dim] in the grouped-query layout) whose last
  *     dimension is contiguous; the other three strides are given in ELEMENTS in
  *     pulsecol_shape (0 = packed).  Base pointers must be 16-byte aligned and the strides
  *     multiples of 8 (bf16) or 4 (fp32) elements.  Attention is non-causal; there is no
@@ -19,9 +20,12 @@
  *   - Column sets are DEVICE int32 arrays idx[batch, heads, U, k]; U is the number of query
  *     groups per head (U = 1 when group_size == 0: one column set per head).  Entries lie in
  *     [0, seq) and are unique within a row; pulsecol_select emits them ascending.  The
- *     sparse kernel counts a repeated entry twice, as the appendix listing would.
+ *     sparse kernel counts a repeated entry twice, as the appendix listing would.  An entry
+ *     outside [0, seq) addresses memory outside K and V: a caller that cannot vouch for its
+ *     indices turns the validation mode on (pulsecol_set_validation).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
- *     enqueue work on it: they never synchronise and never read device memory on the host.
+ *     enqueue work on it: they never synchronise and never read device memory on the host
+ *     (the validation mode of pulsecol_attn is the one exception).
  *     The caller owns every buffer it passes; the context owns only the scratch it
  *     allocated at creation (row log-sum-exp, column scores, top-k counters, the cached
  *     pattern).  No call allocates or frees device memory except create/destroy.
@@ -54,7 +58,8 @@ typedef enum {
     PULSECOL_ERR_ALIGNMENT = 3,   /* base pointer or stride not aligned as stated above           */
     PULSECOL_ERR_NO_PATTERN = 4,  /* refresh == 0 with no cached pattern, or with a different k   */
     PULSECOL_ERR_OOM = 5,         /* scratch allocation failed in pulsecol_create                 */
-    PULSECOL_ERR_HIP = 6          /* a HIP runtime call failed; see pulsecol_last_error           */
+    PULSECOL_ERR_HIP = 6,         /* a HIP runtime call failed; see pulsecol_last_error           */
+    PULSECOL_ERR_BAD_INDEX = 7    /* validation mode: idx holds an entry outside [0, seq)         */
 } pulsecol_status;
 
 typedef enum { PULSECOL_BF16 = 0, PULSECOL_F32 = 1 } pulsecol_dtype;
@@ -95,6 +100,12 @@ PULSECOL_API pulsecol_status pulsecol_validate_shape(const pulsecol_shape* shape
  * (4*B*H*seq bytes of row statistics, 4*B*H*U*seq bytes of scores, 4*B*H*U*seq bytes for the
  * cached pattern, a few KB of counters).  *out is set only on PULSECOL_OK. */
 PULSECOL_API pulsecol_status pulsecol_create(pulsecol_ctx** out, const pulsecol_shape* shape, int device);
+
+/* Validation mode (off by default; on at creation if the environment variable
+ * PULSECOL_VALIDATE is set to anything but 0): pulsecol_attn first checks on the device that
+ * every entry of idx lies in [0, seq), waits for the answer (it synchronises the stream) and
+ * returns PULSECOL_ERR_BAD_INDEX without launching the attention kernel if one does not. */
+PULSECOL_API pulsecol_status pulsecol_set_validation(pulsecol_ctx* ctx, int on);
 
 /* Free the scratch.  The caller must have synchronised the streams it used.  NULL is OK. */
 PULSECOL_API pulsecol_status pulsecol_destroy(pulsecol_ctx* ctx);

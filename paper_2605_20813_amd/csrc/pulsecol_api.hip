@@ -6,6 +6,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstdlib>
 #include <cstdio>
 #include <new>
 #include <string>
@@ -25,6 +26,8 @@ struct pulsecol_ctx {
     float* scores = nullptr;        // [B*H*U, n]
     int32_t* cached_idx = nullptr;  // [B*H*U, cached_k]
     int32_t cached_k = 0;           // 0 = nothing cached
+    int32_t* bad_count = nullptr;   // one device counter for the validation mode
+    bool validate = false;          // check column numbers in front of every pulsecol_attn
     std::string last_error;
 };
 
@@ -237,15 +240,25 @@ pulsecol_status pulsecol_create(pulsecol_ctx** out, const pulsecol_shape* shape,
     hipError_t e1 = hipMalloc((void**)&c->lse, rows * row_bytes);
     hipError_t e2 = e1 == hipSuccess ? hipMalloc((void**)&c->scores, rows * c->groups * row_bytes) : e1;
     hipError_t e3 = e2 == hipSuccess ? hipMalloc((void**)&c->cached_idx, rows * c->groups * row_bytes) : e2;
+    if (e3 == hipSuccess) e3 = hipMalloc((void**)&c->bad_count, 256);
     if (e3 != hipSuccess) {
         if (c->lse) (void)hipFree(c->lse);
         if (c->scores) (void)hipFree(c->scores);
+        if (c->cached_idx) (void)hipFree(c->cached_idx);
         (void)hipGetLastError();
         delete c;
         return e3 == hipErrorOutOfMemory ? fail(nullptr, PULSECOL_ERR_OOM, "pulsecol_create: scratch allocation failed")
                                          : fail_hip(nullptr, e3, "pulsecol_create: hipMalloc");
     }
+    const char* env = std::getenv("PULSECOL_VALIDATE");
+    c->validate = env != nullptr && env[0] != '\0' && env[0] != '0';
     *out = c;
+    return PULSECOL_OK;
+}
+
+pulsecol_status pulsecol_set_validation(pulsecol_ctx* ctx, int on) {
+    if (!ctx) return fail(nullptr, PULSECOL_ERR_INVALID_ARG, "pulsecol_set_validation: ctx is NULL");
+    ctx->validate = on != 0;
     return PULSECOL_OK;
 }
 
@@ -255,6 +268,7 @@ pulsecol_status pulsecol_destroy(pulsecol_ctx* ctx) {
     (void)hipFree(ctx->lse);
     (void)hipFree(ctx->scores);
     (void)hipFree(ctx->cached_idx);
+    (void)hipFree(ctx->bad_count);
     delete ctx;
     return PULSECOL_OK;
 }
@@ -338,6 +352,16 @@ pulsecol_status pulsecol_attn(pulsecol_ctx* ctx, const void* Q, const void* K, c
     if (k < 1 || k > ctx->shape.seq) return fail(ctx, PULSECOL_ERR_INVALID_ARG, "pulsecol_attn: need 1 <= k <= seq");
     DeviceGuard guard(ctx->device);
     if (guard.err != hipSuccess) return fail_hip(ctx, guard.err, "pulsecol_attn: hipSetDevice");
+    if (ctx->validate) {
+        // the one mode that synchronises: the answer has to be known before anything is gathered
+        const int64_t count = (int64_t)ctx->shape.batch * ctx->shape.heads * ctx->groups * k;
+        hipError_t ev = pulsecol::launch_index_range_check(idx, count, ctx->shape.seq, ctx->bad_count, (hipStream_t)stream);
+        int32_t bad = 0;
+        if (ev == hipSuccess) ev = hipMemcpyAsync(&bad, ctx->bad_count, sizeof(bad), hipMemcpyDeviceToHost, (hipStream_t)stream);
+        if (ev == hipSuccess) ev = hipStreamSynchronize((hipStream_t)stream);
+        if (ev != hipSuccess) return fail_hip(ctx, ev, "pulsecol_attn: index validation");
+        if (bad != 0) return fail(ctx, PULSECOL_ERR_BAD_INDEX, "pulsecol_attn: idx holds entries outside [0, seq)");
+    }
     const pulsecol::AttnParams p = attn_params(ctx, Q, K, V, O, idx, k, nullptr, 0);
     const hipError_t e = launch_attn(ctx, p, pulsecol::kSparse, (hipStream_t)stream);
     if (e != hipSuccess) return fail_hip(ctx, e, "column-sparse attention kernel");
@@ -414,6 +438,7 @@ const char* pulsecol_status_str(pulsecol_status status) {
         case PULSECOL_ERR_NO_PATTERN: return "no cached pattern";
         case PULSECOL_ERR_OOM: return "out of device memory";
         case PULSECOL_ERR_HIP: return "HIP runtime error";
+        case PULSECOL_ERR_BAD_INDEX: return "column number out of range";
     }
     return "unknown status";
 }

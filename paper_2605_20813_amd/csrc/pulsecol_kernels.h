@@ -62,5 +62,7 @@ hipError_t launch_attn_f32(const AttnParams& p, int head_dim, AttnMode mode, hip
 hipError_t launch_colmass_bf16(const ScoreParams& p, int head_dim, hipStream_t s);
 hipError_t launch_colmass_f32(const ScoreParams& p, int head_dim, hipStream_t s);
 hipError_t launch_topk(const TopkParams& p, hipStream_t s);
+// *bad_count (device) = number of wavefront-lanes that saw an entry of idx[0..count) outside [0, n); 0 if none
+hipError_t launch_index_range_check(const int32_t* idx, int64_t count, int32_t n, int32_t* bad_count, hipStream_t s);
 
 }  // namespace pulsecol

@@ -16,11 +16,11 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpulsecol.so")
 
-OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_ALIGNMENT, ERR_NO_PATTERN, ERR_OOM, ERR_HIP = range(7)
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_ALIGNMENT, ERR_NO_PATTERN, ERR_OOM, ERR_HIP, ERR_BAD_INDEX = range(8)
 BF16, F32 = 0, 1
 
 EXPORTS = (
-    "pulsecol_validate_shape", "pulsecol_create", "pulsecol_destroy", "pulsecol_num_keep",
+    "pulsecol_validate_shape", "pulsecol_create", "pulsecol_destroy", "pulsecol_set_validation", "pulsecol_num_keep",
     "pulsecol_select", "pulsecol_scores", "pulsecol_topk", "pulsecol_attn", "pulsecol_attn_dense",
     "pulsecol_refresh_dense",
     "pulsecol_refresh_schedule", "pulsecol_refresh_schedule_power", "pulsecol_refresh_schedule_random",
@@ -55,6 +55,7 @@ def lib() -> ctypes.CDLL:
         L.pulsecol_validate_shape.argtypes = [POINTER(Shape)]
         L.pulsecol_create.argtypes = [POINTER(c_void_p), POINTER(Shape), c_int]
         L.pulsecol_destroy.argtypes = [c_void_p]
+        L.pulsecol_set_validation.argtypes = [c_void_p, c_int]
         L.pulsecol_num_keep.argtypes = [c_int32, c_double]
         L.pulsecol_num_keep.restype = c_int32
         L.pulsecol_select.argtypes = [c_void_p, c_void_p, c_void_p, c_double, c_int, c_void_p, c_void_p]
@@ -204,6 +205,10 @@ class Context:
         if s.group_size == 0 or s.group_size >= s.seq:
             return 1
         return (s.seq + s.group_size - 1) // s.group_size
+
+    def set_validation(self, on: bool = True):
+        """Check column numbers on the device in front of every attn call (synchronises)."""
+        self._check(lib().pulsecol_set_validation(self._h, int(bool(on))))
 
     def tile_shape(self):
         bm, bn = c_int32(), c_int32()

@@ -320,3 +320,28 @@ def test_refresh_dense_gives_dense_output_and_the_select_pattern(n, d, dtype, ke
         qh, kh, vh = f64(Q[0, h]), f64(K[0, h]), f64(V[0, h])
         assert_close(O[0, h], oracle.dense_attention(qh, kh, vh), kind_of(dtype), f"refresh_dense O head {h}")
         assert_idx_matches(idx[0, h, 0].cpu().numpy(), oracle.column_scores(qh, kh)[0], k, f"refresh_dense idx head {h}")
+
+
+def test_validation_mode_rejects_out_of_range_columns():
+    """With validation on, an out-of-range column number is reported and nothing is launched
+    (the output buffer keeps its contents); valid sets give the same output as without it."""
+    say("validation mode")
+    B, H, n, d, k = 1, 2, 512, 128, 40
+    Q, K, V = (t.to(DEV) for t in rand_qkv(B, H, n, d, torch.bfloat16, seed=81))
+    good = random_idx(n, k, B * H, seed=82).view(B, H, 1, k).to(DEV)
+    with pc.Context(B, H, n, d, torch.bfloat16) as ctx:
+        want = ctx.attn(Q, K, V, good).clone()
+        ctx.set_validation(True)
+        assert torch.equal(ctx.attn(Q, K, V, good), want)
+        for bad_value in (n, -1, 2**31 - 1):
+            bad = good.clone()
+            bad[0, 1, 0, 17] = bad_value
+            O = torch.full_like(Q, 3.0)
+            with pytest.raises(pc.PulseColError) as e:
+                ctx.attn(Q, K, V, bad, O=O)
+            assert e.value.status == pc.ERR_BAD_INDEX
+            torch.cuda.synchronize()
+            assert bool((O == 3.0).all())
+        ctx.set_validation(False)
+        assert torch.equal(ctx.attn(Q, K, V, good), want)
+        torch.cuda.synchronize()
