@@ -6,18 +6,25 @@
 // One workgroup = 256 query rows (4 waves x 64 rows), one tile = 64 K/V rows, processed as
 // two half-tiles of 32.  Q stays in registers (AGPRs) as the MFMA B operand for the whole
 // kernel.  K and V rows are gathered straight into LDS (global_load_lds_dwordx4: 16 lanes
-// cover one 256-byte row, the XOR swizzle is applied on the global side) into three tile
-// slots per operand, and read back as MFMA A operands (V through the transposing LDS read).
-// Every lane owns one query column of S^T / O^T, so the online-softmax state is two scalars
-// per lane and query block.  P is rounded to bf16 only as the MFMA operand; l is summed from
-// the fp32 P.  The output accumulator lives in AGPRs and is touched by the matrix pipe only.
+// cover one 256-byte row, the XOR swizzle is applied on the global side) into four tile
+// slots per operand, three tiles ahead, and read back as MFMA A operands (V through the
+// transposing LDS read).  Every lane owns one query column of S^T / O^T, so the online-softmax
+// state is two scalars per lane and query block.  P is rounded to bf16 only as the MFMA
+// operand; l is summed from the fp32 P.  The output accumulator lives in AGPRs and is touched
+// by the matrix pipe only.
 //
 // Software pipeline (one wave per SIMD, so overlap has to come from the instruction
 // stream): half-step j issues the MFMAs of  S(j+1) = K(j+1) Q^T  and  O += V(j-1) P(j-1)
 // while the VALU turns S(j) into P(j).  The half-step is written as a sequence of slots, one
-// MFMA each, fenced so that the compiler keeps the hand-made interleaving: every slot issues
-// its MFMA, then a few VALU operations of the exp / row-max work, and every second slot the
-// LDS read of a fragment needed three MFMA pairs later.  The reference maximum is raised
+// MFMA each, fenced so that the compiler keeps the hand-made interleaving.  A wave issues in
+// order, and with one wave per SIMD every instruction between two MFMAs costs issue time
+// (about 12 ticks for the MFMA itself, 8 for an exp, 4 for anything else, against the 32 ticks
+// the matrix pipe is busy), except that the first non-VALU instruction behind an MFMA is
+// free.  So every slot is: the MFMA (with the wait for its fragment fused in front), then the
+// slot's LDS read / gather instruction / scalar work, then one tick of the softmax work
+// (fma, add, pack, exp); a gather is split over two slots; loads are spread over the whole
+// iteration; the steady loop is unrolled by the four tile slots so that LDS addresses are
+// a base register plus an immediate.  The reference maximum is raised
 // lazily and after the fact: P is formed against the current reference, and only when a
 // lane's row sum of the half-tile exceeds 2^kTau (or is not finite) does the wave take the
 // slow path that finds the true maximum, moves the reference by a whole number of log2
@@ -94,20 +101,12 @@ __device__ __forceinline__ void mfma_settle_acc(f32x16 (&o)[2][N]) {
     else
         asm volatile("s_nop 15\n\ts_nop 15" : "+a"(o[0][0]), "+a"(o[1][0]));
 }
-// Order-only statements: the compiler's instruction selection places pure arithmetic wherever
-// its dependencies allow; routing a value through an empty volatile statement ties the
-// arithmetic that produces it (and everything that consumes it) to this point of the slot
-// sequence.
-__device__ __forceinline__ void pin(float& a) { asm volatile("" : "+v"(a)); }
-__device__ __forceinline__ void pin(float& a, float& b) { asm volatile("" : "+v"(a), "+v"(b)); }
-__device__ __forceinline__ void pin(bf16x8& a) { asm volatile("" : "+v"(a)); }
 // element pair `i` (two bf16 in one 32-bit register) of a fragment
 __device__ __forceinline__ void set_pair(bf16x8& f, int i, uint32_t w) {
     u32x4 t = __builtin_bit_cast(u32x4, f);
     t[i] = w;
     f = __builtin_bit_cast(bf16x8, t);
 }
-__device__ __forceinline__ void pin(f32x16& a, f32x16& b) { asm volatile("" : "+v"(a), "+v"(b)); }
 
 // LDS fragment reads of the scheduled half-step, as inline assembly with hand-placed waits.
 // (The compiler's own wait-count insertion drains lgkmcnt to zero whenever a direct-to-LDS
@@ -117,13 +116,6 @@ __device__ __forceinline__ bf16x8 lds_read_b128_at(uint32_t addr) {
     bf16x8 v;
     asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(v) : "v"(addr), "n"(OFF));
     return v;
-}
-template <int OFF0, int OFF1>
-__device__ __forceinline__ bf16x8 lds_read_tr_pair_at(uint32_t addr) {
-    bf16x4 lo, hi;
-    asm volatile("ds_read_b64_tr_b16 %0, %2 offset:%3\n\tds_read_b64_tr_b16 %1, %2 offset:%4"
-                 : "=&v"(lo), "=&v"(hi) : "v"(addr), "n"(OFF0), "n"(OFF1));
-    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 template <int OFF>
 __device__ __forceinline__ bf16x4 lds_read_tr_at(uint32_t addr) {
@@ -135,10 +127,6 @@ __device__ __forceinline__ bf16x4 lds_read_tr_at(uint32_t addr) {
 __device__ __forceinline__ void set_half(bf16x8& f, int h, bf16x4 v) {
     f = h == 0 ? __builtin_shufflevector(v, __builtin_shufflevector(f, f, 4, 5, 6, 7), 0, 1, 2, 3, 4, 5, 6, 7)
                : __builtin_shufflevector(__builtin_shufflevector(f, f, 0, 1, 2, 3), v, 0, 1, 2, 3, 4, 5, 6, 7);
-}
-template <int N>
-__device__ __forceinline__ void lds_wait_all_but(bf16x8& frag) {
-    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(frag) : "n"(N));
 }
 __device__ __forceinline__ uint32_t lds_address(const void* generic_lds_ptr) {
     return (uint32_t)(uintptr_t)(PULSECOL_LDS const void*)generic_lds_ptr;
@@ -169,7 +157,6 @@ struct AttnWave {
     static constexpr int NP = KK + NPV;                  // MFMA pairs of a half-step
     static constexpr int NS = 2 * NP;                    // MFMA slots of a half-step
     static constexpr int EXP_TICKS = 34;                 // 32 values through a 3-stage pipeline
-    // exp ticks finished before slot s (slot NS = end of the half-step)
     // ticks issued before slot s: spread over all slots but the last one, so that the row sums
     // are complete (and their check can be computed) one slot before the half-step ends
     static constexpr int exp_ticks_before(int s) {
@@ -539,9 +526,9 @@ struct AttnWave {
     // S(j+1) and of the V tile of P(j-1).  kpre holds the first AHEAD K fragments, already
     // requested; with HAS_NEXT it is refilled with requests for the following half-step
     // (offset NKOFF).  ROLE 0 = first half-step of an iteration: besides its own work it loads
-    // the row numbers of tile next_tile and issues the direct-to-LDS loads of a K and a V tile
-    // (LDS offsets KW / VW from the wave's base), one instruction per MFMA pair.  ROLE 1 =
-    // second half-step: holds the workgroup barrier, see steady_iter.
+    // the row numbers of tile next_tile and issues the direct-to-LDS loads of a K tile (LDS
+    // offset KW from the wave's base).  ROLE 1 = second half-step: issues the loads of a V tile
+    // (offset VW) and holds the workgroup barrier, see steady_iter.
     template <int KOFF, int VOFF, bool HAS_NEXT, int NKOFF, int ROLE, int KW, int VW>
     __device__ __forceinline__ void fast_step(const uint32_t (&kv)[KK], const uint32_t (&vv)[ODB],
                                               bf16x8 (&kpre)[AHEAD],
@@ -666,10 +653,10 @@ struct AttnWave {
         }
     }
     // One steady-state iteration u (U4 = u % NBUF): half-steps j = 2u+1 and 2u+2, which read K
-    // tile u+1 and V tile u.  The first half-step issues the loads of K(u+3) and V(u+2); the
-    // second one holds the barrier -- placed after its last K read, so that K(u+2), V(u+1) are
-    // visible to every wave before anything reads them -- and then requests the first K
-    // fragments of the next iteration while its P V MFMAs run.
+    // tile u+1 and V tile u.  The first half-step issues the loads of K(u+3), the second one
+    // those of V(u+2); the second one also holds the barrier -- placed after its last K read, so
+    // that K(u+2), V(u+1) are visible to every wave before anything reads them -- and then
+    // requests the first K fragments of the next iteration while its P V MFMAs run.
     template <int U4>
     __device__ __forceinline__ void steady_iter(const uint32_t (&kv)[KK], const uint32_t (&vv)[ODB],
                                                 bf16x8 (&kpre)[AHEAD], int next_tile,
@@ -747,7 +734,18 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     w.init_addresses();
     const int n = p.n, nhalf = w.nhalf;
 
-    // ---- Q fragments: B operand, [query lq][d = kk*16 + 8*lh .. +7], parked in AGPRs
+    // ---- prologue.  Issue order: the row numbers of tiles 0..3, the Q fragments, then -- as
+    // the row numbers arrive -- the direct-to-LDS loads of tiles 0..2, so that the Q loads and
+    // the first K/V tiles are in flight together.  Afterwards rows_v = tile 2, rows_k = tile 3.
+    int rows_k[CH], rows_v[CH], rows_n[CH];
+    int rows_0[CH], rows_1[CH];
+    static_assert(PRO_TILES == 3, "the prologue is written out for three tiles");
+    w.load_rows(0, rows_0);
+    w.load_rows(1, rows_1);
+    w.load_rows(2, rows_v);
+    w.load_rows(3, rows_k);
+
+    // Q fragments: B operand, [query lq][d = kk*16 + 8*lh .. +7], parked in AGPRs
     const int q0 = qblk * BM + w.wave * 64;
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
@@ -757,6 +755,9 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) w.qf[qb][kk] = *(const bf16x8*)(src + kk * 16);
     }
+    w.issue_tile(lds_k, lds_v, w.K, w.V, rows_0, rows_0);
+    w.issue_tile(lds_k + TILE_BYTES, lds_v + (HAS_V ? TILE_BYTES : 0), w.K, w.V, rows_1, rows_1);
+    w.issue_tile(lds_k + 2 * TILE_BYTES, lds_v + (HAS_V ? 2 * TILE_BYTES : 0), w.K, w.V, rows_v, rows_v);
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
@@ -769,16 +770,6 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
             for (int r = 0; r < 16; ++r) w.o_acc[qb][db][r] = 0.f;
             asm volatile("" : "+a"(w.o_acc[qb][db]));
         }
-
-    // ---- prologue: tiles 0..2 of K and V into their slots; then rows_k = tile 3, rows_v = tile 2
-    int rows_k[CH], rows_v[CH], rows_n[CH];
-#pragma unroll 1
-    for (int t = 0; t < PRO_TILES; ++t) {
-        w.load_rows(t, rows_k);
-        w.issue_tile(lds_k + t * TILE_BYTES, lds_v + (HAS_V ? t * TILE_BYTES : 0), w.K, w.V, rows_k, rows_k);
-    }
-    w.load_rows(2, rows_v);
-    w.load_rows(3, rows_k);
     wait_vmcnt_at_most<0>();
     __builtin_amdgcn_s_barrier();
 

@@ -32,18 +32,6 @@ __device__ __forceinline__ f32x16 mfma_bf16(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-// Same instruction with the accumulator pinned to the AGPR half of the register file: the
-// output accumulator is only ever touched by the matrix pipe inside the main loop, and
-// keeping its 128 registers out of the VALU-addressable half leaves room for Q, S and P.
-// The compiler does not see this as a matrix instruction: a VALU access to `c` must be
-// preceded by mfma_agpr_settle().
-__device__ __forceinline__ void mfma_bf16_agpr(f32x16& c, bf16x8 a, bf16x8 b) {
-    asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
-}
-// Waits out the write-back of every matrix instruction issued so far (the longest hazard on
-// gfx950 is 18 wait states after a 16-pass instruction).
-__device__ __forceinline__ void mfma_agpr_settle() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
-
 __device__ __forceinline__ f32x16 mfma_f32(float a, float b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
 }
