@@ -342,6 +342,23 @@ def groupwise_config(pc, torch, dev, w, keep, G, host_qkv):
     topk_ms = timed(lambda: ctx.topk(scores, k, idx_out=idx), 3)
     select_ms = timed(lambda: ctx.select(Q, K, keep, refresh=True, idx_out=idx), 1)
     attn_ms = timed(lambda: ctx.attn(Q, K, V, idx, O=O), 10 if G >= 256 else 4)
+    extra = {}
+    if G >= 256:
+        # In-house block-sparse point at the same budget (the paper's Sec. 3.1 block mask
+        # S(i,j) = G(b(i), b(j)) with query blocks = the groups and key blocks of 64): the same
+        # kernel fed whole key blocks, chosen by block mass.  Index bookkeeping with torch ops --
+        # this is a comparison input, not part of the product path.  "mass" = share of the
+        # group's softmax mass that the kept columns carry (the scores of a group sum to one).
+        kb = max(1, k // 64)
+        blocks = scores.view(B, H, U, n // 64, 64).sum(-1).topk(kb, dim=-1).indices.sort(dim=-1).values
+        bs_idx = (blocks[..., None] * 64 + torch.arange(64, device=dev)).view(B, H, U, kb * 64).to(torch.int32).contiguous()
+        bs_ms = timed(lambda: ctx.attn(Q, K, V, bs_idx, O=O), 10)
+        mass_cs = scores.gather(-1, idx.long()).sum(-1).mean().item()
+        mass_bs = scores.gather(-1, bs_idx.long()).sum(-1).mean().item()
+        extra = {"block_sparse_same_budget": {"key_block": 64, "kept_columns": kb * 64, "attn_ms": round(bs_ms, 4),
+                                              "mass_kept": round(mass_bs, 4)},
+                 "column_sparse_mass_kept": round(mass_cs, 4)}
+        del blocks, bs_idx
     topk_bytes = B * H * U * (5 * 4 * n + 4 * k)
     gather_bytes = B * H * U * 2 * k * d * 2 + 2 * B * H * n * d * 2      # K and V rows per group, Q, O
     res = {"group_size": G, "groups_per_head": U, "k": k,
@@ -350,6 +367,7 @@ def groupwise_config(pc, torch, dev, w, keep, G, host_qkv):
            "select_ms": round(select_ms, 3), "attn_ms": round(attn_ms, 4),
            "kept_tflops": round(4.0 * B * H * n * k * d / (attn_ms * 1e-3) * 1e-12, 2),
            "attn_requested_gbps": round(gather_bytes / (attn_ms * 1e-3) * 1e-9, 1)}
+    res.update(extra)
     ctx.close()
     del Q, K, V, O, idx, scores
     torch.cuda.empty_cache()

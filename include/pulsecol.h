@@ -29,8 +29,9 @@
  *     The caller owns every buffer it passes; the context owns only the scratch it
  *     allocated at creation (row log-sum-exp, column scores, top-k counters, the cached
  *     pattern).  No call allocates or frees device memory except create/destroy.
- *   - Every function returns a pulsecol_status; nothing aborts or throws.  On failure no
- *     kernel has been launched.  pulsecol_last_error gives a text for the last failure on a
+ *   - Every function returns a pulsecol_status; nothing aborts or throws, and nothing is
+ *     printed unless the environment variable PULSECOL_LOG is set (then every failure goes
+ *     to stderr as well).  On failure no kernel has been launched.  pulsecol_last_error gives a text for the last failure on a
  *     context.  Two calls on one context must not overlap in time (they share scratch).
  *   - NaN / Inf in the inputs give unspecified values, never a fault.
  */

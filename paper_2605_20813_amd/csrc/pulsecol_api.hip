@@ -38,6 +38,9 @@ thread_local std::string g_last_error;   // failures that have no context to att
 pulsecol_status fail(pulsecol_ctx* ctx, pulsecol_status st, const std::string& msg) {
     if (ctx) ctx->last_error = msg;
     g_last_error = msg;
+    // nothing is printed unless the caller asks for it
+    static const bool log = [] { const char* e = std::getenv("PULSECOL_LOG"); return e && e[0] && e[0] != '0'; }();
+    if (log) std::fprintf(stderr, "pulsecol: status %d: %s\n", (int)st, msg.c_str());
     return st;
 }
 
