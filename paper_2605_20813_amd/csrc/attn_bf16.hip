@@ -784,6 +784,10 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     w.qk_all(lds_k, 0, SA);
     mfma_settle(SA[0], SA[1]);
     w.mask_tail(0, SA);
+    // The first half-tile sets the softmax reference directly (it is the maximum seen so far, so no term
+    // can overflow), which keeps the first step off the slow reference-update path.
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) w.mc[qb] = w.half_tile_max(SA[qb]) * w.c2;
 
     // j = 0: S(0) in SA -> P(0) in PA, S(1) in SB
     w.general_step(0, lds_k, lds_v, SA, SB, PB, PA);
