@@ -241,66 +241,55 @@ struct AttnWave {
     // Which sequence position goes where: load instruction i of a wave fills LDS tile row
     // (wave*CH + i)*ROWS_PER_CHUNK + lrow, and it takes position wave*16 + lrow*CH + i of the
     // tile's 64 (K and V alike, so scores and values still meet; only tail masking has to know).
-    // A lane's CH positions are then consecutive and their row numbers come with one load.
-    __device__ __forceinline__ void load_rows(int t, int (&dst)[CH]) const {
+    // A lane's CH positions are then consecutive, and their row numbers are ONE load of CH
+    // entries of the pattern, starting at entry `first_entry`: the lane's first position, pulled
+    // back so that all CH entries lie inside the pattern.  In the last tile a lane whose positions
+    // straddle or pass the end thereby fetches entries that belong to earlier positions a second
+    // time; entry_is_new() tells them apart and mask_tail() gives those positions weight zero.
+    typedef int rows_t __attribute__((ext_vector_type(CH)));
+    __device__ __forceinline__ int first_entry(int first_pos) const {
+        const int last = ns > CH ? ns - CH : 0;
+        return first_pos < last ? first_pos : last;
+    }
+    // position p (element p % CH of its lane) holds an entry of its own, inside the pattern
+    __device__ __forceinline__ bool entry_is_new(int p) const {
+        const int p0 = p - p % CH;
+        const int e = first_entry(p0) + p % CH;
+        return e >= p0 && e < ns;
+    }
+    __device__ __forceinline__ void load_rows(int t, rows_t& dst) const {
         static_assert(CH * ROWS_PER_CHUNK == 16, "a wave fills 16 rows of a tile");
         t = t < ntiles ? t : ntiles - 1;          // past the end: repeat the last tile (never read back)
-        const bool whole = (t + 1) * BN <= ns;    // the tile lies inside the pattern (uniform)
+        const int e0 = first_entry(t * BN + wave * 16 + lrow * CH);
         if (GATHER) {
-            const uint32_t off = (uint32_t)(t * (BN * 4)) + lane_rows_off;
-            if (__builtin_expect(whole, 1)) {
-                typedef int rows_t __attribute__((ext_vector_type(CH), aligned(4)));
-                const rows_t r = *(const rows_t*)(idx + off);
+            if (__builtin_expect(ns >= CH, 1)) {
+                typedef int unaligned_rows_t __attribute__((ext_vector_type(CH), aligned(4)));
+                dst = *(const unaligned_rows_t*)(idx + (uint32_t)e0 * 4u);
+            } else {
 #pragma unroll
-                for (int i = 0; i < CH; ++i) dst[i] = r[i];
-            }
-            if (__builtin_expect(!whole, 0)) {
-#pragma unroll
-                for (int i = 0; i < CH; ++i) {
-                    uint32_t o = off + 4u * i;    // ragged tail: any valid row; masked later
-                    o = o < (uint32_t)ns * 4u ? o : (uint32_t)ns * 4u - 4u;
-                    dst[i] = *(const int*)(idx + o);
-                }
+                for (int i = 0; i < CH; ++i) dst[i] = *(const int*)(idx + (uint32_t)(e0 + i < ns ? e0 + i : ns - 1) * 4u);
             }
         } else {
-            const int base = t * BN + wave * 16 + lrow * CH;
 #pragma unroll
-            for (int i = 0; i < CH; ++i) dst[i] = base + i < ns ? base + i : ns - 1;
+            for (int i = 0; i < CH; ++i) dst[i] = e0 + i < ns ? e0 + i : ns - 1;
         }
     }
-    // The same for the scheduled half-steps, with loads the compiler does not see: it would
-    // otherwise wait for ALL outstanding vector memory operations (the direct-to-LDS loads
-    // included) in front of the first use.  The row numbers are used one iteration later; the
-    // wait in front of the running iteration's barrier already covers them (they are older
-    // than every direct-to-LDS load that wait leaves in flight).
-    __device__ __forceinline__ void load_rows_async(int t, int (&dst)[CH]) const {
+    // The same for the scheduled half-steps (which only run when the pattern has more than one
+    // tile, so ns > CH), with a load the compiler does not see: it would otherwise wait for ALL
+    // outstanding vector memory operations (the direct-to-LDS loads included) in front of the
+    // first use.  The row numbers are used one iteration later; the wait in front of the running
+    // iteration's barrier already covers them (they are older than every direct-to-LDS load that
+    // wait leaves in flight).  The destination is the whole variable, written by this one
+    // statement on every path: nothing may copy it before the data has arrived, and the
+    // registers must stay reserved until then (the kernel names them in a final wait).
+    __device__ __forceinline__ void load_rows_async(int t, rows_t& dst) const {
         if (!GATHER) { load_rows(t, dst); return; }
         t = t < ntiles ? t : ntiles - 1;
-        const bool whole = (t + 1) * BN <= ns;
-        const uint32_t off = (uint32_t)(t * (BN * 4)) + lane_rows_off;
-        if (__builtin_expect(whole, 1)) {
-            if constexpr (CH == 4) {
-                u32x4 r;
-                asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(r) : "v"(off), "s"(idx));
-#pragma unroll
-                for (int i = 0; i < CH; ++i) dst[i] = (int)r[i];
-            } else {
-                static_assert(CH == 2 || CH == 4, "row numbers per lane and tile");
-                typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-                u32x2 r;
-                asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(r) : "v"(off), "s"(idx));
-#pragma unroll
-                for (int i = 0; i < CH; ++i) dst[i] = (int)r[i];
-            }
-        }
-        if (__builtin_expect(!whole, 0)) {
-#pragma unroll
-            for (int i = 0; i < CH; ++i) {
-                uint32_t o = off + 4u * i;
-                o = o < (uint32_t)ns * 4u ? o : (uint32_t)ns * 4u - 4u;
-                asm volatile("global_load_dword %0, %1, %2" : "=v"(dst[i]) : "v"(o), "s"(idx));
-            }
-        }
+        const uint32_t want = (uint32_t)(t * (BN * 4)) + lane_rows_off, last = (uint32_t)(ns - CH) * 4u;
+        const uint32_t off = want < last ? want : last;
+        static_assert(CH == 2 || CH == 4, "row numbers per lane and tile");
+        if constexpr (CH == 4) asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(off), "s"(idx));
+        else asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(dst) : "v"(off), "s"(idx));
     }
     // position inside its tile of the key in LDS tile row `row`
     static __device__ __forceinline__ int tile_pos(int row) {
@@ -311,19 +300,21 @@ struct AttnWave {
     // and therefore fetches the global piece (L%PIECES) ^ swizzle(row) of that row.
     // (Every pointer is a restrict parameter so that the loads carry alias scopes: the compiler
     // then knows that LDS reads of other slots need not wait for these loads.)
-    __device__ __forceinline__ void issue_tile(byte* __restrict__ kslot, byte* __restrict__ vslot,
-                                               const byte* __restrict__ Kg, const byte* __restrict__ Vg,
-                                               const int (&krows)[CH], const int (&vrows)[CH]) const {
+    __device__ __forceinline__ void issue_k_tile(byte* __restrict__ kslot, const byte* __restrict__ Kg,
+                                                 const rows_t& rows) const {
 #pragma unroll
         for (int i = 0; i < CH; ++i)
             __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(Kg + row_offset(krows[i], koff[i])),
+                (const __attribute__((address_space(1))) void*)(Kg + row_offset(rows[i], koff[i])),
                 (PULSECOL_LDS void*)(kslot + (wave * CH + i) * 1024), 16, 0, 0);
+    }
+    __device__ __forceinline__ void issue_v_tile(byte* __restrict__ vslot, const byte* __restrict__ Vg,
+                                                 const rows_t& rows) const {
         if (HAS_V) {
 #pragma unroll
             for (int i = 0; i < CH; ++i)
                 __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void*)(Vg + row_offset(vrows[i], voff[i])),
+                    (const __attribute__((address_space(1))) void*)(Vg + row_offset(rows[i], voff[i])),
                     (PULSECOL_LDS void*)(vslot + (wave * CH + i) * 1024), 16, 0, 0);
         }
     }
@@ -359,13 +350,21 @@ struct AttnWave {
     }
 
     // ------------------------------------------------------------------ softmax pieces
-    // columns of the last tile that lie past ns get weight zero
+    // positions of the last tile without an entry of their own (past ns, or a repeat of an
+    // earlier position's entry, see load_rows) get weight zero
     __device__ __forceinline__ void mask_tail(int j, f32x16 (&S)[2]) const {
         if (ragged && j >= nhalf - 2) {
-            const int valid = ns - (j >> 1) * BN;
+            const int tile_start = (j >> 1) * BN;
 #pragma unroll
             for (int r = 0; r < 16; ++r)
-                if (tile_pos((j & 1) * 32 + acc_row(r, lh)) >= valid) { S[0][r] = -INFINITY; S[1][r] = -INFINITY; }
+                if (!entry_is_new(tile_start + tile_pos((j & 1) * 32 + acc_row(r, lh)))) { S[0][r] = -INFINITY; S[1][r] = -INFINITY; }
+        }
+    }
+    // the same for half `half` of the last tile, right behind the scheduled half-step that formed S
+    __device__ __forceinline__ void mask_last_tile(int half, f32x16 (&S)[2]) const {
+        if (ragged) {
+            mfma_settle(S[0], S[1]);
+            mask_tail(nhalf - 2 + half, S);
         }
     }
     // maximum over this lane's 16 values and the 16 of the lane that shares its query column
@@ -459,10 +458,17 @@ struct AttnWave {
                 mc[qb] = first ? m2 : mc[qb] + steps;
                 l_run[qb] *= alpha;
                 if (HAS_V) {
+                    // one block at a time, pinned inside this branch: the accumulator passes through
+                    // VGPRs, and all of it at once does not fit beside the rest of the loop's registers
 #pragma unroll
-                    for (int db = 0; db < ODB; ++db)
+                    for (int db = 0; db < ODB; ++db) {
+                        f32x16 t = o_acc[qb][db];
+                        asm volatile("" : "+v"(t));
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) o_acc[qb][db][r] *= alpha;
+                        for (int r = 0; r < 16; ++r) t[r] *= alpha;
+                        o_acc[qb][db] = t;
+                        asm volatile("" : "+a"(o_acc[qb][db]));
+                    }
                 }
                 float rs = 0.f;
 #pragma unroll
@@ -532,8 +538,8 @@ struct AttnWave {
     template <int KOFF, int VOFF, bool HAS_NEXT, int NKOFF, int ROLE, int KW, int VW>
     __device__ __forceinline__ void fast_step(const uint32_t (&kv)[KK], const uint32_t (&vv)[ODB],
                                               bf16x8 (&kpre)[AHEAD],
-                                              int next_tile, const int (&krows)[CH], const int (&vrows)[CH],
-                                              int (&rows_n)[CH],
+                                              int next_tile, const rows_t& krows, const rows_t& vrows,
+                                              rows_t& rows_n,
                                               f32x16 (&S_in)[2], f32x16 (&S_out)[2],
                                               bf16x8 (&P_in)[2][2], bf16x8 (&P_out)[2][2]) {
         bf16x8 fr[NP + AHEAD];
@@ -554,8 +560,8 @@ struct AttnWave {
     __device__ __forceinline__ void fast_pairs(std::integer_sequence<int, Ps...>,
                                                const uint32_t (&kv)[KK], const uint32_t (&vv)[ODB],
                                                bf16x8 (&fr)[NP + AHEAD], ExpPipe& ep,
-                                               int next_tile, const int (&krows)[CH], const int (&vrows)[CH],
-                                               int (&rows_n)[CH],
+                                               int next_tile, const rows_t& krows, const rows_t& vrows,
+                                               rows_t& rows_n,
                                                f32x16 (&S_in)[2], f32x16 (&S_out)[2],
                                                bf16x8 (&P_in)[2][2], bf16x8 (&P_out)[2][2]) {
         (fast_pair<Ps, KOFF, VOFF, HAS_NEXT, NKOFF, ROLE, KW, VW>(kv, vv, fr, ep, next_tile, krows, vrows, rows_n,
@@ -565,8 +571,8 @@ struct AttnWave {
     template <int P, int KOFF, int VOFF, bool HAS_NEXT, int NKOFF, int ROLE, int KW, int VW>
     __device__ __forceinline__ void fast_pair(const uint32_t (&kv)[KK], const uint32_t (&vv)[ODB],
                                               bf16x8 (&fr)[NP + AHEAD], ExpPipe& ep,
-                                              int next_tile, const int (&krows)[CH], const int (&vrows)[CH],
-                                              int (&rows_n)[CH],
+                                              int next_tile, const rows_t& krows, const rows_t& vrows,
+                                              rows_t& rows_n,
                                               f32x16 (&S_in)[2], f32x16 (&S_out)[2],
                                               bf16x8 (&P_in)[2][2], bf16x8 (&P_out)[2][2]) {
         static_assert(LOAD_STRIDE >= 1 && k_addr_pair(CH - 1) + 1 < NP && v_addr_pair(CH - 1) + 1 < NP, "load schedule fits the half-step");
@@ -653,16 +659,18 @@ struct AttnWave {
         }
     }
     // One steady-state iteration u (U4 = u % NBUF): half-steps j = 2u+1 and 2u+2, which read K
-    // tile u+1 and V tile u.  The first half-step issues the loads of K(u+3), the second one
+    // tile u+1 and V tile u.  `last` marks the iteration whose K tile is the last one of the pattern:
+    // its scores get the tail mask.  (It still issues loads, of tiles past the end: load_rows hands
+    // those the row numbers of the last tile, and the slots they fill are not read again.)  The first half-step issues the loads of K(u+3), the second one
     // those of V(u+2); the second one also holds the barrier -- placed after its last K read, so
     // that K(u+2), V(u+1) are visible to every wave before anything reads them -- and then
     // requests the first K fragments of the next iteration while its P V MFMAs run.
     template <int U4>
     __device__ __forceinline__ void steady_iter(const uint32_t (&kv)[KK], const uint32_t (&vv)[ODB],
                                                 bf16x8 (&kpre)[AHEAD], int next_tile,
-                                                const int (&krows)[CH], const int (&vrows)[CH], int (&rows_n)[CH],
+                                                const rows_t& krows, const rows_t& vrows, rows_t& rows_n,
                                                 f32x16 (&SA)[2], f32x16 (&SB)[2],
-                                                bf16x8 (&PA)[2][2], bf16x8 (&PB)[2][2]) {
+                                                bf16x8 (&PA)[2][2], bf16x8 (&PB)[2][2], bool last) {
         static_assert(KK >= AHEAD, "the first fragments of a half-step are K fragments");
         constexpr int KR = (U4 + 1) % NBUF * TILE_BYTES;        // K(u+1)
         constexpr int VR = U4 * TILE_BYTES;                     // V(u)
@@ -671,9 +679,11 @@ struct AttnWave {
         constexpr int VW = (NBUF + (U4 + 2) % NBUF) * TILE_BYTES;   // V(u+2), the V slots follow the K slots
         // odd:  S(j) in SB, P(j-1) in PA -> S(j+1) in SA, P(j) in PB
         fast_step<KR, VR, true, KR + HALF_BYTES, 0, KW, VW>(kv, vv, kpre, next_tile, krows, vrows, rows_n, SB, SA, PA, PB);
+        if (last) mask_last_tile(0, SA);
         // even: S(j) in SA, P(j-1) in PB -> S(j+1) in SB, P(j) in PA
         fast_step<KR + HALF_BYTES, VR + HALF_BYTES, HAS_V, KN, 1, KW, VW>(kv, vv, kpre, next_tile, krows, vrows, rows_n,
                                                                          SA, SB, PB, PA);
+        if (last) mask_last_tile(1, SB);
         if (!HAS_V) {
             // row pass: no P V stream to cover the barrier; synchronise at the end of the iteration
             wait_vmcnt_at_most<VM_PER_ISSUE>();
@@ -697,10 +707,20 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     // ONE shared array for all tile slots: with a single LDS object the alias scopes that the
     // restrict parameters give the direct-to-LDS loads are what the compiler's wait-count
     // insertion sees, and LDS reads of one slot do not wait for loads into another.
-    __shared__ __attribute__((aligned(1024))) byte lds_all[(NBUF_K + (HAS_V ? NBUF_V : 0)) * TILE_BYTES];
+    // Behind them, room for the Q block, which is turned around in LDS at the start: a wave's 64 Q
+    // rows are one tile's worth of bytes, and with V slots three of the waves borrow the tile slots
+    // that the prologue leaves empty (K slot 3, V slots 2 and 3).
+    constexpr int QSTAGE_TILES = HAS_V ? 1 : 4;
+    __shared__ __attribute__((aligned(1024))) byte lds_all[(NBUF_K + (HAS_V ? NBUF_V : 0) + QSTAGE_TILES) * TILE_BYTES];
     byte* const lds_k = lds_all;
     byte* const lds_v = lds_all + (HAS_V ? NBUF_K * TILE_BYTES : 0);
 
+    // Fetch every kernel argument with the first batch of scalar loads: left to itself the compiler
+    // loads them where they are first used, one memory round trip after another.
+    asm volatile("" : : "s"(p.q), "s"(p.k), "s"(p.v), "s"(p.o), "s"(p.idx), "s"(p.lse), "s"(p.lse_base2),
+                         "s"(p.td.sb), "s"(p.td.sh), "s"(p.td.sn), "s"(p.td_kv.sb), "s"(p.td_kv.sh), "s"(p.td_kv.sn),
+                         "s"(p.kv_heads), "s"(p.batch), "s"(p.heads), "s"(p.n), "s"(p.ns), "s"(p.groups),
+                         "s"(p.group_size), "s"(p.scale));
     const int nqb = (p.n + BM - 1) / BM;
     int bh, qblk;
     if (!xcd_tile(blockIdx.x, nqb, p.batch * p.heads, &bh, &qblk)) return;
@@ -734,34 +754,46 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     w.init_addresses();
     const int n = p.n, nhalf = w.nhalf;
 
-    // ---- prologue.  Issue order: the row numbers of tiles 0..3, the Q fragments, then -- as
-    // the row numbers arrive -- the direct-to-LDS loads of tiles 0..2, so that the Q loads and
-    // the first K/V tiles are in flight together.  Afterwards rows_v = tile 2, rows_k = tile 3.
-    int rows_k[CH], rows_v[CH], rows_n[CH];
-    int rows_0[CH], rows_1[CH];
+    // ---- prologue.  The vector memory pipe returns loads in issue order, so the order below is
+    // the order of need, and each wait names how many of the youngest loads may still be in flight:
+    //   row numbers of tiles 0..3, the first touch of every Q line, K(0), the rest of Q  -> S(0), S(1)
+    //   V(0), K(1)                                                                        -> first iteration
+    //   V(1), K(2)                                                                        -> its barrier
+    // (V(2) is loaded by the first iteration itself.)  Afterwards rows_v = tile 2, rows_k = tile 3.
+    typename W::rows_t rows_k, rows_v, rows_n, rows_0, rows_1;
     static_assert(PRO_TILES == 3, "the prologue is written out for three tiles");
     w.load_rows(0, rows_0);
     w.load_rows(1, rows_1);
     w.load_rows(2, rows_v);
     w.load_rows(3, rows_k);
 
-    // Q fragments: B operand, [query lq][d = kk*16 + 8*lh .. +7], parked in AGPRs
+    // Q block: loaded like a K tile -- whole rows straight into LDS, 16 lanes per row, swizzled on
+    // the global side -- and read back as B-operand fragments [query lq][d = kk*16 + 8*lh .. +7].
+    // (A direct load of a fragment touches 32 rows x 32 bytes, four instructions per 128-byte line,
+    // and the block does not fit the vector cache.)  Each wave stages its own 64 rows.
     const int q0 = qblk * BM + w.wave * 64;
+    const int qstage_tile = HAS_V ? (w.wave == 0 ? PRO_TILES : w.wave == 3 ? NBUF_K + NBUF_V : NBUF_K + 1 + w.wave)
+                                  : NBUF_K + w.wave;
+    byte* const qstage = lds_all + qstage_tile * TILE_BYTES;
+    {
+        constexpr int RPC = W::ROWS_PER_CHUNK, PIECES = W::PIECES;
+        const int lrow = w.lane / PIECES, lpiece = w.lane % PIECES;
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-        int row = q0 + qb * 32 + w.lq;
-        row = row < n ? row : n - 1;
-        const __bf16* src = Q + (int64_t)row * p.td.sn + 8 * w.lh;
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk) w.qf[qb][kk] = *(const bf16x8*)(src + kk * 16);
+        for (int t = 0; t < TILE_BYTES / 1024; ++t) {
+            const int r = t * RPC + lrow;
+            int row = q0 + r;
+            row = row < n ? row : n - 1;
+            const byte* src = (const byte*)Q + ((int64_t)row * p.td.sn * 2 + ((lpiece ^ swizzle_k<PIECES>(r)) << 4));
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                             (PULSECOL_LDS void*)(qstage + t * 1024), 16, 0, 0);
+        }
     }
-    w.issue_tile(lds_k, lds_v, w.K, w.V, rows_0, rows_0);
-    w.issue_tile(lds_k + TILE_BYTES, lds_v + (HAS_V ? TILE_BYTES : 0), w.K, w.V, rows_1, rows_1);
-    w.issue_tile(lds_k + 2 * TILE_BYTES, lds_v + (HAS_V ? 2 * TILE_BYTES : 0), w.K, w.V, rows_v, rows_v);
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk) asm volatile("" : "+a"(w.qf[qb][kk]));
+    w.issue_k_tile(lds_k, w.K, rows_0);
+    w.issue_v_tile(lds_v, w.V, rows_0);
+    w.issue_k_tile(lds_k + TILE_BYTES, w.K, rows_1);
+    w.issue_v_tile(lds_v + (HAS_V ? TILE_BYTES : 0), w.V, rows_1);
+    w.issue_k_tile(lds_k + 2 * TILE_BYTES, w.K, rows_v);
+    constexpr int LATER_LOADS = CH * (HAS_V ? 4 : 2);     // V(0), K(1), V(1), K(2)
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
@@ -770,7 +802,14 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
             for (int r = 0; r < 16; ++r) w.o_acc[qb][db][r] = 0.f;
             asm volatile("" : "+a"(w.o_acc[qb][db]));
         }
-    wait_vmcnt_at_most<0>();
+    wait_vmcnt_at_most<LATER_LOADS>();
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            w.qf[qb][kk] = *(const bf16x8*)(qstage + qb * W::HALF_BYTES + w.kaddr[kk]);
+            asm volatile("" : "+a"(w.qf[qb][kk]));
+        }
     __builtin_amdgcn_s_barrier();
 
     f32x16 SA[2], SB[2];
@@ -792,9 +831,12 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     // j = 0: S(0) in SA -> P(0) in PA, S(1) in SB
     w.general_step(0, lds_k, lds_v, SA, SB, PB, PA);
 
-    // ---- steady state: iteration u runs half-steps 2u+1 and 2u+2 (both <= nhalf-4)
-    const int npairs = nhalf >= 4 ? (nhalf - 4) / 2 : 0;
-    if (npairs > 0) {
+    // ---- steady state: iteration u runs half-steps 2u+1 and 2u+2, u = 0 .. ntiles-2; the last
+    // one forms the scores of the last tile.
+    const int niter = w.ntiles - 1;
+    if (niter > 0) {
+        wait_vmcnt_at_most<LATER_LOADS / 2>();            // V(0) and K(1) have landed ...
+        __builtin_amdgcn_s_barrier();                     // ... in every wave
         const uint32_t kbase = lds_address(lds_k), vbase = lds_address(lds_v);
         uint32_t kv[KK], vv[ODB];      // fragment addresses inside slot 0; slots and halves are immediates
         bf16x8 kpre[AHEAD];
@@ -806,46 +848,30 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
         for (int i = 0; i < AHEAD; ++i) kpre[i] = lds_read_b128_at<TILE_BYTES>(kv[i]);     // K tile 1
         // rows_k / rows_v / rows_n rotate by name: after an iteration, v <- k <- n
         int u = 0;
-        for (; u + NBUF <= npairs; u += NBUF) {
-            w.template steady_iter<0>(kv, vv, kpre, u + 4, rows_k, rows_v, rows_n, SA, SB, PA, PB);
-            w.template steady_iter<1>(kv, vv, kpre, u + 5, rows_n, rows_k, rows_v, SA, SB, PA, PB);
-            w.template steady_iter<2>(kv, vv, kpre, u + 6, rows_v, rows_n, rows_k, SA, SB, PA, PB);
-            w.template steady_iter<3>(kv, vv, kpre, u + 7, rows_k, rows_v, rows_n, SA, SB, PA, PB);
-#pragma unroll
-            for (int i = 0; i < CH; ++i) { const int t = rows_n[i]; rows_n[i] = rows_v[i]; rows_v[i] = rows_k[i]; rows_k[i] = t; }
+        for (; u + NBUF < niter; u += NBUF) {
+            w.template steady_iter<0>(kv, vv, kpre, u + 4, rows_k, rows_v, rows_n, SA, SB, PA, PB, false);
+            w.template steady_iter<1>(kv, vv, kpre, u + 5, rows_n, rows_k, rows_v, SA, SB, PA, PB, false);
+            w.template steady_iter<2>(kv, vv, kpre, u + 6, rows_v, rows_n, rows_k, SA, SB, PA, PB, false);
+            w.template steady_iter<3>(kv, vv, kpre, u + 7, rows_k, rows_v, rows_n, SA, SB, PA, PB, false);
+            { const typename W::rows_t t = rows_n; rows_n = rows_v; rows_v = rows_k; rows_k = t; }
         }
-        if (u < npairs) w.template steady_iter<0>(kv, vv, kpre, u + 4, rows_k, rows_v, rows_n, SA, SB, PA, PB);
-        if (u + 1 < npairs) w.template steady_iter<1>(kv, vv, kpre, u + 5, rows_n, rows_k, rows_v, SA, SB, PA, PB);
-        if (u + 2 < npairs) w.template steady_iter<2>(kv, vv, kpre, u + 6, rows_v, rows_n, rows_k, SA, SB, PA, PB);
+        const int rem = niter - u;     // 1 .. NBUF iterations left
+        w.template steady_iter<0>(kv, vv, kpre, u + 4, rows_k, rows_v, rows_n, SA, SB, PA, PB, rem == 1);
+        if (rem >= 2) w.template steady_iter<1>(kv, vv, kpre, u + 5, rows_n, rows_k, rows_v, SA, SB, PA, PB, rem == 2);
+        if (rem >= 3) w.template steady_iter<2>(kv, vv, kpre, u + 6, rows_v, rows_n, rows_k, SA, SB, PA, PB, rem == 3);
+        if (rem >= 4) w.template steady_iter<3>(kv, vv, kpre, u + 7, rows_k, rows_v, rows_n, SA, SB, PA, PB, true);
         // The last iteration has requested fragments for a next one that does not exist: their
         // registers must stay reserved until the data has arrived.
         static_assert(AHEAD == 3, "one operand per prefetched fragment");
         asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kpre[0]), "+v"(kpre[1]), "+v"(kpre[2]));
     }
-    // ---- tail: the remaining half-steps (at most three), then the last P V product.
+    // ---- tail: the last half-step, then the last P V product.
     // The wait names the row-number registers: loads into them that nobody reads any more are
     // still in flight, and the registers must not be handed to other values before they land.
-    static_assert(CH == 2 || CH == 4, "row numbers per lane and tile");
-    if constexpr (CH == 4)
-        asm volatile("s_waitcnt vmcnt(0)"
-                     : "+v"(rows_k[0]), "+v"(rows_k[1]), "+v"(rows_k[2]), "+v"(rows_k[3]),
-                       "+v"(rows_v[0]), "+v"(rows_v[1]), "+v"(rows_v[2]), "+v"(rows_v[3]),
-                       "+v"(rows_n[0]), "+v"(rows_n[1]), "+v"(rows_n[2]), "+v"(rows_n[3]) : : "memory");
-    else
-        asm volatile("s_waitcnt vmcnt(0)"
-                     : "+v"(rows_k[0]), "+v"(rows_k[1]), "+v"(rows_v[0]), "+v"(rows_v[1]),
-                       "+v"(rows_n[0]), "+v"(rows_n[1]) : : "memory");
+    // It also lets the loads of tiles past the end land before the epilogue reuses the slots.
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(rows_k), "+v"(rows_v), "+v"(rows_n) : : "memory");
     __builtin_amdgcn_s_barrier();
-    int j = 2 * npairs + 1;
-    if (j < nhalf) {                              // odd
-        w.general_step(j, lds_k, lds_v, SB, SA, PA, PB);
-        ++j;
-        if (j < nhalf) {                          // even, then the last odd one (nhalf is even)
-            w.general_step(j, lds_k, lds_v, SA, SB, PB, PA);
-            ++j;
-            w.general_step(j, lds_k, lds_v, SB, SA, PA, PB);
-        }
-    }
+    w.general_step(nhalf - 1, lds_k, lds_v, SB, SA, PA, PB);
     w.pv_all(lds_v + (HAS_V ? (((nhalf - 1) >> 1) % NBUF_V) * TILE_BYTES : 0), (nhalf - 1) & 1, PB);
 
     // ---- epilogue: O = diag(l)^-1 acc, optional row log-sum-exp.
@@ -880,13 +906,21 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
                     *(bf16x4*)(stage + r * ROW_BYTES + (((db * 4 + r4) ^ (r & (PIECES - 1))) << 4) + 8 * w.lh) = o4;
                 }
         }
-        byte* const obase = (byte*)((__bf16*)p.o + head_off);
         const int lrow = w.lane / PIECES, lpiece = w.lane % PIECES;
+        byte* const obase = (byte*)((__bf16*)p.o + head_off) + (int64_t)(q0 + lrow) * p.td.sn * 2 + lpiece * 16;
+        const int64_t group_stride = (int64_t)RPC * p.td.sn * 2;      // bytes between row groups (uniform)
+        // all reads first, then the stores: one LDS round trip instead of one per row group
+        u32x4 rows_out[64 / RPC];
 #pragma unroll
         for (int t = 0; t < 64 / RPC; ++t) {
             const int r = t * RPC + lrow;
-            const u32x4 v = *(const u32x4*)(stage + r * ROW_BYTES + ((lpiece ^ (r & (PIECES - 1))) << 4));
-            if (q0 + r < n) *(u32x4*)(obase + (int64_t)(q0 + r) * p.td.sn * 2 + lpiece * 16) = v;
+            rows_out[t] = *(const u32x4*)(stage + r * ROW_BYTES + ((lpiece ^ (r & (PIECES - 1))) << 4));
+        }
+        fence();
+#pragma unroll
+        for (int t = 0; t < 64 / RPC; ++t) {
+            const int r = t * RPC + lrow;
+            if (q0 + r < n) *(u32x4*)(obase + t * group_stride) = rows_out[t];
         }
     }
 }
