@@ -52,7 +52,6 @@ constexpr int NBUF = 4;            // LDS tile slots for K and for V: tile t liv
 constexpr int NBUF_K = NBUF;
 constexpr int NBUF_V = NBUF;
 constexpr int PRO_TILES = 3;       // tiles loaded before the first half-step
-constexpr int AHEAD = 3;           // fragment reads run this many MFMA pairs ahead of their use
 constexpr float kTau = 8.0f;       // log2 of the growth allowed before the reference max is raised
 
 typedef unsigned char byte;
@@ -157,6 +156,11 @@ struct AttnWave {
     static constexpr int NP = KK + NPV;                  // MFMA pairs of a half-step
     static constexpr int NS = 2 * NP;                    // MFMA slots of a half-step
     static constexpr int EXP_TICKS = 34;                 // 32 values through a 3-stage pipeline
+    // One wait per WAIT_PAIRS MFMA pairs, for the fragments of all of them (a wait costs issue
+    // time); fragment reads run AHEAD pairs ahead of their use, so that the last fragment of a
+    // group still has AHEAD - WAIT_PAIRS + 1 pairs to arrive.
+    static constexpr int WAIT_PAIRS = KK >= 8 ? 4 : 2;
+    static constexpr int AHEAD = WAIT_PAIRS + 2;
     // ticks issued before slot s: spread over all slots but the last one, so that the row sums
     // are complete (and their check can be computed) one slot before the half-step ends
     static constexpr int exp_ticks_before(int s) {
@@ -320,20 +324,27 @@ struct AttnWave {
     }
 
     // One load of the scheduled half-step in two parts, so that no slot gets more than two
-    // instructions on top of its own: LDS destination into m0 and the row offset (one VALU
-    // instruction, which also covers the wait state an m0 write needs before its use) behind
-    // the second MFMA of a pair, the load itself behind the first MFMA of the next pair.
-    template <int LDS_OFF>
+    // instructions on top of its own: the row offset (one VALU instruction) behind the second
+    // MFMA of a pair, the load itself behind the first MFMA of the next pair.  The CH loads of a
+    // tile share one LDS base in m0 (written with the first address; the VALU instruction behind
+    // it also covers the wait state an m0 write needs before its use): load j carries the
+    // instruction offset j*1024, which the hardware adds to the LDS address and to the global
+    // address alike, so it reads through a base pointer that lies j*1024 bytes lower.
+    template <int LDS_OFF, int J>
     __device__ __forceinline__ uint32_t issue_addr(int row, uint32_t piece_off) const {
         uint32_t off;
-        asm volatile("s_add_i32 m0, %1, %2\n\tv_mad_u32_u24 %0, %3, %4, %5"
-                     : "=v"(off) : "s"(wave_lds), "n"(LDS_OFF), "v"(row), "s"(row_bytes), "v"(piece_off));
+        if constexpr (J == 0)
+            asm volatile("s_add_i32 m0, %1, %2\n\tv_mad_u32_u24 %0, %3, %4, %5"
+                         : "=v"(off) : "s"(wave_lds), "n"(LDS_OFF), "v"(row), "s"(row_bytes), "v"(piece_off));
+        else
+            asm volatile("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(off) : "v"(row), "s"(row_bytes), "v"(piece_off));
         return off;
     }
     // m0 is written by issue_addr and, in compiler-generated code, only right in front of the
-    // compiler's own uses: nothing touches it between the two halves of a load
+    // compiler's own uses (the prologue's loads): nothing touches it between the loads of a tile
+    template <int J>
     __device__ __forceinline__ void issue_load(const byte* g, uint32_t off) const {
-        asm volatile("global_load_lds_dwordx4 %0, %1" : : "v"(off), "s"(g) : "memory");
+        asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" : : "v"(off), "s"(g - J * 1024), "n"(J * 1024) : "memory");
     }
 
     // ------------------------------------------------------------------ fragment reads
@@ -517,10 +528,11 @@ struct AttnWave {
 
     // LDS operations that the read of fragment q of a scheduled half-step issues: one for a K
     // fragment (q < KK, or q >= NP: the next half-step's first K fragments), two for a V fragment.
+    // ... that have been issued behind the read of fragment p + WAIT_PAIRS - 1 when pair p starts
     template <bool HAS_NEXT>
     static constexpr int newer_ops(int p) {
         int c = 0;
-        for (int i = 1; i < AHEAD; ++i) c += frag_ops<HAS_NEXT>(p + i);
+        for (int i = WAIT_PAIRS; i < AHEAD; ++i) c += frag_ops<HAS_NEXT>(p + i);
         return c;
     }
     template <bool HAS_NEXT>
@@ -580,22 +592,25 @@ struct AttnWave {
         // (Measured on gfx950 with one wave per SIMD: the first non-VALU instruction after an
         // MFMA issues for free, the same instruction in front of the MFMA delays it.)
         constexpr int PA = P + AHEAD;       // the fragment requested during this pair
-        // fragment P has landed once only the requests made after it are outstanding
+        // The fragments of pairs P .. P+WAIT_PAIRS-1 have landed once only the requests made after
+        // them are outstanding; the first pair of each such group waits for all of them.
+        constexpr bool WAITS = P % WAIT_PAIRS == 0;
         constexpr int NEWER = newer_ops<HAS_NEXT>(P);
+        static_assert(NP % WAIT_PAIRS == 0 && AHEAD >= WAIT_PAIRS, "wait groups tile the half-step");
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
             const int s = 2 * P + qb;
             if constexpr (P < KK) {
                 if constexpr (P == 0) {
-                    if (qb == 0) mfma_qk_first_after<NEWER>(S_out[qb], fr[P], qf[qb][P]);
+                    if (qb == 0 && WAITS) mfma_qk_first_after<NEWER>(S_out[qb], fr[P], qf[qb][P]);
                     else mfma_qk_first(S_out[qb], fr[P], qf[qb][P]);
                 } else {
-                    if (qb == 0) mfma_qk_after<NEWER>(S_out[qb], fr[P], qf[qb][P]);
+                    if (qb == 0 && WAITS) mfma_qk_after<NEWER>(S_out[qb], fr[P], qf[qb][P]);
                     else mfma_qk(S_out[qb], fr[P], qf[qb][P]);
                 }
             } else {
                 constexpr int q = P - KK;
-                if (qb == 0) mfma_pv_after<NEWER>(o_acc[qb][q % ODB], fr[P], P_in[qb][q / ODB]);
+                if (qb == 0 && WAITS) mfma_pv_after<NEWER>(o_acc[qb][q % ODB], fr[P], P_in[qb][q / ODB]);
                 else mfma_pv(o_acc[qb][q % ODB], fr[P], P_in[qb][q / ODB]);
             }
             fence();
@@ -609,10 +624,10 @@ struct AttnWave {
                     __builtin_amdgcn_s_barrier();
                 }
                 if constexpr (ROLE == 0 && P >= 1) {
-                    if constexpr (k_addr_at(P - 1) >= 0) issue_load(K, dma_off);
+                    if constexpr (k_addr_at(P - 1) >= 0) issue_load<k_addr_at(P - 1)>(K, dma_off);
                 }
                 if constexpr (ROLE == 1 && HAS_V && P >= 1) {
-                    if constexpr (v_addr_at(P - 1) >= 0) issue_load(V, dma_off);
+                    if constexpr (v_addr_at(P - 1) >= 0) issue_load<v_addr_at(P - 1)>(V, dma_off);
                 }
                 if constexpr (PA < KK) {
                     fr[PA] = lds_read_b128_at<KOFF>(kv[PA]);
@@ -630,11 +645,11 @@ struct AttnWave {
                 if constexpr (ROLE == 0) {
                     if constexpr (P == 0) load_rows_async(next_tile, rows_n);
                     constexpr int j = k_addr_at(P);
-                    if constexpr (j >= 0) dma_off = issue_addr<KW + j * 1024>(krows[j], koff[j]);
+                    if constexpr (j >= 0) dma_off = issue_addr<KW, j>(krows[j], koff[j]);
                 }
                 if constexpr (ROLE == 1 && HAS_V) {
                     constexpr int j = v_addr_at(P);
-                    if constexpr (j >= 0) dma_off = issue_addr<VW + j * 1024>(vrows[j], voff[j]);
+                    if constexpr (j >= 0) dma_off = issue_addr<VW, j>(vrows[j], voff[j]);
                 }
             }
             fence();
@@ -839,6 +854,7 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
         __builtin_amdgcn_s_barrier();                     // ... in every wave
         const uint32_t kbase = lds_address(lds_k), vbase = lds_address(lds_v);
         uint32_t kv[KK], vv[ODB];      // fragment addresses inside slot 0; slots and halves are immediates
+        constexpr int AHEAD = W::AHEAD;
         bf16x8 kpre[AHEAD];
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) kv[kk] = kbase + w.kaddr[kk];
@@ -862,8 +878,8 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
         if (rem >= 4) w.template steady_iter<3>(kv, vv, kpre, u + 7, rows_k, rows_v, rows_n, SA, SB, PA, PB, true);
         // The last iteration has requested fragments for a next one that does not exist: their
         // registers must stay reserved until the data has arrived.
-        static_assert(AHEAD == 3, "one operand per prefetched fragment");
-        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kpre[0]), "+v"(kpre[1]), "+v"(kpre[2]));
+#pragma unroll
+        for (int i = 0; i < AHEAD; ++i) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kpre[i]));
     }
     // ---- tail: the last half-step, then the last P V product.
     // The wait names the row-number registers: loads into them that nobody reads any more are
