@@ -159,7 +159,9 @@ struct AttnWave {
     // One wait per WAIT_PAIRS MFMA pairs, for the fragments of all of them (a wait costs issue
     // time); fragment reads run AHEAD pairs ahead of their use, so that the last fragment of a
     // group still has AHEAD - WAIT_PAIRS + 1 pairs to arrive.
-    static constexpr int WAIT_PAIRS = KK >= 8 ? 4 : 2;
+    // (The row pass has no P V stream behind which the next half-step's first fragments could be
+    // requested; it reads them right behind its barrier and waits for each by itself.)
+    static constexpr int WAIT_PAIRS = !HAS_V ? 1 : (KK >= 8 ? 4 : 2);
     static constexpr int AHEAD = WAIT_PAIRS + 2;
     // ticks issued before slot s: spread over all slots but the last one, so that the row sums
     // are complete (and their check can be computed) one slot before the half-step ends
@@ -725,7 +727,8 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     // Behind them, room for the Q block, which is turned around in LDS at the start: a wave's 64 Q
     // rows are one tile's worth of bytes, and with V slots three of the waves borrow the tile slots
     // that the prologue leaves empty (K slot 3, V slots 2 and 3).
-    constexpr int QSTAGE_TILES = HAS_V ? 1 : 4;
+    // (The row pass keeps its LDS small enough for two workgroups per CU and loads Q directly.)
+    constexpr int QSTAGE_TILES = HAS_V ? 1 : 0;
     __shared__ __attribute__((aligned(1024))) byte lds_all[(NBUF_K + (HAS_V ? NBUF_V : 0) + QSTAGE_TILES) * TILE_BYTES];
     byte* const lds_k = lds_all;
     byte* const lds_v = lds_all + (HAS_V ? NBUF_K * TILE_BYTES : 0);
@@ -787,10 +790,9 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     // (A direct load of a fragment touches 32 rows x 32 bytes, four instructions per 128-byte line,
     // and the block does not fit the vector cache.)  Each wave stages its own 64 rows.
     const int q0 = qblk * BM + w.wave * 64;
-    const int qstage_tile = HAS_V ? (w.wave == 0 ? PRO_TILES : w.wave == 3 ? NBUF_K + NBUF_V : NBUF_K + 1 + w.wave)
-                                  : NBUF_K + w.wave;
+    const int qstage_tile = w.wave == 0 ? PRO_TILES : w.wave == 3 ? NBUF_K + NBUF_V : NBUF_K + 1 + w.wave;
     byte* const qstage = lds_all + qstage_tile * TILE_BYTES;
-    {
+    if constexpr (HAS_V) {
         constexpr int RPC = W::ROWS_PER_CHUNK, PIECES = W::PIECES;
         const int lrow = w.lane / PIECES, lpiece = w.lane % PIECES;
 #pragma unroll
@@ -801,6 +803,15 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
             const byte* src = (const byte*)Q + ((int64_t)row * p.td.sn * 2 + ((lpiece ^ swizzle_k<PIECES>(r)) << 4));
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                              (PULSECOL_LDS void*)(qstage + t * 1024), 16, 0, 0);
+        }
+    } else {
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            int row = q0 + qb * 32 + w.lq;
+            row = row < n ? row : n - 1;
+            const __bf16* src = Q + (int64_t)row * p.td.sn + 8 * w.lh;
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) w.qf[qb][kk] = *(const bf16x8*)(src + kk * 16);
         }
     }
     w.issue_k_tile(lds_k, w.K, rows_0);
@@ -822,7 +833,7 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
-            w.qf[qb][kk] = *(const bf16x8*)(qstage + qb * W::HALF_BYTES + w.kaddr[kk]);
+            if constexpr (HAS_V) w.qf[qb][kk] = *(const bf16x8*)(qstage + qb * W::HALF_BYTES + w.kaddr[kk]);
             asm volatile("" : "+a"(w.qf[qb][kk]));
         }
     __builtin_amdgcn_s_barrier();
