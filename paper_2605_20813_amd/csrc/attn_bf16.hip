@@ -509,21 +509,28 @@ struct AttnWave {
 
     // ------------------------------------------------------------------ half-steps
     // Plain (unscheduled) matrix steps, used by the general half-step.
+    // (All fragment reads go out before the first MFMA: one LDS round trip, not one per fragment.)
     __device__ __forceinline__ void qk_all(const byte* kslot, int half, f32x16 (&S)[2]) const {
+        bf16x8 a[KK];
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) a[kk] = read_k(kslot, half, kk);
+        fence();
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
-            const bf16x8 a = read_k(kslot, half, kk);
-            if (kk == 0) { mfma_qk_first(S[0], a, qf[0][kk]); mfma_qk_first(S[1], a, qf[1][kk]); }
-            else { mfma_qk(S[0], a, qf[0][kk]); mfma_qk(S[1], a, qf[1][kk]); }
+            if (kk == 0) { mfma_qk_first(S[0], a[kk], qf[0][kk]); mfma_qk_first(S[1], a[kk], qf[1][kk]); }
+            else { mfma_qk(S[0], a[kk], qf[0][kk]); mfma_qk(S[1], a[kk], qf[1][kk]); }
         }
     }
     __device__ __forceinline__ void pv_all(const byte* vslot, int half, const bf16x8 (&P)[2][2]) {
-        if (HAS_V) {
+        if constexpr (HAS_V) {
+            bf16x8 a[NPV];
+#pragma unroll
+            for (int q = 0; q < NPV; ++q) a[q] = read_v(vslot, half, q);
+            fence();
 #pragma unroll
             for (int q = 0; q < NPV; ++q) {
-                const bf16x8 a = read_v(vslot, half, q);
-                mfma_pv(o_acc[0][q % ODB], a, P[0][q / ODB]);
-                mfma_pv(o_acc[1][q % ODB], a, P[1][q / ODB]);
+                mfma_pv(o_acc[0][q % ODB], a[q], P[0][q / ODB]);
+                mfma_pv(o_acc[1][q % ODB], a[q], P[1][q / ODB]);
             }
         }
     }
@@ -772,11 +779,11 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     w.init_addresses();
     const int n = p.n, nhalf = w.nhalf;
 
-    // ---- prologue.  The vector memory pipe returns loads in issue order, so the order below is
-    // the order of need, and each wait names how many of the youngest loads may still be in flight:
-    //   row numbers of tiles 0..3, the first touch of every Q line, K(0), the rest of Q  -> S(0), S(1)
-    //   V(0), K(1)                                                                        -> first iteration
-    //   V(1), K(2)                                                                        -> its barrier
+    // ---- prologue.  The vector memory pipe returns loads in issue order, so each wait names how
+    // many of the youngest loads may still be in flight:
+    //   row numbers of tiles 0..3, Q, K(0)  -> everything has landed         -> S(0), S(1)
+    //   V(0), K(1), V(1), K(2)              -> the last two may be in flight -> first iteration
+    //                                       -> its own barrier covers V(1), K(2)
     // (V(2) is loaded by the first iteration itself.)  Afterwards rows_v = tile 2, rows_k = tile 3.
     typename W::rows_t rows_k, rows_v, rows_n, rows_0, rows_1;
     static_assert(PRO_TILES == 3, "the prologue is written out for three tiles");
@@ -815,11 +822,7 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
         }
     }
     w.issue_k_tile(lds_k, w.K, rows_0);
-    w.issue_v_tile(lds_v, w.V, rows_0);
-    w.issue_k_tile(lds_k + TILE_BYTES, w.K, rows_1);
-    w.issue_v_tile(lds_v + (HAS_V ? TILE_BYTES : 0), w.V, rows_1);
-    w.issue_k_tile(lds_k + 2 * TILE_BYTES, w.K, rows_v);
-    constexpr int LATER_LOADS = CH * (HAS_V ? 4 : 2);     // V(0), K(1), V(1), K(2)
+    constexpr int LATER_LOADS = CH * (HAS_V ? 4 : 2);     // V(0), K(1), V(1), K(2): issued behind the first barrier
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
@@ -828,15 +831,25 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
             for (int r = 0; r < 16; ++r) w.o_acc[qb][db][r] = 0.f;
             asm volatile("" : "+a"(w.o_acc[qb][db]));
         }
-    wait_vmcnt_at_most<LATER_LOADS>();
+    wait_vmcnt_at_most<0>();
+    if constexpr (HAS_V) {          // all fragment reads, then one wait
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) w.qf[qb][kk] = *(const bf16x8*)(qstage + qb * W::HALF_BYTES + w.kaddr[kk]);
+    }
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-            if constexpr (HAS_V) w.qf[qb][kk] = *(const bf16x8*)(qstage + qb * W::HALF_BYTES + w.kaddr[kk]);
-            asm volatile("" : "+a"(w.qf[qb][kk]));
-        }
+        for (int kk = 0; kk < KK; ++kk) asm volatile("" : "+a"(w.qf[qb][kk]));
     __builtin_amdgcn_s_barrier();
+    // The next tiles go out now, in the order of need, and arrive while the first half-steps run
+    // (issued in front of the first wait they would have held the wave for as long as they queue
+    // in the memory pipe).
+    w.issue_v_tile(lds_v, w.V, rows_0);
+    w.issue_k_tile(lds_k + TILE_BYTES, w.K, rows_1);
+    w.issue_v_tile(lds_v + (HAS_V ? TILE_BYTES : 0), w.V, rows_1);
+    w.issue_k_tile(lds_k + 2 * TILE_BYTES, w.K, rows_v);
 
     f32x16 SA[2], SB[2];
     bf16x8 PA[2][2], PB[2][2];
@@ -899,14 +912,17 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     asm volatile("s_waitcnt vmcnt(0)" : "+v"(rows_k), "+v"(rows_v), "+v"(rows_n) : : "memory");
     __builtin_amdgcn_s_barrier();
     w.general_step(nhalf - 1, lds_k, lds_v, SB, SA, PA, PB);
+
     w.pv_all(lds_v + (HAS_V ? (((nhalf - 1) >> 1) % NBUF_V) * TILE_BYTES : 0), (nhalf - 1) & 1, PB);
 
     // ---- epilogue: O = diag(l)^-1 acc, optional row log-sum-exp.
     // In the accumulator a lane holds one query row in 8-byte runs: stored directly, every
     // instruction would touch 64 different rows.  Each wave turns its 64 x D tile around in
     // its own piece of LDS (16-byte pieces XOR-swizzled by row against bank conflicts) and
-    // writes whole rows, 16 bytes per lane.
-    if (HAS_V) mfma_settle_acc(w.o_acc);
+    // writes whole rows, 16 bytes per lane.  The staging area is the K slots: no wave reads K
+    // after the barrier above, and the loads that were still writing there have landed.
+    // (Staging d-block by d-block behind the MFMAs of the next block gains nothing: a read of
+    // the accumulator registers waits for the matrix pipe to drain anyway.)
     float l_tot[2];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
@@ -915,9 +931,10 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
         if (p.lse != nullptr && w.lh == 0 && row < n)
             p.lse[(int64_t)bh * n + row] = (w.mc[qb] + fast_log2(l_tot[qb])) * (p.lse_base2 ? 1.0f : kLn2);
     }
-    if (HAS_V) {
+    if constexpr (HAS_V) {
         constexpr int PIECES = W::PIECES, ROW_BYTES = W::ROW_BYTES, RPC = W::ROWS_PER_CHUNK;
-        __builtin_amdgcn_s_barrier();        // every wave has finished reading K and V tiles
+        static_assert(4 * 64 * ROW_BYTES <= NBUF_K * TILE_BYTES, "the staging area lies inside the K slots");
+        mfma_settle_acc(w.o_acc);
         byte* const stage = lds_all + w.wave * 64 * ROW_BYTES;
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
