@@ -53,6 +53,7 @@ constexpr int NBUF_K = NBUF;
 constexpr int NBUF_V = NBUF;
 constexpr int PRO_TILES = 3;       // tiles loaded before the first half-step
 constexpr float kTau = 8.0f;       // log2 of the growth allowed before the reference max is raised
+constexpr float kGrowthLimit = 256.0f;   // 2^kTau
 
 typedef unsigned char byte;
 
@@ -443,10 +444,9 @@ struct AttnWave {
     }
     // Close a half-tile: accept the row sums, or -- if some lane's sum says that its weights
     // outgrew the reference -- fix the reference first.  Every MFMA that adds P(j-1) to the
-    // accumulator has been issued.  SCHEDULED half-steps see finite logits and a finite
-    // reference, so their sums are numbers and one compare serves both query blocks; the general
-    // half-step also meets -inf - (-inf) (first half-tile with masked columns) and tests each
-    // sum in the NaN-catching form.
+    // accumulator has been issued.  SCHEDULED half-steps have formed the test one slot before their
+    // end (on the bit patterns of the sums, which also catches NaN); the general half-step tests
+    // each sum in the NaN-catching floating-point form.
     template <bool SCHEDULED>
     __device__ __forceinline__ void exp_end(ExpPipe& ep, const f32x16 (&S)[2], bf16x8 (&P)[2][2]) {
         if (!SCHEDULED) {
@@ -666,7 +666,13 @@ struct AttnWave {
 #pragma unroll
             for (int i = exp_ticks_before(s); i < exp_ticks_before(s + 1); ++i) exp_tick(i, S_in, P_out, ep);
             // the row sums are complete one slot early: compare now, branch after the last MFMA
-            if (s == NS - 2) ep.bad = __ballot(fmaxf(ep.rs[0], ep.rs[1]) > __builtin_amdgcn_exp2f(kTau));
+            // (Row sums are sums of exp2 results: non-negative, or NaN / +inf.  On their bit patterns the
+            // order of the floats is the order of the integers, NaN lies above everything, and the
+            // integer maximum needs no canonicalising copies of its operands.)
+            if (s == NS - 2) {
+                const uint32_t r0 = __builtin_bit_cast(uint32_t, ep.rs[0]), r1 = __builtin_bit_cast(uint32_t, ep.rs[1]);
+                ep.bad = __ballot((r0 > r1 ? r0 : r1) > __builtin_bit_cast(uint32_t, kGrowthLimit));
+            }
             fence();
         }
     }
