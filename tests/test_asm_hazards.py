@@ -6,7 +6,9 @@ things must therefore hold in the generated code, and neither is visible in the 
 
   * nothing reads or overwrites the destination registers of such a load before a wait that
     covers it (a register copy placed right behind the load would copy the old content);
-  * the registers are not given to another value while the load is in flight.
+  * the registers are not given to another value while the load is in flight;
+  * m0, which the gathers of a tile share as their LDS base, is not written by anything else
+    between the first and the last of them.
 
 The test compiles the file to assembly and walks every attention kernel: it keeps the vector
 memory and the LDS operations in issue order, retires them at each s_waitcnt the way the
@@ -52,6 +54,7 @@ def check_function(lines):
     vm, lgkm = [], []            # in-flight operations, oldest first: sets of guarded registers
     bad = []
     in_asm = False
+    m0_from_asm = False          # m0 holds the LDS base that an assembly statement put there
     for no, raw in lines:
         ins = raw.split(";")[0].strip() if not raw.strip().startswith(";;#") else raw.strip()
         if ins.startswith(";;#ASMSTART"):
@@ -73,6 +76,13 @@ def check_function(lines):
         if op in ("s_branch", "s_endpgm", "s_setpc_b64"):
             vm, lgkm = [], []
             continue
+        # The gathers of a tile share one LDS base in m0: written by the first assembly statement,
+        # used by the later loads through their instruction offsets.  Nothing else may write m0 in
+        # between.
+        if re.match(r"^s_\w+\s+m0\b", ins):
+            m0_from_asm = in_asm
+        if in_asm and op.startswith("global_load_lds") and not m0_from_asm:
+            bad.append((no, ins, ["m0 not set by the gather's own code"]))
         touched = regs_of(ins)
         pending = set().union(*vm, *lgkm) if (vm or lgkm) else set()
         hit = touched & pending
@@ -124,6 +134,21 @@ def test_checker_sees_a_copy_behind_an_asynchronous_load():
     """.split("\n")
     bad = check_function(list(enumerate(reuse)))
     assert len(bad) == 1 and "v11" in bad[0][1]
+    base_lost = """
+        ;;#ASMSTART
+        s_add_i32 m0, s5, 0x4000
+        v_mad_u32_u24 v3, v1, s2, v2
+        ;;#ASMEND
+        ;;#ASMSTART
+        global_load_lds_dwordx4 v3, s[8:9] offset:0
+        ;;#ASMEND
+        s_mov_b32 m0, s7
+        ;;#ASMSTART
+        global_load_lds_dwordx4 v4, s[10:11] offset:0x400
+        ;;#ASMEND
+    """.split("\n")
+    bad = check_function(list(enumerate(base_lost)))
+    assert len(bad) == 1 and "offset:0x400" in bad[0][1]
 
 
 @pytest.mark.skipif(shutil.which("hipcc") is None and not os.path.exists("/opt/rocm/bin/hipcc"), reason="needs hipcc")
