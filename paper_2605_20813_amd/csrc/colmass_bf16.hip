@@ -65,18 +65,34 @@ __global__ void __launch_bounds__(NTHREADS) colmass_bf16_kernel(ScoreParams p) {
 
     u32x4 stage[CH];
     float stage_lse = 0.f;
-    auto fetch = [&](int t) {
+    // Each thread stages the same CH pieces of every tile: its pointers advance by one tile per
+    // iteration (no per-tile row arithmetic); only a last, partial tile clamps its rows.
+    const __bf16* qsrc[CH];
 #pragma unroll
-        for (int j = 0; j < CH; ++j) {
-            const int c = tid + NTHREADS * j;
-            int row = t * QT + c / PIECES;
-            row = row < n ? row : n - 1;
-            stage[j] = *(const u32x4*)(Q + (int64_t)row * p.td.sn + (c % PIECES) * 8);
-        }
-        if (tid < QT) {
-            const int row = t * QT + tid;
-            // rows past the end get +inf: exp2(z - inf) = 0, they add nothing to any column
-            stage_lse = row < n ? lse[row] : INFINITY;
+    for (int j = 0; j < CH; ++j) {
+        const int c = tid + NTHREADS * j;
+        qsrc[j] = Q + (int64_t)(c / PIECES) * p.td.sn + (c % PIECES) * 8;
+    }
+    const int64_t tile_stride = (int64_t)QT * p.td.sn;
+    const float* lse_src = lse + (tid < QT ? tid : 0);
+    auto fetch = [&](int t) {
+        if (__builtin_expect((t + 1) * QT <= n, 1)) {
+#pragma unroll
+            for (int j = 0; j < CH; ++j) stage[j] = *(const u32x4*)(qsrc[j] + t * tile_stride);
+            if (tid < QT) stage_lse = lse_src[t * QT];
+        } else {
+#pragma unroll
+            for (int j = 0; j < CH; ++j) {
+                const int c = tid + NTHREADS * j;
+                int row = t * QT + c / PIECES;
+                row = row < n ? row : n - 1;
+                stage[j] = *(const u32x4*)(Q + (int64_t)row * p.td.sn + (c % PIECES) * 8);
+            }
+            if (tid < QT) {
+                const int row = t * QT + tid;
+                // rows past the end get +inf: exp2(z - inf) = 0, they add nothing to any column
+                stage_lse = row < n ? lse[row] : INFINITY;
+            }
         }
     };
     auto commit = [&](int buf) {
@@ -98,6 +114,8 @@ __global__ void __launch_bounds__(NTHREADS) colmass_bf16_kernel(ScoreParams p) {
     // per key block kb, this lane's key column; four interleaved partial sums keep the add chains independent
     float acc_short[2][4] = {}, acc_long[2][4] = {};
 
+    // rows until the running query group ends (groups are multiples of 32 rows; one group: never)
+    int rows_to_group_end = p.groups > 1 ? p.group_size : 0x7fffffff;
     for (int t = 0; t < ntiles; ++t) {
         const int buf = t & 1;
         if (t + 1 < ntiles) fetch(t + 1);
@@ -144,7 +162,9 @@ __global__ void __launch_bounds__(NTHREADS) colmass_bf16_kernel(ScoreParams p) {
             // half-waves (they hold the same key columns, other query rows), divide by the
             // group's size, store the group's score row, start over
             const int rows_done = t * QT + (qb + 1) * 32;
-            const bool group_end = (qb == 1 && t + 1 == ntiles) || (p.groups > 1 && rows_done < n && rows_done % p.group_size == 0);
+            rows_to_group_end -= 32;
+            const bool group_end = (qb == 1 && t + 1 == ntiles) || (rows_to_group_end == 0 && rows_done < n);
+            if (rows_to_group_end == 0) rows_to_group_end = p.group_size;
             if (group_end) {
                 const int rows_seen = rows_done < n ? rows_done : n;
                 const int u = p.groups > 1 ? (rows_seen - 1) / p.group_size : 0;
