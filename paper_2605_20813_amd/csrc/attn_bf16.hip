@@ -20,11 +20,14 @@
 // order, and with one wave per SIMD every instruction between two MFMAs costs issue time
 // (about 12 ticks for the MFMA itself, 8 for an exp, 4 for anything else, against the 32 ticks
 // the matrix pipe is busy), except that the first non-VALU instruction behind an MFMA is
-// free.  So every slot is: the MFMA (with the wait for its fragment fused in front), then the
-// slot's LDS read / gather instruction / scalar work, then one tick of the softmax work
-// (fma, add, pack, exp); a gather is split over two slots; loads are spread over the whole
-// iteration; the steady loop is unrolled by the four tile slots so that LDS addresses are
-// a base register plus an immediate.  The reference maximum is raised
+// free.  So every slot is: the MFMA (the first of a group of pairs with the wait for the
+// group's fragments fused in front), then the slot's LDS read / gather instruction / scalar
+// work, then one tick of the softmax work (fma, add, pack, exp); a gather is split over two
+// slots; loads are spread over the whole iteration; the steady loop is unrolled by the four
+// tile slots so that LDS addresses are a base register plus an immediate.  One workgroup runs
+// per CU, so nothing covers its start and end: the first half-step waits only for the Q block
+// (staged through LDS) and the first K tile, and the last tile still goes through a scheduled
+// iteration.  The reference maximum is raised
 // lazily and after the fact: P is formed against the current reference, and only when a
 // lane's row sum of the half-tile exceeds 2^kTau (or is not finite) does the wave take the
 // slow path that finds the true maximum, moves the reference by a whole number of log2
@@ -35,7 +38,12 @@
 // The MFMAs are inline assembly (to pin operands to AGPRs), so the compiler does not know
 // their latency: every place where the VALU reads an MFMA result is either separated from
 // the producer by several later MFMAs of the same in-order stream or preceded by
-// mfma_settle().
+// mfma_settle().  Some loads are inline assembly too (row numbers, LDS fragments), so that
+// their waits can be placed by hand; for those the compiler knows neither the latency nor that
+// the destination is written later.  The rules that keep this sound: such a load is one
+// statement whose output is the whole variable, nothing reads the variable before the wait
+// that covers it, and every such variable is named by a statement behind that wait (which
+// keeps its registers reserved).  tests/test_asm_hazards.py checks the generated code.
 #include <utility>
 
 #include "pulsecol_device.h"
@@ -51,7 +59,7 @@ constexpr int NBUF = 4;            // LDS tile slots for K and for V: tile t liv
                                    // steady loop is unrolled NBUF times so that every slot is an immediate
 constexpr int NBUF_K = NBUF;
 constexpr int NBUF_V = NBUF;
-constexpr int PRO_TILES = 3;       // tiles loaded before the first half-step
+constexpr int PRO_TILES = 3;       // K tiles requested by the prologue (the loop loads tile PRO_TILES first)
 constexpr float kTau = 8.0f;       // log2 of the growth allowed before the reference max is raised
 constexpr float kGrowthLimit = 256.0f;   // 2^kTau
 
