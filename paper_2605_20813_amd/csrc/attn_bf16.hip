@@ -733,6 +733,33 @@ struct AttnWave {
 };
 
 
+// Work distribution.  The grid is a fixed set of workgroups (as many as fit the chip at once)
+// that take query blocks from eight queues, one per XCD: queue y holds the query blocks of the
+// heads 8*hh + y in order, so that at any time an XCD works on one or two heads whose gathered
+// K/V rows fit its L2, and a workgroup takes from the queue of the XCD it runs on (consecutive
+// workgroup ids are dealt round-robin over the XCDs).  The XCDs of one chip do not run at the
+// same speed (a few percent apart under this load): a workgroup whose queue is empty goes on
+// with the next non-empty one instead of idling until the slowest XCD is done.
+// Counters: work[y] = next item of queue y, work[8] = workgroups that have finished.  All are
+// zero when the kernel starts, and the last workgroup to finish zeroes them again.
+struct WorkQueues {
+    int32_t* work;
+    int bh_total, nqb;
+    __device__ __forceinline__ int items(int y) const { return y < bh_total ? ((bh_total - y + 7) >> 3) * nqb : 0; }
+    static __device__ __forceinline__ int take(int32_t* counter) {
+        return __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    // One thread: item j taken from queue q is good, or else the first item that the following
+    // queues still have; j = -1 when every queue has been found empty.
+    __device__ __forceinline__ void settle(int home, int& q, int& j) const {
+        while (j >= items(q)) {
+            q = (q + 1) & 7;
+            if (q == home) { j = -1; return; }
+            j = take(work + q);
+        }
+    }
+};
+
 template <int D, int MODE>
 __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     using W = AttnWave<D, MODE>;
@@ -759,10 +786,23 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     asm volatile("" : : "s"(p.q), "s"(p.k), "s"(p.v), "s"(p.o), "s"(p.idx), "s"(p.lse), "s"(p.lse_base2),
                          "s"(p.td.sb), "s"(p.td.sh), "s"(p.td.sn), "s"(p.td_kv.sb), "s"(p.td_kv.sh), "s"(p.td_kv.sn),
                          "s"(p.kv_heads), "s"(p.batch), "s"(p.heads), "s"(p.n), "s"(p.ns), "s"(p.groups),
-                         "s"(p.group_size), "s"(p.scale));
+                         "s"(p.group_size), "s"(p.scale), "s"(p.work));
     const int nqb = (p.n + BM - 1) / BM;
-    int bh, qblk;
-    if (!xcd_tile(blockIdx.x, nqb, p.batch * p.heads, &bh, &qblk)) return;
+    const WorkQueues queues{p.work, p.batch * p.heads, nqb};
+    __shared__ int32_t lds_item[2];          // the workgroup's next item: queue, index in the queue
+    const int home = blockIdx.x & 7;
+    if (threadIdx.x == 0) {
+        int q = home, j = WorkQueues::take(p.work + home);
+        queues.settle(home, q, j);
+        lds_item[0] = q;
+        lds_item[1] = j;
+    }
+    __syncthreads();
+    int cur_q = __builtin_amdgcn_readfirstlane(lds_item[0]), cur_j = __builtin_amdgcn_readfirstlane(lds_item[1]);
+
+  while (cur_j >= 0) {
+    const int head_block = cur_j / nqb;
+    const int qblk = cur_j - head_block * nqb, bh = head_block * 8 + cur_q;
     const int b = bh / p.heads, h = bh - b * p.heads;
     const int64_t head_off = (int64_t)b * p.td.sb + (int64_t)h * p.td.sh;
     // grouped-query layout: query head h reads K/V head h / (heads / kv_heads)
@@ -925,6 +965,11 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     // It also lets the loads of tiles past the end land before the epilogue reuses the slots.
     asm volatile("s_waitcnt vmcnt(0)" : "+v"(rows_k), "+v"(rows_v), "+v"(rows_n) : : "memory");
     __builtin_amdgcn_s_barrier();
+    // The next item is asked for now: late, so that it is not held back for long from workgroups
+    // that have nothing left to do, and early enough for the answer to be there when the output
+    // tile has been staged (nothing else is in flight in between).
+    int early_j = 0;
+    if (threadIdx.x == 0) early_j = WorkQueues::take(p.work + cur_q);
     w.general_step(nhalf - 1, lds_k, lds_v, SB, SA, PA, PB);
 
     w.pv_all(lds_v + (HAS_V ? (((nhalf - 1) >> 1) % NBUF_V) * TILE_BYTES : 0), (nhalf - 1) & 1, PB);
@@ -937,6 +982,7 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     // after the barrier above, and the loads that were still writing there have landed.
     // (Staging d-block by d-block behind the MFMAs of the next block gains nothing: a read of
     // the accumulator registers waits for the matrix pipe to drain anyway.)
+    int next_j;       // meaningful in wave 0 only
     float l_tot[2];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
@@ -975,19 +1021,61 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
             rows_out[t] = *(const u32x4*)(stage + r * ROW_BYTES + ((lpiece ^ (r & (PIECES - 1))) << 4));
         }
         fence();
+        next_j = __builtin_amdgcn_readfirstlane(early_j);     // in front of the stores: it would wait for them too
+        fence();
 #pragma unroll
         for (int t = 0; t < 64 / RPC; ++t) {
             const int r = t * RPC + lrow;
             if (q0 + r < n) *(u32x4*)(obase + t * group_stride) = rows_out[t];
         }
+    } else {
+        next_j = __builtin_amdgcn_readfirstlane(early_j);
     }
+
+    // ---- next item.  The barrier also separates this item's last LDS reads from the loads that
+    // the next one sends into the same slots.
+    if (threadIdx.x == 0) {
+        int q = cur_q, j = next_j;
+        queues.settle(home, q, j);
+        lds_item[0] = q;
+        lds_item[1] = j;
+    }
+    __syncthreads();
+    cur_q = __builtin_amdgcn_readfirstlane(lds_item[0]);
+    cur_j = __builtin_amdgcn_readfirstlane(lds_item[1]);
+  }
+
+    // ---- the last workgroup to get here leaves the counters as it found them
+    if (threadIdx.x == 0) {
+        const int done = __hip_atomic_fetch_add(p.work + 8, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        if (done == (int)gridDim.x - 1) {
+#pragma unroll
+            for (int y = 0; y <= 8; ++y) __hip_atomic_store(p.work + y, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+// workgroups that one CU holds at a time (LDS and registers): the row pass fits two
+template <int MODE> constexpr int wg_per_cu() { return MODE == kLseOnly ? 2 : 1; }
+
+int compute_units() {
+    static int cached[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        cached[dev] = (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) ? n : 256;
+    }
+    return cached[dev];
 }
 
 template <int D, int MODE>
 hipError_t launch(const AttnParams& p, hipStream_t s) {
-    const int nqb = (p.n + BM - 1) / BM;
-    const int bh_pad = (p.batch * p.heads + 7) / 8 * 8;
-    hipLaunchKernelGGL((attn_bf16_kernel<D, MODE>), dim3(nqb * bh_pad), dim3(NTHREADS), 0, s, p);
+    if (p.work == nullptr) return hipErrorInvalidValue;
+    const int64_t items = (int64_t)((p.n + BM - 1) / BM) * p.batch * p.heads;
+    const int64_t resident = (int64_t)compute_units() * wg_per_cu<MODE>();
+    const int grid = (int)(items < resident ? items : resident);
+    hipLaunchKernelGGL((attn_bf16_kernel<D, MODE>), dim3(grid), dim3(NTHREADS), 0, s, p);
     return hipGetLastError();
 }
 

@@ -26,7 +26,8 @@ struct pulsecol_ctx {
     float* scores = nullptr;        // [B*H*U, n]
     int32_t* cached_idx = nullptr;  // [B*H*U, cached_k]
     int32_t cached_k = 0;           // 0 = nothing cached
-    int32_t* bad_count = nullptr;   // one device counter for the validation mode
+    int32_t* bad_count = nullptr;   // one device counter for the validation mode (first word of a small block)
+    int32_t* work = nullptr;        // work counters of the bf16 attention kernels (same block), zero between launches
     bool validate = false;          // check column numbers in front of every pulsecol_attn
     std::string last_error;
 };
@@ -127,6 +128,7 @@ pulsecol::AttnParams attn_params(const pulsecol_ctx* c, const void* Q, const voi
     p.batch = c->shape.batch; p.heads = c->shape.heads; p.n = c->shape.seq; p.ns = ns;
     p.groups = c->groups; p.group_size = c->shape.group_size;
     p.scale = c->scale;
+    p.work = c->work;
     return p;
 }
 
@@ -243,11 +245,15 @@ pulsecol_status pulsecol_create(pulsecol_ctx** out, const pulsecol_shape* shape,
     hipError_t e1 = hipMalloc((void**)&c->lse, rows * row_bytes);
     hipError_t e2 = e1 == hipSuccess ? hipMalloc((void**)&c->scores, rows * c->groups * row_bytes) : e1;
     hipError_t e3 = e2 == hipSuccess ? hipMalloc((void**)&c->cached_idx, rows * c->groups * row_bytes) : e2;
+    static_assert(64 + pulsecol::kWorkCounters * sizeof(int32_t) <= 256, "counter block");
     if (e3 == hipSuccess) e3 = hipMalloc((void**)&c->bad_count, 256);
+    if (e3 == hipSuccess) e3 = hipMemset(c->bad_count, 0, 256);
+    if (e3 == hipSuccess) c->work = c->bad_count + 16;
     if (e3 != hipSuccess) {
         if (c->lse) (void)hipFree(c->lse);
         if (c->scores) (void)hipFree(c->scores);
         if (c->cached_idx) (void)hipFree(c->cached_idx);
+        if (c->bad_count) (void)hipFree(c->bad_count);
         (void)hipGetLastError();
         delete c;
         return e3 == hipErrorOutOfMemory ? fail(nullptr, PULSECOL_ERR_OOM, "pulsecol_create: scratch allocation failed")

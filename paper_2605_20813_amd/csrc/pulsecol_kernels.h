@@ -25,7 +25,12 @@ struct AttnParams {
     int32_t groups;          // U query groups per head (1 = the whole head)
     int32_t group_size;      // rows per group, a multiple of the kernel's query block (unused when U = 1)
     float scale;             // logit scale
+    // bf16 kernel with 256-row query blocks only: kWorkCounters ints of device memory, all zero between
+    // launches (the kernel leaves them so), through which its workgroups hand out the query blocks
+    int32_t* work;
 };
+
+constexpr int kWorkCounters = 16;
 
 struct ScoreParams {
     const void* q;
