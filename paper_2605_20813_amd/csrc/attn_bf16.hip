@@ -272,7 +272,9 @@ struct AttnWave {
         const int e = first_entry(p0) + p % CH;
         return e >= p0 && e < ns;
     }
-    __device__ __forceinline__ void load_rows(int t, rows_t& dst) const {
+    __device__ __forceinline__ void load_rows(int t, rows_t& dst) const { load_rows(idx, t, dst); }
+    // ... from the pattern `idx` (the set of another query block than the running one)
+    __device__ __forceinline__ void load_rows(const byte* idx, int t, rows_t& dst) const {
         static_assert(CH * ROWS_PER_CHUNK == 16, "a wave fills 16 rows of a tile");
         t = t < ntiles ? t : ntiles - 1;          // past the end: repeat the last tile (never read back)
         const int e0 = first_entry(t * BN + wave * 16 + lrow * CH);
@@ -772,12 +774,10 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     // ONE shared array for all tile slots: with a single LDS object the alias scopes that the
     // restrict parameters give the direct-to-LDS loads are what the compiler's wait-count
     // insertion sees, and LDS reads of one slot do not wait for loads into another.
-    // Behind them, room for the Q block, which is turned around in LDS at the start: a wave's 64 Q
-    // rows are one tile's worth of bytes, and with V slots three of the waves borrow the tile slots
-    // that the prologue leaves empty (K slot 3, V slots 2 and 3).
-    // (The row pass keeps its LDS small enough for two workgroups per CU and loads Q directly.)
-    constexpr int QSTAGE_TILES = HAS_V ? 1 : 0;
-    __shared__ __attribute__((aligned(1024))) byte lds_all[(NBUF_K + (HAS_V ? NBUF_V : 0) + QSTAGE_TILES) * TILE_BYTES];
+    // The Q block is turned around in LDS at the start of a query block: a wave's 64 Q rows are one
+    // tile's worth of bytes and go through V slot `wave`, which is not needed yet at that point.
+    // (The row pass has no V slots; it loads its Q fragments directly.)
+    __shared__ __attribute__((aligned(1024))) byte lds_all[(NBUF_K + (HAS_V ? NBUF_V : 0)) * TILE_BYTES];
     byte* const lds_k = lds_all;
     byte* const lds_v = lds_all + (HAS_V ? NBUF_K * TILE_BYTES : 0);
 
@@ -800,15 +800,70 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     __syncthreads();
     int cur_q = __builtin_amdgcn_readfirstlane(lds_item[0]), cur_j = __builtin_amdgcn_readfirstlane(lds_item[1]);
 
-  while (cur_j >= 0) {
-    const int head_block = cur_j / nqb;
-    const int qblk = cur_j - head_block * nqb, bh = head_block * 8 + cur_q;
-    const int b = bh / p.heads, h = bh - b * p.heads;
-    const int64_t head_off = (int64_t)b * p.td.sb + (int64_t)h * p.td.sh;
-    // grouped-query layout: query head h reads K/V head h / (heads / kv_heads)
-    const int64_t kv_off = (int64_t)b * p.td_kv.sb + (int64_t)(h / (p.heads / p.kv_heads)) * p.td_kv.sh;
-    const __bf16* __restrict__ Q = (const __bf16*)p.q + head_off;
+    // the geometry that requesting a query block's first loads needs
+    W wq;
+    wq.lane = threadIdx.x & 63;
+    wq.wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    wq.ns = p.ns;
+    wq.ntiles = (p.ns + BN - 1) / BN;
+    wq.lrow = wq.lane / W::PIECES;
+    wq.idx = nullptr;
+    const int n = p.n;
+    // item (queue, index) -> head and query block; pointers of a head
+    auto decode = [&](int q, int j, int& bh, int& qblk) {
+        const int head_block = j / nqb;
+        qblk = j - head_block * nqb;
+        bh = head_block * 8 + q;
+    };
+    auto q_of = [&](int bh) {
+        const int b = bh / p.heads, h = bh - b * p.heads;
+        return (int64_t)b * p.td.sb + (int64_t)h * p.td.sh;
+    };
+    // the column set of a query block's group (Sec. 3.3: one set per query group)
+    auto pattern_of = [&](int bh, int qblk) -> const byte* {
+        const int group = p.groups > 1 ? (qblk * BM) / p.group_size : 0;
+        return W::GATHER ? (const byte*)(p.idx + ((int64_t)bh * p.groups + group) * p.ns) : nullptr;
+    };
 
+    // What a query block needs first, requested ahead of its turn (for the first one: now; for
+    // the others: from the epilogue of the block before, once no wave reads the V slots any more):
+    // the row numbers of tiles 0..3 and the Q block.  Q is loaded like a K tile -- whole rows
+    // straight into LDS, 16 lanes per row, swizzled on the global side -- and read back as
+    // B-operand fragments [query lq][d = kk*16 + 8*lh .. +7].  (A direct load of a fragment
+    // touches 32 rows x 32 bytes, four instructions per 128-byte line, and the block does not
+    // fit the vector cache.)  Each wave stages its own 64 rows.
+    typename W::rows_t rows_k, rows_v, rows_n, rows_0, rows_1;
+    static_assert(PRO_TILES == 3, "the prologue is written out for three tiles");
+    auto request = [&](int q, int j) {
+        int bh, qblk;
+        decode(q, j, bh, qblk);
+        const byte* const pattern = pattern_of(bh, qblk);
+        wq.load_rows(pattern, 0, rows_0);
+        wq.load_rows(pattern, 1, rows_1);
+        wq.load_rows(pattern, 2, rows_v);
+        wq.load_rows(pattern, 3, rows_k);
+        if constexpr (HAS_V) {
+            constexpr int RPC = W::ROWS_PER_CHUNK, PIECES = W::PIECES;
+            const byte* const Qb = (const byte*)((const __bf16*)p.q + q_of(bh));
+            const int q0 = qblk * BM + wq.wave * 64;
+            const int lrow = wq.lane / PIECES, lpiece = wq.lane % PIECES;
+            byte* const qstage = lds_v + wq.wave * TILE_BYTES;
+#pragma unroll
+            for (int t = 0; t < TILE_BYTES / 1024; ++t) {
+                const int r = t * RPC + lrow;
+                int row = q0 + r;
+                row = row < n ? row : n - 1;
+                const byte* src = Qb + ((int64_t)row * p.td.sn * 2 + ((lpiece ^ swizzle_k<PIECES>(r)) << 4));
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                                 (PULSECOL_LDS void*)(qstage + t * 1024), 16, 0, 0);
+            }
+        }
+    };
+    if (cur_j >= 0) request(cur_q, cur_j);
+
+  while (cur_j >= 0) {
+    int bh, qblk;
+    decode(cur_q, cur_j, bh, qblk);
     W w;
     const int tid = threadIdx.x;
     w.lane = tid & 63;
@@ -822,50 +877,31 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     w.ragged = (p.ns & (BN - 1)) != 0;
     w.row_bytes = (uint32_t)p.td_kv.sn * 2u;
     w.wave_lds = __builtin_amdgcn_readfirstlane(lds_address(lds_k) + w.wave * CH * 1024);
+    w.idx = nullptr;
+    w.c2 = p.scale * kLog2e;                 // exp(z*scale) = exp2(z*c2)
+    w.init_addresses();
+    const int nhalf = w.nhalf;
+    byte* const qstage = lds_v + w.wave * TILE_BYTES;      // HAS_V only
+
+    const int b = bh / p.heads, h = bh - b * p.heads;
+    const int64_t head_off = q_of(bh);
+    // grouped-query layout: query head h reads K/V head h / (heads / kv_heads)
+    const int64_t kv_off = (int64_t)b * p.td_kv.sb + (int64_t)(h / (p.heads / p.kv_heads)) * p.td_kv.sh;
+    const __bf16* __restrict__ Q = (const __bf16*)p.q + head_off;
     w.K = (const byte*)((const __bf16*)p.k + kv_off);
     w.V = HAS_V ? (const byte*)((const __bf16*)p.v + kv_off) : nullptr;
-    // the column set of this query block's group (Sec. 3.3: one set per query group)
-    const int group = p.groups > 1 ? (qblk * BM) / p.group_size : 0;
-    w.idx = W::GATHER ? (const byte*)(p.idx + ((int64_t)bh * p.groups + group) * p.ns) : nullptr;
-    w.c2 = p.scale * kLog2e;                 // exp(z*scale) = exp2(z*c2)
+    w.idx = pattern_of(bh, qblk);
     w.mc[0] = w.mc[1] = -INFINITY;
     w.l_run[0] = w.l_run[1] = 0.f;
-    w.init_addresses();
-    const int n = p.n, nhalf = w.nhalf;
+    const int q0 = qblk * BM + w.wave * 64;
 
     // ---- prologue.  The vector memory pipe returns loads in issue order, so each wait names how
     // many of the youngest loads may still be in flight:
-    //   row numbers of tiles 0..3, Q, K(0)  -> everything has landed         -> S(0), S(1)
+    //   (requested ahead: row numbers of tiles 0..3, Q), K(0)  -> everything has landed -> S(0), S(1)
     //   V(0), K(1), V(1), K(2)              -> the last two may be in flight -> first iteration
     //                                       -> its own barrier covers V(1), K(2)
     // (V(2) is loaded by the first iteration itself.)  Afterwards rows_v = tile 2, rows_k = tile 3.
-    typename W::rows_t rows_k, rows_v, rows_n, rows_0, rows_1;
-    static_assert(PRO_TILES == 3, "the prologue is written out for three tiles");
-    w.load_rows(0, rows_0);
-    w.load_rows(1, rows_1);
-    w.load_rows(2, rows_v);
-    w.load_rows(3, rows_k);
-
-    // Q block: loaded like a K tile -- whole rows straight into LDS, 16 lanes per row, swizzled on
-    // the global side -- and read back as B-operand fragments [query lq][d = kk*16 + 8*lh .. +7].
-    // (A direct load of a fragment touches 32 rows x 32 bytes, four instructions per 128-byte line,
-    // and the block does not fit the vector cache.)  Each wave stages its own 64 rows.
-    const int q0 = qblk * BM + w.wave * 64;
-    const int qstage_tile = w.wave == 0 ? PRO_TILES : w.wave == 3 ? NBUF_K + NBUF_V : NBUF_K + 1 + w.wave;
-    byte* const qstage = lds_all + qstage_tile * TILE_BYTES;
-    if constexpr (HAS_V) {
-        constexpr int RPC = W::ROWS_PER_CHUNK, PIECES = W::PIECES;
-        const int lrow = w.lane / PIECES, lpiece = w.lane % PIECES;
-#pragma unroll
-        for (int t = 0; t < TILE_BYTES / 1024; ++t) {
-            const int r = t * RPC + lrow;
-            int row = q0 + r;
-            row = row < n ? row : n - 1;
-            const byte* src = (const byte*)Q + ((int64_t)row * p.td.sn * 2 + ((lpiece ^ swizzle_k<PIECES>(r)) << 4));
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                             (PULSECOL_LDS void*)(qstage + t * 1024), 16, 0, 0);
-        }
-    } else {
+    if constexpr (!HAS_V) {
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
             int row = q0 + qb * 32 + w.lq;
@@ -982,7 +1018,6 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     // after the barrier above, and the loads that were still writing there have landed.
     // (Staging d-block by d-block behind the MFMAs of the next block gains nothing: a read of
     // the accumulator registers waits for the matrix pipe to drain anyway.)
-    int next_j;       // meaningful in wave 0 only
     float l_tot[2];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
@@ -991,6 +1026,11 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
         if (p.lse != nullptr && w.lh == 0 && row < n)
             p.lse[(int64_t)bh * n + row] = (w.mc[qb] + fast_log2(l_tot[qb])) * (p.lse_base2 ? 1.0f : kLn2);
     }
+    constexpr int OUT_GROUPS = 64 / W::ROWS_PER_CHUNK;
+    const int out_lrow = w.lane / W::PIECES, out_lpiece = w.lane % W::PIECES;
+    byte* const obase = (byte*)((__bf16*)p.o + head_off) + (int64_t)(q0 + out_lrow) * p.td.sn * 2 + out_lpiece * 16;
+    const int64_t group_stride = (int64_t)W::ROWS_PER_CHUNK * p.td.sn * 2;      // bytes between row groups (uniform)
+    u32x4 rows_out[OUT_GROUPS];
     if constexpr (HAS_V) {
         constexpr int PIECES = W::PIECES, ROW_BYTES = W::ROW_BYTES, RPC = W::ROWS_PER_CHUNK;
         static_assert(4 * 64 * ROW_BYTES <= NBUF_K * TILE_BYTES, "the staging area lies inside the K slots");
@@ -1010,30 +1050,19 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
                     *(bf16x4*)(stage + r * ROW_BYTES + (((db * 4 + r4) ^ (r & (PIECES - 1))) << 4) + 8 * w.lh) = o4;
                 }
         }
-        const int lrow = w.lane / PIECES, lpiece = w.lane % PIECES;
-        byte* const obase = (byte*)((__bf16*)p.o + head_off) + (int64_t)(q0 + lrow) * p.td.sn * 2 + lpiece * 16;
-        const int64_t group_stride = (int64_t)RPC * p.td.sn * 2;      // bytes between row groups (uniform)
-        // all reads first, then the stores: one LDS round trip instead of one per row group
-        u32x4 rows_out[64 / RPC];
+        // all reads first, then (further down) the stores: one LDS round trip instead of one per row group
 #pragma unroll
-        for (int t = 0; t < 64 / RPC; ++t) {
-            const int r = t * RPC + lrow;
-            rows_out[t] = *(const u32x4*)(stage + r * ROW_BYTES + ((lpiece ^ (r & (PIECES - 1))) << 4));
+        for (int t = 0; t < OUT_GROUPS; ++t) {
+            const int r = t * RPC + out_lrow;
+            rows_out[t] = *(const u32x4*)(stage + r * ROW_BYTES + ((out_lpiece ^ (r & (PIECES - 1))) << 4));
         }
         fence();
-        next_j = __builtin_amdgcn_readfirstlane(early_j);     // in front of the stores: it would wait for them too
-        fence();
-#pragma unroll
-        for (int t = 0; t < 64 / RPC; ++t) {
-            const int r = t * RPC + lrow;
-            if (q0 + r < n) *(u32x4*)(obase + t * group_stride) = rows_out[t];
-        }
-    } else {
-        next_j = __builtin_amdgcn_readfirstlane(early_j);
     }
 
-    // ---- next item.  The barrier also separates this item's last LDS reads from the loads that
-    // the next one sends into the same slots.
+    // ---- next item.  Behind the barrier no wave reads this block's tiles or staging area any
+    // more, so the next block's first loads can go out now, ahead of this block's stores.
+    // (The taken index is read in front of the stores: its wait would cover them too.)
+    const int next_j = __builtin_amdgcn_readfirstlane(early_j);       // meaningful in wave 0 only
     if (threadIdx.x == 0) {
         int q = cur_q, j = next_j;
         queues.settle(home, q, j);
@@ -1043,6 +1072,15 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     __syncthreads();
     cur_q = __builtin_amdgcn_readfirstlane(lds_item[0]);
     cur_j = __builtin_amdgcn_readfirstlane(lds_item[1]);
+    if (cur_j >= 0) request(cur_q, cur_j);
+    if constexpr (HAS_V) {
+        fence();
+#pragma unroll
+        for (int t = 0; t < OUT_GROUPS; ++t) {
+            const int r = t * W::ROWS_PER_CHUNK + out_lrow;
+            if (q0 + r < n) *(u32x4*)(obase + t * group_stride) = rows_out[t];
+        }
+    }
   }
 
     // ---- the last workgroup to get here leaves the counters as it found them
