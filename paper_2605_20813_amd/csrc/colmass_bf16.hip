@@ -75,11 +75,13 @@ __global__ void __launch_bounds__(NTHREADS) colmass_bf16_kernel(ScoreParams p) {
     }
     const int64_t tile_stride = (int64_t)QT * p.td.sn;
     const float* lse_src = lse + (tid < QT ? tid : 0);
+    // (tiles are fetched in order: the pointers move on by one tile per call)
     auto fetch = [&](int t) {
         if (__builtin_expect((t + 1) * QT <= n, 1)) {
 #pragma unroll
-            for (int j = 0; j < CH; ++j) stage[j] = *(const u32x4*)(qsrc[j] + t * tile_stride);
-            if (tid < QT) stage_lse = lse_src[t * QT];
+            for (int j = 0; j < CH; ++j) { stage[j] = *(const u32x4*)qsrc[j]; qsrc[j] += tile_stride; }
+            if (tid < QT) stage_lse = *lse_src;
+            lse_src += QT;
         } else {
 #pragma unroll
             for (int j = 0; j < CH; ++j) {
