@@ -345,3 +345,37 @@ def test_validation_mode_rejects_out_of_range_columns():
         ctx.set_validation(False)
         assert torch.equal(ctx.attn(Q, K, V, good), want)
         torch.cuda.synchronize()
+
+
+# ---------------------------------------------------------------------------------------
+# work distribution of the bf16 attention kernels
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("B,H,n,k", [(1, 1, 1300, 333), (1, 5, 2100, 257), (2, 13, 700, 64), (1, 32, 1024, 128)])
+def test_query_block_queues_hand_out_every_block_once(B, H, n, k):
+    """The kernels' workgroups take query blocks from per-XCD queues (and from other queues once
+    theirs is empty) and leave the counters at zero.  Fewer heads than queues, head counts that
+    are no multiple of eight, more blocks than workgroups: every query row must come out, the
+    same on every launch, with two contexts taking turns."""
+    say(f"queue case B={B} H={H} n={n} k={k}")
+    d = 128
+    Q, K, V = rand_qkv(B, H, n, d, torch.bfloat16, seed=9000 + H * n)
+    idx = random_idx(n, k, B * H, seed=77 + H).view(B, H, 1, k)
+    q, k_, v, ix = Q.to(DEV), K.to(DEV), V.to(DEV), idx.to(DEV)
+    with pc.Context(B, H, n, d, torch.bfloat16) as c1, pc.Context(B, H, n, d, torch.bfloat16) as c2:
+        outs = []
+        for rep in range(6):
+            ctx = c1 if rep % 2 == 0 else c2
+            O = torch.full((B, H, n, d), float("nan"), dtype=torch.bfloat16, device=DEV)
+            ctx.attn(q, k_, v, ix, O)
+            outs.append(O)
+            if rep == 2:
+                ctx.attn_dense(q, k_, v)                 # another kernel of the same family in between
+                ctx.scores(q, k_)                        # and the row pass (two workgroups per CU)
+        torch.cuda.synchronize()
+    for O in outs:
+        assert not torch.isnan(O.float()).any()          # no block left out
+        assert torch.equal(O, outs[0])
+    for b in range(B):
+        for h in range(0, H, max(1, H // 3)):
+            want = oracle.sparse_attention_masked(f64(Q[b, h]), f64(K[b, h]), f64(V[b, h]), idx[b, h].numpy())
+            assert_close(outs[-1][b, h], want, "bf16", f"queues b{b} h{h}")
