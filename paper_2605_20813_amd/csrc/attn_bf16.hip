@@ -777,7 +777,9 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     // The Q block is turned around in LDS at the start of a query block: a wave's 64 Q rows are one
     // tile's worth of bytes and go through V slot `wave`, which is not needed yet at that point.
     // (The row pass has no V slots; it loads its Q fragments directly.)
-    __shared__ __attribute__((aligned(1024))) byte lds_all[(NBUF_K + (HAS_V ? NBUF_V : 0)) * TILE_BYTES];
+    // One more tile behind them is wave 0's share of the output staging area (the other waves use
+    // K slots 1..3): K slot 0 then is free for the next query block's first tile at once.
+    __shared__ __attribute__((aligned(1024))) byte lds_all[(NBUF_K + (HAS_V ? NBUF_V + 1 : 0)) * TILE_BYTES];
     byte* const lds_k = lds_all;
     byte* const lds_v = lds_all + (HAS_V ? NBUF_K * TILE_BYTES : 0);
 
@@ -834,7 +836,10 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     // fit the vector cache.)  Each wave stages its own 64 rows.
     typename W::rows_t rows_k, rows_v, rows_n, rows_0, rows_1;
     static_assert(PRO_TILES == 3, "the prologue is written out for three tiles");
-    auto request = [&](int q, int j) {
+    constexpr int Q_LOADS = HAS_V ? TILE_BYTES / 1024 : 0;        // direct-to-LDS loads of a wave's share of Q
+    const byte* req_q = nullptr;          // the requested block's head of Q, and its first row for this wave
+    int req_q0 = 0;
+    auto request_rows = [&](int q, int j) {
         int bh, qblk;
         decode(q, j, bh, qblk);
         const byte* const pattern = pattern_of(bh, qblk);
@@ -842,24 +847,26 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
         wq.load_rows(pattern, 1, rows_1);
         wq.load_rows(pattern, 2, rows_v);
         wq.load_rows(pattern, 3, rows_k);
+        req_q = (const byte*)((const __bf16*)p.q + q_of(bh));
+        req_q0 = qblk * BM + wq.wave * 64;
+    };
+    auto request_q = [&](int t0, int t1) {        // loads t0 .. t1-1 of the Q_LOADS
         if constexpr (HAS_V) {
             constexpr int RPC = W::ROWS_PER_CHUNK, PIECES = W::PIECES;
-            const byte* const Qb = (const byte*)((const __bf16*)p.q + q_of(bh));
-            const int q0 = qblk * BM + wq.wave * 64;
             const int lrow = wq.lane / PIECES, lpiece = wq.lane % PIECES;
             byte* const qstage = lds_v + wq.wave * TILE_BYTES;
 #pragma unroll
-            for (int t = 0; t < TILE_BYTES / 1024; ++t) {
+            for (int t = t0; t < t1; ++t) {
                 const int r = t * RPC + lrow;
-                int row = q0 + r;
+                int row = req_q0 + r;
                 row = row < n ? row : n - 1;
-                const byte* src = Qb + ((int64_t)row * p.td.sn * 2 + ((lpiece ^ swizzle_k<PIECES>(r)) << 4));
+                const byte* src = req_q + ((int64_t)row * p.td.sn * 2 + ((lpiece ^ swizzle_k<PIECES>(r)) << 4));
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                                  (PULSECOL_LDS void*)(qstage + t * 1024), 16, 0, 0);
             }
         }
     };
-    if (cur_j >= 0) request(cur_q, cur_j);
+    if (cur_j >= 0) { request_rows(cur_q, cur_j); request_q(0, Q_LOADS); }
 
   while (cur_j >= 0) {
     int bh, qblk;
@@ -1010,14 +1017,13 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
 
     w.pv_all(lds_v + (HAS_V ? (((nhalf - 1) >> 1) % NBUF_V) * TILE_BYTES : 0), (nhalf - 1) & 1, PB);
 
-    // ---- epilogue: O = diag(l)^-1 acc, optional row log-sum-exp.
+    // ---- epilogue: O = diag(l)^-1 acc, optional row log-sum-exp; hand-over to the next item.
     // In the accumulator a lane holds one query row in 8-byte runs: stored directly, every
     // instruction would touch 64 different rows.  Each wave turns its 64 x D tile around in
     // its own piece of LDS (16-byte pieces XOR-swizzled by row against bank conflicts) and
-    // writes whole rows, 16 bytes per lane.  The staging area is the K slots: no wave reads K
-    // after the barrier above, and the loads that were still writing there have landed.
-    // (Staging d-block by d-block behind the MFMAs of the next block gains nothing: a read of
-    // the accumulator registers waits for the matrix pipe to drain anyway.)
+    // writes whole rows, 16 bytes per lane.  The staging area is K slots 1..3 and the spare tile:
+    // no wave reads K after the barrier above, and the loads that were still writing there have
+    // landed.
     float l_tot[2];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
@@ -1030,38 +1036,13 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     const int out_lrow = w.lane / W::PIECES, out_lpiece = w.lane % W::PIECES;
     byte* const obase = (byte*)((__bf16*)p.o + head_off) + (int64_t)(q0 + out_lrow) * p.td.sn * 2 + out_lpiece * 16;
     const int64_t group_stride = (int64_t)W::ROWS_PER_CHUNK * p.td.sn * 2;      // bytes between row groups (uniform)
-    u32x4 rows_out[OUT_GROUPS];
-    if constexpr (HAS_V) {
-        constexpr int PIECES = W::PIECES, ROW_BYTES = W::ROW_BYTES, RPC = W::ROWS_PER_CHUNK;
-        static_assert(4 * 64 * ROW_BYTES <= NBUF_K * TILE_BYTES, "the staging area lies inside the K slots");
-        mfma_settle_acc(w.o_acc);
-        byte* const stage = lds_all + w.wave * 64 * ROW_BYTES;
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-            const float inv = 1.0f / l_tot[qb];
-            const int r = qb * 32 + w.lq;
-#pragma unroll
-            for (int db = 0; db < ODB; ++db)
-#pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    bf16x4 o4;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(w.o_acc[qb][db][r4 * 4 + e] * inv);
-                    *(bf16x4*)(stage + r * ROW_BYTES + (((db * 4 + r4) ^ (r & (PIECES - 1))) << 4) + 8 * w.lh) = o4;
-                }
-        }
-        // all reads first, then (further down) the stores: one LDS round trip instead of one per row group
-#pragma unroll
-        for (int t = 0; t < OUT_GROUPS; ++t) {
-            const int r = t * RPC + out_lrow;
-            rows_out[t] = *(const u32x4*)(stage + r * ROW_BYTES + ((out_lpiece ^ (r & (PIECES - 1))) << 4));
-        }
-        fence();
-    }
 
-    // ---- next item.  Behind the barrier no wave reads this block's tiles or staging area any
-    // more, so the next block's first loads can go out now, ahead of this block's stores.
-    // (The taken index is read in front of the stores: its wait would cover them too.)
+    // The next item.  Behind this barrier every wave has issued its last P V product, so no wave
+    // reads the V slots any more and the next block's Q copy may land there; its first loads go
+    // out now, spread over the staging of this block's output (the copy comes from memory and
+    // holds the wave at every instruction while the memory pipe is full), and ahead of this
+    // block's stores.  (The taken index is read in front of every store: its wait would cover
+    // them too.)
     const int next_j = __builtin_amdgcn_readfirstlane(early_j);       // meaningful in wave 0 only
     if (threadIdx.x == 0) {
         int q = cur_q, j = next_j;
@@ -1072,12 +1053,41 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     __syncthreads();
     cur_q = __builtin_amdgcn_readfirstlane(lds_item[0]);
     cur_j = __builtin_amdgcn_readfirstlane(lds_item[1]);
-    if (cur_j >= 0) request(cur_q, cur_j);
+    const bool more = cur_j >= 0;
+    if (more) request_rows(cur_q, cur_j);
     if constexpr (HAS_V) {
+        constexpr int PIECES = W::PIECES, ROW_BYTES = W::ROW_BYTES, RPC = W::ROWS_PER_CHUNK;
+        static_assert(64 * ROW_BYTES <= TILE_BYTES && Q_LOADS % ODB == 0, "a wave's output tile fits one tile slot");
+        mfma_settle_acc(w.o_acc);
+        byte* const stage = lds_all + (w.wave == 0 ? NBUF_K + NBUF_V : w.wave) * TILE_BYTES;
+        const float inv[2] = {1.0f / l_tot[0], 1.0f / l_tot[1]};
+#pragma unroll
+        for (int db = 0; db < ODB; ++db) {
+            if (more) request_q(db * (Q_LOADS / ODB), (db + 1) * (Q_LOADS / ODB));
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
+                const int r = qb * 32 + w.lq;
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    bf16x4 o4;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(w.o_acc[qb][db][r4 * 4 + e] * inv[qb]);
+                    *(bf16x4*)(stage + r * ROW_BYTES + (((db * 4 + r4) ^ (r & (PIECES - 1))) << 4) + 8 * w.lh) = o4;
+                }
+            }
+            fence();
+        }
+        // all reads first, then the stores: one LDS round trip instead of one per row group
+        u32x4 rows_out[OUT_GROUPS];
+#pragma unroll
+        for (int t = 0; t < OUT_GROUPS; ++t) {
+            const int r = t * RPC + out_lrow;
+            rows_out[t] = *(const u32x4*)(stage + r * ROW_BYTES + ((out_lpiece ^ (r & (PIECES - 1))) << 4));
+        }
         fence();
 #pragma unroll
         for (int t = 0; t < OUT_GROUPS; ++t) {
-            const int r = t * W::ROWS_PER_CHUNK + out_lrow;
+            const int r = t * RPC + out_lrow;
             if (q0 + r < n) *(u32x4*)(obase + t * group_stride) = rows_out[t];
         }
     }
