@@ -850,23 +850,48 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
         req_q = (const byte*)((const __bf16*)p.q + q_of(bh));
         req_q0 = qblk * BM + wq.wave * 64;
     };
-    auto request_q = [&](int t0, int t1) {        // loads t0 .. t1-1 of the Q_LOADS
+    // The copy itself, loads t0 .. t1-1 of the wave's Q_LOADS: assembly like the gathers of the
+    // steady loop (one LDS base in m0 per four loads, told apart by the instruction offset, which
+    // the hardware adds on both sides; 24-bit multiply-add for the row offset).  The compiler does
+    // not see these loads: the wait in front of the fragment reads is the prologue's own.
+    const uint32_t q_row_bytes = (uint32_t)p.td.sn * 2u;
+    const uint32_t qstage_lds = __builtin_amdgcn_readfirstlane(lds_address(lds_v) + wq.wave * TILE_BYTES);
+    uint32_t q_piece[4];                  // byte offset of this lane's piece inside a Q row, per load of a group
+    {
+        constexpr int RPC = W::ROWS_PER_CHUNK, PIECES = W::PIECES;
+        const int lrow = wq.lane / PIECES, lpiece = wq.lane % PIECES;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) q_piece[jj] = (uint32_t)((lpiece ^ swizzle_k<PIECES>(jj * RPC + lrow)) << 4);
+        static_assert((4 * RPC) % PIECES == 0, "the swizzle of a row repeats every four loads");
+    }
+    auto request_q = [&](auto t0_c, auto t1_c) {
         if constexpr (HAS_V) {
-            constexpr int RPC = W::ROWS_PER_CHUNK, PIECES = W::PIECES;
-            const int lrow = wq.lane / PIECES, lpiece = wq.lane % PIECES;
-            byte* const qstage = lds_v + wq.wave * TILE_BYTES;
+            constexpr int t0 = decltype(t0_c)::value, t1 = decltype(t1_c)::value;
+            static_assert(t0 % 4 == 0 && t1 % 4 == 0, "whole groups of four loads");
+            constexpr int RPC = W::ROWS_PER_CHUNK;
+            const int row0 = req_q0 + wq.lane / W::PIECES;
 #pragma unroll
             for (int t = t0; t < t1; ++t) {
-                const int r = t * RPC + lrow;
-                int row = req_q0 + r;
+                int row = row0 + t * RPC;
                 row = row < n ? row : n - 1;
-                const byte* src = req_q + ((int64_t)row * p.td.sn * 2 + ((lpiece ^ swizzle_k<PIECES>(r)) << 4));
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                                 (PULSECOL_LDS void*)(qstage + t * 1024), 16, 0, 0);
+                uint32_t off;
+                if (t % 4 == 0) {
+                    asm volatile("s_add_i32 m0, %1, %2\n\tv_mad_u32_u24 %0, %3, %4, %5"
+                                 : "=v"(off) : "s"(qstage_lds), "s"((uint32_t)(t * 1024)), "v"(row), "s"(q_row_bytes), "v"(q_piece[0]));
+                } else {
+                    asm volatile("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(off) : "v"(row), "s"(q_row_bytes), "v"(q_piece[t % 4]));
+                }
+                switch (t % 4) {
+                    case 0: asm volatile("global_load_lds_dwordx4 %0, %1 offset:0" : : "v"(off), "s"(req_q) : "memory"); break;
+                    case 1: asm volatile("global_load_lds_dwordx4 %0, %1 offset:1024" : : "v"(off), "s"(req_q - 1024) : "memory"); break;
+                    case 2: asm volatile("global_load_lds_dwordx4 %0, %1 offset:2048" : : "v"(off), "s"(req_q - 2048) : "memory"); break;
+                    default: asm volatile("global_load_lds_dwordx4 %0, %1 offset:3072" : : "v"(off), "s"(req_q - 3072) : "memory"); break;
+                }
             }
         }
     };
-    if (cur_j >= 0) { request_rows(cur_q, cur_j); request_q(0, Q_LOADS); }
+    auto request_q_all = [&] { request_q(std::integral_constant<int, 0>{}, std::integral_constant<int, Q_LOADS>{}); };
+    if (cur_j >= 0) { request_rows(cur_q, cur_j); request_q_all(); }
 
   while (cur_j >= 0) {
     int bh, qblk;
@@ -929,6 +954,7 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
             asm volatile("" : "+a"(w.o_acc[qb][db]));
         }
     wait_vmcnt_at_most<0>();
+    fence();                        // the compiler does not know that the Q copy wrote what is read next
     if constexpr (HAS_V) {          // all fragment reads, then one wait
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb)
@@ -1061,9 +1087,10 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
         mfma_settle_acc(w.o_acc);
         byte* const stage = lds_all + (w.wave == 0 ? NBUF_K + NBUF_V : w.wave) * TILE_BYTES;
         const float inv[2] = {1.0f / l_tot[0], 1.0f / l_tot[1]};
-#pragma unroll
-        for (int db = 0; db < ODB; ++db) {
-            if (more) request_q(db * (Q_LOADS / ODB), (db + 1) * (Q_LOADS / ODB));
+        static_assert((Q_LOADS / ODB) % 4 == 0, "whole groups of four loads per d-block");
+        const auto stage_db = [&](auto db_c) {
+            constexpr int db = decltype(db_c)::value;
+            if (more) request_q(std::integral_constant<int, db * (Q_LOADS / ODB)>{}, std::integral_constant<int, (db + 1) * (Q_LOADS / ODB)>{});
 #pragma unroll
             for (int qb = 0; qb < 2; ++qb) {
                 const int r = qb * 32 + w.lq;
@@ -1076,7 +1103,10 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
                 }
             }
             fence();
-        }
+        };
+        stage_db(std::integral_constant<int, 0>{});
+        if constexpr (ODB > 1) stage_db(std::integral_constant<int, 1>{});
+        if constexpr (ODB > 2) { stage_db(std::integral_constant<int, 2>{}); stage_db(std::integral_constant<int, 3>{}); }
         // all reads first, then the stores: one LDS round trip instead of one per row group
         u32x4 rows_out[OUT_GROUPS];
 #pragma unroll

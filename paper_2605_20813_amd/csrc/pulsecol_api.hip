@@ -97,6 +97,10 @@ pulsecol_status check_shape(const pulsecol_shape* s, std::string* why) {
         const int64_t esize = s->dtype == PULSECOL_BF16 ? 2 : 4;
         if ((int64_t)s->seq * sn * esize >= ((int64_t)1 << 32)) { *why = "seq * stride_n of K/V exceeds 4 GiB per head"; return PULSECOL_ERR_UNSUPPORTED; }
         if (s->seq >= (1 << 24) || sn * esize >= (1 << 24)) { *why = "seq or the K/V row stride in bytes reaches 2^24"; return PULSECOL_ERR_UNSUPPORTED; }
+        // ... and so does the copy of a query block
+        const int64_t qn = s->stride_n ? s->stride_n : s->head_dim;
+        if ((int64_t)s->seq * qn * esize >= ((int64_t)1 << 32)) { *why = "seq * stride_n of Q exceeds 4 GiB per head"; return PULSECOL_ERR_UNSUPPORTED; }
+        if (qn * esize >= (1 << 24)) { *why = "the Q row stride in bytes reaches 2^24"; return PULSECOL_ERR_UNSUPPORTED; }
     }
     const int a = elem_align(s->dtype);
     if (s->stride_b % a || s->stride_h % a || s->stride_n % a || s->kv_stride_b % a || s->kv_stride_h % a || s->kv_stride_n % a) {
