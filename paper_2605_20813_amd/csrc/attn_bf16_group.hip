@@ -61,8 +61,7 @@ __device__ __forceinline__ void issue_tile(byte* __restrict__ kslot, byte* __res
 // NBUF = LDS tile slots per operand: one being read, NBUF-1 on their way (2 or 3).  A third slot
 // buys a second tile of lead for the gathers and costs workgroups per CU (LDS); which one wins was
 // measured per workgroup size, see launch_by_block.  The 4-wave kernel is held to the register
-// budget of three waves per SIMD, so that three workgroups share a CU: one value of the
-// epilogue then waits in scratch memory while the loop runs, nothing inside the loop does.
+// budget of three waves per SIMD, so that three workgroups share a CU (it fits without spills).
 template <int D, int QB, int NW, int NBUF>
 __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW == 4 ? 3 : 1)))
 attn_bf16_group_kernel(AttnParams p) {
@@ -322,11 +321,14 @@ attn_bf16_group_kernel(AttnParams p) {
     }
     wait_vmcnt_at_most<0>();        // nothing of this workgroup is on its way to LDS when it ends
 
-    // ---- epilogue: O = diag(l)^-1 acc
+    // ---- epilogue: O = diag(l)^-1 acc.  The lane number is formed anew here (two instructions),
+    // so that no register has to carry the output address across the loop.
+    const int lane_out = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+    const int lq_out = lane_out & 31, lh_out = lane_out >> 5;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         const float l_tot = half_sum(l_run[qb]);
-        const int row = q0 + qb * 32 + lq;
+        const int row = q0 + qb * 32 + lq_out;
         if (row >= n) continue;
         const float inv = 1.0f / l_tot;
         __bf16* dst = (__bf16*)p.o + head_off + (int64_t)row * p.td.sn;
@@ -337,7 +339,7 @@ attn_bf16_group_kernel(AttnParams p) {
                 bf16x4 w;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o_acc[qb][db][r4 * 4 + e] * inv);
-                *(bf16x4*)(dst + db * 32 + 8 * r4 + 4 * lh) = w;
+                *(bf16x4*)(dst + db * 32 + 8 * r4 + 4 * lh_out) = w;
             }
     }
 }
