@@ -148,9 +148,9 @@ def main():
     ctx.scores(Q, K, scores_out=scores)
     scores_ms = timed(lambda: ctx.scores(Q, K, scores_out=scores), 2)
     topk_ms = timed(lambda: ctx.topk(scores, k, idx_out=idx), 5)
-    # top-k is the memory-bound stage of select: four histogram passes and one compaction pass
-    # over the fp32 score rows, k int32 indices written
-    topk_bytes = B * H * (5 * 4 * n + 4 * k)
+    # top-k is the memory-bound stage of select: algorithmic bytes = the fp32 score rows read once
+    # (the kernel holds a row in registers) and k int32 indices written per row
+    topk_bytes = B * H * (4 * n + 4 * k)
     dense_ms = timed(lambda: ctx.attn_dense(Q, K, V, O=O), a.dense_steps) if a.dense_steps > 0 else None
     # a refresh step that keeps the dense output: dense attention + column pass + top-k in one call
     refresh_dense_ms = timed(lambda: ctx.refresh_dense(Q, K, V, keep, O=O, idx_out=idx), 2)
@@ -359,7 +359,7 @@ def groupwise_config(pc, torch, dev, w, keep, G, host_qkv):
                                               "mass_kept": round(mass_bs, 4)},
                  "column_sparse_mass_kept": round(mass_cs, 4)}
         del blocks, bs_idx
-    topk_bytes = B * H * U * (5 * 4 * n + 4 * k)
+    topk_bytes = B * H * U * (4 * n + 4 * k)
     gather_bytes = B * H * U * 2 * k * d * 2 + 2 * B * H * n * d * 2      # K and V rows per group, Q, O
     res = {"group_size": G, "groups_per_head": U, "k": k,
            "scores_ms": round(scores_ms, 3), "topk_ms": round(topk_ms, 3),

@@ -1,12 +1,15 @@
 // Exact per-row top-k of fp32 scores (Sec. 3.3, TopK equation), gfx950.
 //
-// One workgroup per score row.  The k-th largest value is found by a 4-pass radix select on
-// the order-preserving integer image of the floats (one 256-bin LDS histogram per byte, most
-// significant first); the row is then swept once more in index order and every element above
-// the threshold, plus the first `need` elements equal to it, is written at the position a
-// ballot/popcount prefix sum gives it.  The output is therefore ascending in column index
-// and, among equal scores, the lower index wins.  Integer work only: results are exact and
-// identical from run to run.
+// One workgroup per score row.  The k-th largest value is found by a radix select on the
+// order-preserving integer image of the floats (LDS histograms, most significant digit first);
+// then every element above the threshold, plus the first `need` elements equal to it in index
+// order, is written at the position a ballot/popcount prefix sum gives it.  The output is
+// therefore ascending in column index and, among equal scores, the lower index wins.  Integer
+// work only: results are exact and identical from run to run.
+//
+// Two kernels: topk_rows_kernel reads the row once and keeps it in registers (rows of up to
+// 65536 elements, a multiple of 4, 16-byte aligned: every shape of the paper's workloads);
+// topk_kernel streams the row from memory five times and takes everything else.
 #include "pulsecol_device.h"
 #include "pulsecol_kernels.h"
 
@@ -108,9 +111,219 @@ __global__ void __launch_bounds__(TK_THREADS) topk_kernel(TopkParams p) {
     }
 }
 
+
+// ---- rows that fit the registers of one workgroup (n <= 65536, n % 4 == 0, 16-byte aligned):
+// the row is read from memory ONCE, as order keys, 4 * V4 per thread; everything after that works
+// on registers.  Wave w owns the contiguous segment [w*SEG, (w+1)*SEG), SEG = 256 * V4; its load
+// instruction i covers 256 consecutive elements, lane l the four elements seg0 + i*256 + 4*l .. +3
+// (one 16-byte load per lane, 1 KB contiguous per instruction).
+//
+// Radix select with 11-bit digits, starting at the highest bit in which the row's keys differ at
+// all (scores of one row share their sign and most of their exponent: a fixed first digit would
+// send every element to the same histogram bin, and same-address LDS atomics serialise): at most
+// three passes, 2048 bins.  Then the ordered compaction: every wave knows from the per-wave
+// totals where its output starts, and places its elements with ballots alone (no barrier inside).
+constexpr int TKR_DIGIT = 11;
+constexpr int TKR_BINS = 1 << TKR_DIGIT;
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) { const uint32_t o = __shfl_xor(v, d); v = o > v ? o : v; }
+    return v;
+}
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) { const uint32_t o = __shfl_xor(v, d); v = o < v ? o : v; }
+    return v;
+}
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
+    return v;
+}
+
+template <int V4>
+__global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
+    constexpr int SEG = 256 * V4;
+    static_assert(TK_THREADS * 2 == TKR_BINS, "two histogram bins per thread");
+    __shared__ uint32_t hist[TKR_BINS];
+    __shared__ uint32_t wave_a[TK_WAVES], wave_b[TK_WAVES];
+    __shared__ uint32_t sh_bin, sh_need;
+
+    const int row = blockIdx.x;
+    const float* __restrict__ s = p.scores + (int64_t)row * p.n;
+    int32_t* __restrict__ out = p.idx + (int64_t)row * p.k;
+    const int n = p.n;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int first = wave * SEG + lane * 4;          // this lane's first element
+    // load instructions of this lane that lie inside the row (n % 4 == 0: a lane's four elements
+    // are inside or outside together)
+    const int nv = first >= n ? 0 : ((n - first + 255) / 256 < V4 ? (n - first + 255) / 256 : V4);
+
+    uint32_t key[V4][4];
+    uint32_t kmax = 0u, kmin = 0xFFFFFFFFu;
+#pragma unroll
+    for (int i = 0; i < V4; ++i) {
+        if (i < nv) {
+            const f32x4 v = *(const f32x4*)(s + first + i * 256);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                key[i][c] = order_key(v[c]);
+                kmax = key[i][c] > kmax ? key[i][c] : kmax;
+                kmin = key[i][c] < kmin ? key[i][c] : kmin;
+            }
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) key[i][c] = 0u;     // never looked at: every use is guarded by nv
+        }
+    }
+    kmax = wave_max_u32(kmax);
+    kmin = wave_min_u32(kmin);
+    if (lane == 0) { wave_a[wave] = kmax; wave_b[wave] = kmin; }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < TK_WAVES; ++w) {
+        kmax = wave_a[w] > kmax ? wave_a[w] : kmax;
+        kmin = wave_b[w] < kmin ? wave_b[w] : kmin;
+    }
+    __syncthreads();                                   // wave_a / wave_b are reused below
+
+    // ---- radix select: afterwards `prefix` is the key of the k-th largest element and `need`
+    //      how many elements equal to it belong to the top-k.  Bits above `hi` are the same in
+    //      every key of the row.
+    int hi = 31 - __clz((int)(kmax ^ kmin));           // -1 if all keys are equal
+    uint32_t prefix = hi >= 31 ? 0u : ((kmax >> (hi + 1)) << (hi + 1));
+    uint32_t need = (uint32_t)p.k;
+    while (hi >= 0) {
+        const int width = hi + 1 < TKR_DIGIT ? hi + 1 : TKR_DIGIT;
+        const int shift = hi + 1 - width;
+        hist[tid] = 0u;
+        hist[tid + TK_THREADS] = 0u;
+        __syncthreads();
+        const uint32_t limit = 1u << width;
+#pragma unroll
+        for (int i = 0; i < V4; ++i) {
+            if (i < nv) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    // the digit, if all bits above it agree with the prefix (whose lower bits are zero)
+                    const uint32_t x = (key[i][c] ^ prefix) >> shift;
+                    if (x < limit) atomicAdd(&hist[x], 1u);
+                }
+            }
+        }
+        __syncthreads();
+        // the digit of the k-th largest: the highest bin b with count(bins >= b) >= need.
+        // Thread t looks at bins 2t and 2t+1; `above` = count of all bins beyond 2t+1.
+        const uint32_t h0 = hist[2 * tid], h1 = hist[2 * tid + 1];
+        uint32_t suffix = h0 + h1;                     // inclusive suffix sum over the lanes of the wave
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t o = __shfl_down(suffix, d);
+            if (lane + d < 64) suffix += o;
+        }
+        if (lane == 0) wave_a[wave] = suffix;
+        __syncthreads();
+        uint32_t above = suffix - (h0 + h1);
+#pragma unroll
+        for (int w = 0; w < TK_WAVES; ++w) above += (w > wave) ? wave_a[w] : 0u;
+        const uint32_t from1 = above + h1, from0 = from1 + h0;
+        if (above < need && from1 >= need) { sh_bin = 2 * tid + 1; sh_need = need - above; }
+        else if (from1 < need && from0 >= need) { sh_bin = 2 * tid; sh_need = need - from1; }
+        __syncthreads();
+        prefix |= sh_bin << shift;
+        need = sh_need;
+        hi = shift - 1;
+        // (hist, wave_a, sh_bin are rewritten only behind the next pass's first barrier or, after
+        //  the last pass, behind the barrier below)
+    }
+
+    // ---- ordered compaction.  Per wave: elements above the threshold and elements equal to it.
+    uint32_t n_gt = 0, n_eq = 0;
+#pragma unroll
+    for (int i = 0; i < V4; ++i) {
+        if (i < nv) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                n_gt += key[i][c] > prefix ? 1u : 0u;
+                n_eq += key[i][c] == prefix ? 1u : 0u;
+            }
+        }
+    }
+    n_gt = wave_sum_u32(n_gt);
+    n_eq = wave_sum_u32(n_eq);
+    __syncthreads();
+    if (lane == 0) { wave_a[wave] = n_gt; wave_b[wave] = n_eq; }
+    __syncthreads();
+    // the first `need` equal elements in index order are taken: waves in front of this one
+    // have used up eq_seen of them and written out_pos entries
+    uint32_t eq_seen = 0, out_pos = 0;
+#pragma unroll
+    for (int w = 0; w < TK_WAVES; ++w) {
+        if (w < wave) {
+            const uint32_t e = wave_b[w];
+            const uint32_t left = need > eq_seen ? need - eq_seen : 0u;
+            out_pos += wave_a[w] + (e < left ? e : left);
+            eq_seen += e;
+        }
+    }
+    const uint64_t lanes_before = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int i = 0; i < V4; ++i) {
+        if (wave * SEG + i * 256 >= n) break;          // uniform: nothing of this wave lies beyond
+        const bool in = i < nv;
+        bool eq[4], sel[4];
+        uint64_t eq_b[4];
+        uint32_t eq_rank = eq_seen, eq_all = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            eq[c] = in && key[i][c] == prefix;
+            eq_b[c] = __ballot(eq[c]);
+            eq_rank += __popcll(eq_b[c] & lanes_before);      // equal elements of the lanes in front
+            eq_all += __popcll(eq_b[c]);
+        }
+        uint64_t sel_b[4];
+        uint32_t pos = out_pos, sel_all = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            sel[c] = in && (key[i][c] > prefix || (eq[c] && eq_rank < need));
+            eq_rank += eq[c] ? 1u : 0u;                         // ... and of this lane's earlier elements
+            sel_b[c] = __ballot(sel[c]);
+            pos += __popcll(sel_b[c] & lanes_before);
+            sel_all += __popcll(sel_b[c]);
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (sel[c]) {
+                if (pos < (uint32_t)p.k) out[pos] = first + i * 256 + c;     // guard: holds by construction
+                ++pos;
+            }
+        }
+        eq_seen += eq_all;
+        out_pos += sel_all;
+    }
+}
+
+template <int V4>
+hipError_t launch_rows(const TopkParams& p, hipStream_t s) {
+    hipLaunchKernelGGL((topk_rows_kernel<V4>), dim3(p.rows), dim3(TK_THREADS), 0, s, p);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_topk(const TopkParams& p, hipStream_t s) {
+    if (p.rows < 1 || p.n < 1 || p.k < 1 || p.k > p.n) return hipErrorInvalidValue;
+    // rows that one workgroup can hold in registers, and that 16-byte loads can read
+    if (p.n <= 65536 && p.n % 4 == 0 && (reinterpret_cast<uintptr_t>(p.scores) & 15u) == 0) {
+        const int per_wave = (p.n + TK_WAVES - 1) / TK_WAVES;      // elements a wave has to hold
+        if (per_wave <= 256) return launch_rows<1>(p, s);
+        if (per_wave <= 512) return launch_rows<2>(p, s);
+        if (per_wave <= 1024) return launch_rows<4>(p, s);
+        if (per_wave <= 2048) return launch_rows<8>(p, s);
+        return launch_rows<16>(p, s);
+    }
     hipLaunchKernelGGL(topk_kernel, dim3(p.rows), dim3(TK_THREADS), 0, s, p);
     return hipGetLastError();
 }

@@ -192,7 +192,10 @@ def test_scores_match_oracle(B, H, n, d, dtype):
 @pytest.mark.parametrize("rows,n,k,ties", [
     (2, 256, 64, False), (3, 1000, 137, False), (4, 5000, 1, False), (2, 5000, 5000, False),
     (3, 4096, 409, True), (2, 1023, 500, True), (1, 65536, 6553, False), (1, 65536, 6553, True),
-    (2, 70001, 7000, True)])
+    (2, 70001, 7000, True),
+    # rows held in registers (n % 4 == 0, n <= 65536): ragged segments, every register count, k = n
+    (2, 12, 12, True), (3, 16, 3, False), (2, 4100, 300, True), (3, 8192, 8192, False), (2, 16388, 1, True),
+    (2, 32768, 3276, True), (2, 65532, 1000, True), (40, 65536, 6553, True)])
 def test_topk_is_bit_exact_on_identical_scores(rows, n, k, ties):
     say(f"topk case rows={rows} n={n} k={k} ties={ties}")
     s = wl.random_scores(rows, n, seed=n + k, ties=ties)
@@ -201,6 +204,26 @@ def test_topk_is_bit_exact_on_identical_scores(rows, n, k, ties):
         torch.cuda.synchronize()
     want = oracle.topk_columns(f64(s), k)
     assert np.array_equal(idx.cpu().numpy().reshape(rows, k), want)
+
+
+@pytest.mark.parametrize("n", [4096, 5001])
+def test_topk_orders_signs_magnitudes_and_narrow_ranges(n):
+    """Rows whose keys differ in the sign bit, in the exponent, or only in the last mantissa bits
+    (the radix select starts at the highest bit that differs inside the row); n = 5001 takes the
+    streaming kernel, n = 4096 the register-resident one."""
+    say(f"topk value ranges n={n}")
+    g = torch.Generator().manual_seed(n)
+    s = torch.empty(6, n)
+    s[0] = torch.randn(n, generator=g)                                      # both signs
+    s[1] = -torch.rand(n, generator=g) - 1.0                                # all negative
+    s[2] = torch.rand(n, generator=g) * 1e30                                # huge
+    s[3] = 1.0 + torch.randint(0, 7, (n,), generator=g).float() * 2.0 ** -23    # differ in 3 mantissa bits: many ties
+    s[4] = torch.randn(n, generator=g) * 10.0 ** torch.randint(-30, 30, (n,), generator=g).float()   # every exponent
+    s[5] = torch.where(torch.rand(n, generator=g) < 0.5, torch.tensor(0.0), torch.rand(n, generator=g))  # half zeros (+0)
+    for k in (1, 7, n // 3, n - 1, n):
+        with pc.Context(1, 6, n, 128, torch.bfloat16) as ctx:
+            idx = ctx.topk(s.view(1, 6, 1, n).to(DEV), k).cpu().numpy().reshape(6, k)
+        assert np.array_equal(idx, oracle.topk_columns(f64(s), k)), f"k={k}"
 
 
 def test_topk_degenerate_rows():
