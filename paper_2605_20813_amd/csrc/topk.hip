@@ -268,7 +268,10 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
             eq_seen += e;
         }
     }
-    const uint64_t lanes_before = (1ull << lane) - 1ull;
+    // bits of a ballot that belong to the lanes in front of this one, counted on top of `acc`
+    auto count_before = [](uint64_t ballot, uint32_t acc) {
+        return __builtin_amdgcn_mbcnt_hi((uint32_t)(ballot >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ballot, acc));
+    };
 #pragma unroll
     for (int i = 0; i < V4; ++i) {
         if (wave * SEG + i * 256 >= n) break;          // uniform: nothing of this wave lies beyond
@@ -280,7 +283,7 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
         for (int c = 0; c < 4; ++c) {
             eq[c] = in && key[i][c] == prefix;
             eq_b[c] = __ballot(eq[c]);
-            eq_rank += __popcll(eq_b[c] & lanes_before);      // equal elements of the lanes in front
+            eq_rank = count_before(eq_b[c], eq_rank);         // equal elements of the lanes in front
             eq_all += __popcll(eq_b[c]);
         }
         uint64_t sel_b[4];
@@ -290,7 +293,7 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
             sel[c] = in && (key[i][c] > prefix || (eq[c] && eq_rank < need));
             eq_rank += eq[c] ? 1u : 0u;                         // ... and of this lane's earlier elements
             sel_b[c] = __ballot(sel[c]);
-            pos += __popcll(sel_b[c] & lanes_before);
+            pos = count_before(sel_b[c], pos);
             sel_all += __popcll(sel_b[c]);
         }
 #pragma unroll
