@@ -373,6 +373,32 @@ def test_validation_mode_rejects_out_of_range_columns():
 # ---------------------------------------------------------------------------------------
 # work distribution of the bf16 attention kernels
 # ---------------------------------------------------------------------------------------
+def test_non_finite_inputs_stay_inside_their_head():
+    """NaN / Inf in the inputs give an undefined result for the head that holds them, and
+    nothing else: every call returns, the other head's outputs and columns are bit-identical
+    to those of a run on clean inputs (no address, loop bound or wait depends on a value)."""
+    B, H, n, d, k = 1, 2, 900, 128, 300
+    say("non-finite inputs")
+    Q, K, V = rand_qkv(B, H, n, d, torch.bfloat16, seed=77)
+    idx = random_idx(n, k, B * H, seed=78).view(B, H, 1, k)
+    Qb, Kb, Vb = Q.clone(), K.clone(), V.clone()
+    Qb[0, 0, 5, 3] = float("nan")
+    Qb[0, 0, 300] = float("inf")
+    Kb[0, 0, 17, :] = float("-inf")
+    Kb[0, 0, 400, 1] = float("nan")
+    Vb[0, 0, 33, 0] = float("inf")
+    with pc.Context(B, H, n, d, torch.bfloat16) as ctx:
+        clean = [ctx.attn(Q.to(DEV), K.to(DEV), V.to(DEV), idx.to(DEV)), ctx.attn_dense(Q.to(DEV), K.to(DEV), V.to(DEV)),
+                 ctx.scores(Q.to(DEV), K.to(DEV)), ctx.select(Q.to(DEV), K.to(DEV), 0.2, refresh=True)]
+        dirty = [ctx.attn(Qb.to(DEV), Kb.to(DEV), Vb.to(DEV), idx.to(DEV)), ctx.attn_dense(Qb.to(DEV), Kb.to(DEV), Vb.to(DEV)),
+                 ctx.scores(Qb.to(DEV), Kb.to(DEV)), ctx.select(Qb.to(DEV), Kb.to(DEV), 0.2, refresh=True)]
+        torch.cuda.synchronize()
+    for c, x in zip(clean, dirty):
+        assert torch.equal(c[0, 1], x[0, 1])
+    sel = dirty[3][0, 0, 0].cpu().numpy()          # the disturbed head still gets k distinct ascending columns in range
+    assert sel.shape == (pc.num_keep(n, 0.2),) and (sel[1:] > sel[:-1]).all() and sel[0] >= 0 and sel[-1] < n
+
+
 @pytest.mark.parametrize("B,H,n,k", [(1, 1, 1300, 333), (1, 5, 2100, 257), (2, 13, 700, 64), (1, 32, 1024, 128)])
 def test_query_block_queues_hand_out_every_block_once(B, H, n, k):
     """The kernels' workgroups take query blocks from per-XCD queues (and from other queues once
