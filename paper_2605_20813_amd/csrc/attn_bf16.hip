@@ -1136,17 +1136,6 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
 // workgroups that one CU holds at a time (LDS and registers): the row pass fits two
 template <int MODE> constexpr int wg_per_cu() { return MODE == kLseOnly ? 2 : 1; }
 
-int compute_units() {
-    static int cached[64] = {};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-    if (cached[dev] == 0) {
-        int n = 0;
-        cached[dev] = (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) ? n : 256;
-    }
-    return cached[dev];
-}
-
 template <int D, int MODE>
 hipError_t launch(const AttnParams& p, hipStream_t s) {
     if (p.work == nullptr) return hipErrorInvalidValue;
@@ -1158,6 +1147,17 @@ hipError_t launch(const AttnParams& p, hipStream_t s) {
 }
 
 }  // namespace
+
+int compute_units() {
+    static int cached[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        cached[dev] = (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) ? n : 256;
+    }
+    return cached[dev];
+}
 
 hipError_t launch_attn_bf16(const AttnParams& p, int head_dim, AttnMode mode, hipStream_t s) {
     if (head_dim == 128) {

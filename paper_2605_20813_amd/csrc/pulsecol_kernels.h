@@ -60,6 +60,9 @@ constexpr int kBlockN_bf16 = 64;    // gathered columns per tile
 constexpr int kBlockM_f32 = 128;    // 4 waves x 32
 constexpr int kBlockN_f32 = 32;
 
+// compute units of the current device (cached per device; 256 if the runtime does not say)
+int compute_units();
+
 hipError_t launch_attn_bf16(const AttnParams& p, int head_dim, AttnMode mode, hipStream_t s);
 // column-sparse attention with query blocks of block_m = 32, 64 or 128 rows (small query groups)
 hipError_t launch_attn_bf16_group(const AttnParams& p, int head_dim, int block_m, hipStream_t s);

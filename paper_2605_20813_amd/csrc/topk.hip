@@ -8,7 +8,8 @@
 // work only: results are exact and identical from run to run.
 //
 // Two kernels: topk_rows_kernel reads the row once and keeps it in registers (rows of up to
-// 65536 elements, a multiple of 4, 16-byte aligned: every shape of the paper's workloads);
+// 65536 elements, a multiple of 4, 16-byte aligned: every shape of the paper's workloads; a
+// resident grid whose workgroups walk over the rows and fetch the next row while writing out);
 // topk_kernel streams the row from memory five times and takes everything else.
 #include "pulsecol_device.h"
 #include "pulsecol_kernels.h"
@@ -20,10 +21,10 @@ constexpr int TK_THREADS = 1024;
 constexpr int TK_WAVES = TK_THREADS / 64;
 
 // floats -> unsigned keys with the same order (larger float <=> larger key)
-__device__ __forceinline__ uint32_t order_key(float x) {
-    const uint32_t u = __float_as_uint(x);
+__device__ __forceinline__ uint32_t order_key_of_bits(uint32_t u) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
+__device__ __forceinline__ uint32_t order_key(float x) { return order_key_of_bits(__float_as_uint(x)); }
 
 __global__ void __launch_bounds__(TK_THREADS) topk_kernel(TopkParams p) {
     __shared__ uint32_t hist[256];
@@ -150,9 +151,6 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
     __shared__ uint32_t wave_a[TK_WAVES], wave_b[TK_WAVES];
     __shared__ uint32_t sh_bin, sh_need;
 
-    const int row = blockIdx.x;
-    const float* __restrict__ s = p.scores + (int64_t)row * p.n;
-    int32_t* __restrict__ out = p.idx + (int64_t)row * p.k;
     const int n = p.n;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -161,21 +159,36 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
     // are inside or outside together)
     const int nv = first >= n ? 0 : ((n - first + 255) / 256 < V4 ? (n - first + 255) / 256 : V4);
 
+    // The workgroup walks over rows blockIdx.x, + gridDim.x, ...; the scores of the next row are
+    // requested while the running row is written out (each register group as soon as the
+    // compaction is done with it), so that only the first row's load is waited for in full.
+    // key[][] holds the row: as float bit patterns from the load until the row's turn comes, as
+    // order keys from then on
     uint32_t key[V4][4];
+    const uint32_t* __restrict__ bits = (const uint32_t*)p.scores;
+#pragma unroll
+    for (int i = 0; i < V4; ++i) {
+        u32x4 v = {0u, 0u, 0u, 0u};                          // outside the row: never looked at, every use is guarded by nv
+        if (i < nv) v = *(const u32x4*)(bits + (int64_t)blockIdx.x * n + first + i * 256);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) key[i][c] = v[c];
+    }
+
+  for (int row = blockIdx.x; row < p.rows; row += gridDim.x) {
+    int32_t* __restrict__ out = p.idx + (int64_t)row * p.k;
+    const bool more = row + (int)gridDim.x < p.rows;
+    const uint32_t* __restrict__ next_bits = bits + (int64_t)(more ? row + (int)gridDim.x : row) * n + first;
+
     uint32_t kmax = 0u, kmin = 0xFFFFFFFFu;
 #pragma unroll
     for (int i = 0; i < V4; ++i) {
-        if (i < nv) {
-            const f32x4 v = *(const f32x4*)(s + first + i * 256);
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                key[i][c] = order_key(v[c]);
+        for (int c = 0; c < 4; ++c) {
+            key[i][c] = order_key_of_bits(key[i][c]);
+            if (i < nv) {
                 kmax = key[i][c] > kmax ? key[i][c] : kmax;
                 kmin = key[i][c] < kmin ? key[i][c] : kmin;
             }
-        } else {
-#pragma unroll
-            for (int c = 0; c < 4; ++c) key[i][c] = 0u;     // never looked at: every use is guarded by nv
         }
     }
     kmax = wave_max_u32(kmax);
@@ -195,6 +208,10 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
     int hi = 31 - __clz((int)(kmax ^ kmin));           // -1 if all keys are equal
     uint32_t prefix = hi >= 31 ? 0u : ((kmax >> (hi + 1)) << (hi + 1));
     uint32_t need = (uint32_t)p.k;
+    // register groups of this lane that still hold an element matching the prefix: all of them in
+    // the first pass, next to none later (a bin of the first pass holds n/2048 elements on
+    // average), so that the later passes skip almost all of their work, whole waves at a time
+    uint32_t live = nv >= 32 ? 0xFFFFFFFFu : ((1u << nv) - 1u);
     while (hi >= 0) {
         const int width = hi + 1 < TKR_DIGIT ? hi + 1 : TKR_DIGIT;
         const int shift = hi + 1 - width;
@@ -202,16 +219,20 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
         hist[tid + TK_THREADS] = 0u;
         __syncthreads();
         const uint32_t limit = 1u << width;
+        if (__ballot(live != 0u) != 0ull) {
+            uint32_t still = 0u;
 #pragma unroll
-        for (int i = 0; i < V4; ++i) {
-            if (i < nv) {
+            for (int i = 0; i < V4; ++i) {
+                if ((live >> i) & 1u) {
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    // the digit, if all bits above it agree with the prefix (whose lower bits are zero)
-                    const uint32_t x = (key[i][c] ^ prefix) >> shift;
-                    if (x < limit) atomicAdd(&hist[x], 1u);
+                    for (int c = 0; c < 4; ++c) {
+                        // the digit, if all bits above it agree with the prefix (whose lower bits are zero)
+                        const uint32_t x = (key[i][c] ^ prefix) >> shift;
+                        if (x < limit) { atomicAdd(&hist[x], 1u); still |= 1u << i; }
+                    }
                 }
             }
+            live = still;
         }
         __syncthreads();
         // the digit of the k-th largest: the highest bin b with count(bins >= b) >= need.
@@ -305,12 +326,24 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
         }
         eq_seen += eq_all;
         out_pos += sel_all;
+        if (more && in) {
+            const u32x4 v = *(const u32x4*)(next_bits + i * 256);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) key[i][c] = v[c];
+        }
     }
+    // register groups beyond this wave's share of the row were skipped above; they hold nothing
+    __syncthreads();                                   // wave_a / wave_b are rewritten by the next row
+  }
 }
 
 template <int V4>
 hipError_t launch_rows(const TopkParams& p, hipStream_t s) {
-    hipLaunchKernelGGL((topk_rows_kernel<V4>), dim3(p.rows), dim3(TK_THREADS), 0, s, p);
+    // as many workgroups as the chip holds at a time (the register count allows two per CU up to
+    // 16 keys per thread, one beyond); each walks over its share of the rows
+    const int resident = compute_units() * (V4 <= 4 ? 2 : 1);
+    const int grid = p.rows < resident ? p.rows : resident;
+    hipLaunchKernelGGL((topk_rows_kernel<V4>), dim3(grid), dim3(TK_THREADS), 0, s, p);
     return hipGetLastError();
 }
 
