@@ -24,7 +24,7 @@ PEAK_F32_TFLOPS = 157.3
 # HBM-side bytes per launch of the column-sparse attention kernel, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs of this script scaled by a 1 GiB copy in the same run (summary under profiles/);
 # a measured constant of the workload, not something this script can read live.
-MEASURED_TRAFFIC_BYTES = {("llada_64k", 0.10): 1.918e9}
+MEASURED_TRAFFIC_BYTES = {("llada_64k", 0.10): 1.906e9}
 
 
 def parse():
