@@ -195,7 +195,10 @@ def test_scores_match_oracle(B, H, n, d, dtype):
     (2, 70001, 7000, True),
     # rows held in registers (n % 4 == 0, n <= 65536): ragged segments, every register count, k = n
     (2, 12, 12, True), (3, 16, 3, False), (2, 4100, 300, True), (3, 8192, 8192, False), (2, 16388, 1, True),
-    (2, 32768, 3276, True), (2, 65532, 1000, True), (40, 65536, 6553, True)])
+    (2, 32768, 3276, True), (2, 65532, 1000, True), (40, 65536, 6553, True),
+    # more rows than resident workgroups: every workgroup walks over several rows, fetching the next
+    # one while it writes the running one out (1 and 16 register groups per lane, ragged rows)
+    (1300, 1020, 100, True), (700, 8200, 999, True), (300, 65536, 6553, True), (530, 40000, 4000, False)])
 def test_topk_is_bit_exact_on_identical_scores(rows, n, k, ties):
     say(f"topk case rows={rows} n={n} k={k} ties={ties}")
     s = wl.random_scores(rows, n, seed=n + k, ties=ties)
