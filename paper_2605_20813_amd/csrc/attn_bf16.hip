@@ -893,6 +893,7 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     auto request_q_all = [&] { request_q(std::integral_constant<int, 0>{}, std::integral_constant<int, Q_LOADS>{}); };
     if (cur_j >= 0) { request_rows(cur_q, cur_j); request_q_all(); }
 
+  bool k0_on_its_way = false;
   while (cur_j >= 0) {
     int bh, qblk;
     decode(cur_q, cur_j, bh, qblk);
@@ -943,7 +944,7 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
             for (int kk = 0; kk < KK; ++kk) w.qf[qb][kk] = *(const bf16x8*)(src + kk * 16);
         }
     }
-    w.issue_k_tile(lds_k, w.K, rows_0);
+    if (!k0_on_its_way) w.issue_k_tile(lds_k, w.K, rows_0);      // else: issued from the epilogue of the block before
     constexpr int LATER_LOADS = CH * (HAS_V ? 4 : 2);     // V(0), K(1), V(1), K(2): issued behind the first barrier
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb)
@@ -1090,7 +1091,6 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
         static_assert((Q_LOADS / ODB) % 4 == 0, "whole groups of four loads per d-block");
         const auto stage_db = [&](auto db_c) {
             constexpr int db = decltype(db_c)::value;
-            if (more) request_q(std::integral_constant<int, db * (Q_LOADS / ODB)>{}, std::integral_constant<int, (db + 1) * (Q_LOADS / ODB)>{});
 #pragma unroll
             for (int qb = 0; qb < 2; ++qb) {
                 const int r = qb * 32 + w.lq;
@@ -1104,9 +1104,30 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
             }
             fence();
         };
+        // piece db of the next block's Q copy
+        const auto request_q_piece = [&](auto db_c) {
+            constexpr int db = decltype(db_c)::value;
+            if (more) request_q(std::integral_constant<int, db * (Q_LOADS / ODB)>{}, std::integral_constant<int, (db + 1) * (Q_LOADS / ODB)>{});
+        };
         stage_db(std::integral_constant<int, 0>{});
-        if constexpr (ODB > 1) stage_db(std::integral_constant<int, 1>{});
-        if constexpr (ODB > 2) { stage_db(std::integral_constant<int, 2>{}); stage_db(std::integral_constant<int, 3>{}); }
+        // The next block's first K tile goes out as soon as its row numbers are there (they were
+        // requested a d-block of staging ago; the compiler's wait for them drains the vector
+        // memory pipe, so nothing else is put in flight before it): K slot 0 is not part of the
+        // staging area and no wave reads K any more, and the tile lands while the stores queue.
+        k0_on_its_way = more;
+        if (more) {
+            int nbh, nqblk;
+            decode(cur_q, cur_j, nbh, nqblk);
+            const int nb = nbh / p.heads, nh = nbh - nb * p.heads;
+            const int64_t nkv = (int64_t)nb * p.td_kv.sb + (int64_t)(nh / (p.heads / p.kv_heads)) * p.td_kv.sh;
+            w.issue_k_tile(lds_k, (const byte*)((const __bf16*)p.k + nkv), rows_0);
+        }
+        request_q_piece(std::integral_constant<int, 0>{});
+        if constexpr (ODB > 1) { stage_db(std::integral_constant<int, 1>{}); request_q_piece(std::integral_constant<int, 1>{}); }
+        if constexpr (ODB > 2) {
+            stage_db(std::integral_constant<int, 2>{}); request_q_piece(std::integral_constant<int, 2>{});
+            stage_db(std::integral_constant<int, 3>{}); request_q_piece(std::integral_constant<int, 3>{});
+        }
         // all reads first, then the stores: one LDS round trip instead of one per row group
         u32x4 rows_out[OUT_GROUPS];
 #pragma unroll
