@@ -339,9 +339,9 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
 
 template <int V4>
 hipError_t launch_rows(const TopkParams& p, hipStream_t s) {
-    // as many workgroups as the chip holds at a time (the register count allows two per CU up to
-    // 16 keys per thread, one beyond); each walks over its share of the rows
-    const int resident = compute_units() * (V4 <= 4 ? 2 : 1);
+    // as many workgroups as the chip holds at a time (1024 threads at more than 64 registers: one
+    // per CU); each walks over its share of the rows
+    const int resident = compute_units();
     const int grid = p.rows < resident ? p.rows : resident;
     hipLaunchKernelGGL((topk_rows_kernel<V4>), dim3(grid), dim3(TK_THREADS), 0, s, p);
     return hipGetLastError();
