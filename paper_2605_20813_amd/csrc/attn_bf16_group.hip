@@ -359,6 +359,8 @@ hipError_t launch_by_block(const AttnParams& p, int block_m, hipStream_t s) {
     // SIMD (two blocks per wave halve the LDS reads per MFMA, and measured slower at every size).
     // Slots, measured at 64K / keep 10%: 128 rows 3 (6.9 ms, against 7.6 with 2), 64 rows 2 (10.8
     // against 12.2), 32 rows 3 (14.7 against 24.4: a one-wave workgroup has nobody to wait with).
+    // (Three slots of K with two of V -- 40 KB, a fourth workgroup per CU on paper -- measured
+    // 11.3 and 16.9 ms for 64 and 32 rows: worse than either.)
     if (block_m == 128) return launch<D, 1, 4, 3>(p, s);
     if (block_m == 64) return launch<D, 1, 2, 2>(p, s);
     if (block_m == 32) return launch<D, 1, 1, 3>(p, s);
