@@ -223,7 +223,9 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
             uint32_t still = 0u;
 #pragma unroll
             for (int i = 0; i < V4; ++i) {
-                if ((live >> i) & 1u) {
+                const bool mine = (live >> i) & 1u;
+                if (__ballot(mine) == 0ull) continue;        // nobody in the wave: skip the group outright
+                if (mine) {
 #pragma unroll
                     for (int c = 0; c < 4; ++c) {
                         // the digit, if all bits above it agree with the prefix (whose lower bits are zero)
@@ -297,15 +299,19 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
     for (int i = 0; i < V4; ++i) {
         if (wave * SEG + i * 256 >= n) break;          // uniform: nothing of this wave lies beyond
         const bool in = i < nv;
+        // elements equal to the threshold are rare (ties at the k-th value): the four ballots that
+        // rank them are taken only if the wave holds one in this register group
         bool eq[4], sel[4];
-        uint64_t eq_b[4];
         uint32_t eq_rank = eq_seen, eq_all = 0;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            eq[c] = in && key[i][c] == prefix;
-            eq_b[c] = __ballot(eq[c]);
-            eq_rank = count_before(eq_b[c], eq_rank);         // equal elements of the lanes in front
-            eq_all += __popcll(eq_b[c]);
+        for (int c = 0; c < 4; ++c) eq[c] = in && key[i][c] == prefix;
+        if (__ballot(eq[0] || eq[1] || eq[2] || eq[3]) != 0ull) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint64_t eq_b = __ballot(eq[c]);
+                eq_rank = count_before(eq_b, eq_rank);          // equal elements of the lanes in front
+                eq_all += __popcll(eq_b);
+            }
         }
         uint64_t sel_b[4];
         uint32_t pos = out_pos, sel_all = 0;
