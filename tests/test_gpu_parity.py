@@ -376,6 +376,41 @@ def test_validation_mode_rejects_out_of_range_columns():
 # ---------------------------------------------------------------------------------------
 # work distribution of the bf16 attention kernels
 # ---------------------------------------------------------------------------------------
+def test_two_contexts_on_two_streams_at_once():
+    """Calls on different contexts may overlap in time (each context owns its scratch and its
+    work counters): two streams of default priority, each running select + attention launches of
+    its own context back to back, give what the same calls give one after the other."""
+    B, H, n, d, k = 1, 4, 2048, 128, 300
+    say("two contexts, two streams")
+    inputs = []
+    for seed in (91, 92):
+        Q, K, V = rand_qkv(B, H, n, d, torch.bfloat16, seed=seed)
+        idx = random_idx(n, k, B * H, seed=seed + 10).view(B, H, 1, k)
+        inputs.append(tuple(t.to(DEV) for t in (Q, K, V, idx)))
+    with pc.Context(B, H, n, d, torch.bfloat16) as c0, pc.Context(B, H, n, d, torch.bfloat16) as c1:
+        ctxs = (c0, c1)
+        want = []
+        for c, (Q, K, V, idx) in zip(ctxs, inputs):
+            want.append((c.attn(Q, K, V, idx).clone(), c.select(Q, K, 0.1, refresh=True).clone(), c.attn_dense(Q, K, V).clone()))
+        torch.cuda.synchronize()
+        streams = (torch.cuda.Stream(), torch.cuda.Stream())
+        got = [None, None]
+        for rep in range(3):
+            outs = [[], []]
+            for i in range(2):                       # interleaved submission: the launches of the two contexts overlap
+                with torch.cuda.stream(streams[i]):
+                    Q, K, V, idx = inputs[i]
+                    outs[i].append(ctxs[i].attn(Q, K, V, idx))
+                    outs[i].append(ctxs[i].select(Q, K, 0.1, refresh=True))
+                    outs[i].append(ctxs[i].attn_dense(Q, K, V))
+            for st in streams:
+                st.synchronize()
+            got = outs
+            for i in range(2):
+                for a, b in zip(got[i], want[i]):
+                    assert torch.equal(a, b), f"context {i}, repetition {rep}"
+
+
 def test_non_finite_inputs_stay_inside_their_head():
     """NaN / Inf in the inputs give an undefined result for the head that holds them, and
     nothing else: every call returns, the other head's outputs and columns are bit-identical
