@@ -202,6 +202,19 @@ def main():
                      "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, round(keep, 4)))},
         "paper_context": "paper: 1.95x end-to-end over FlashAttention at 64K/1024 steps, keep 20%, whole model, RTX PRO 6000",
     }
+    # The paper's schedule settings (refresh window eta = 30% of 1024 steps, R = 4 / 8 / 16 refreshes,
+    # placed by its schedule equation): ms per layer-step from the times measured above (no extra
+    # launches: steps are identical in cost), with the refresh done by select and by the fused
+    # refresh_dense that also yields the dense output of the refresh step.
+    from paper_2605_20813_amd import schedule as sch
+    sweep = []
+    for R in (4, 8, 16):
+        placed = sch.refresh_steps(1024, 0.30, R)
+        sweep.append({"eta": 0.30, "R": R, "first_and_last_refresh_step": [placed[0], placed[-1]],
+                      "ms_per_step_select": round(attn_ms + R * select_ms / 1024.0, 4),
+                      "ms_per_step_refresh_dense": round((attn_ms * (1024 - R) + R * refresh_dense_ms) / 1024.0, 4),
+                      "speedup_vs_dense": None if dense_ms is None else round(dense_ms / (attn_ms + R * select_ms / 1024.0), 3)})
+    out["schedule_sweep_1024_steps"] = sweep
 
     ctx.close()
     del Q, K, V, O, scores, idx
