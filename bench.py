@@ -181,6 +181,10 @@ def main():
         "attn_ms_median": round(attn_ms_median, 4),
         "attn_ms_min": round(attn_ms_min, 4),
         "attn_ms_cold": None if attn_ms_cold is None else round(attn_ms_cold, 4),
+        # the same layer-step with every attention launch behind a 1 GiB fill (caches flushed, as
+        # when the other layers of a model run in between); `value` is the back-to-back figure
+        "ms_per_step_cold": None if attn_ms_cold is None else round(ms_per_step - attn_ms + attn_ms_cold, 4),
+        "kept_tflops_cold": None if attn_ms_cold is None else round(kept_flop / (attn_ms_cold * 1e-3) * 1e-12, 2),
         "select_ms": round(select_ms, 4),
         "scores_ms": round(scores_ms, 4),
         "topk_ms": round(topk_ms, 4),
