@@ -119,13 +119,14 @@ __global__ void __launch_bounds__(TK_THREADS) topk_kernel(TopkParams p) {
 // instruction i covers 256 consecutive elements, lane l the four elements seg0 + i*256 + 4*l .. +3
 // (one 16-byte load per lane, 1 KB contiguous per instruction).
 //
-// Radix select with 11-bit digits, starting at the highest bit in which the row's keys differ at
+// Radix select with 13-bit digits, starting at the highest bit in which the row's keys differ at
 // all (scores of one row share their sign and most of their exponent: a fixed first digit would
 // send every element to the same histogram bin, and same-address LDS atomics serialise): at most
-// three passes, 2048 bins.  Then the ordered compaction: every wave knows from the per-wave
+// three passes, 8192 bins.  Then the ordered compaction: every wave knows from the per-wave
 // totals where its output starts, and places its elements with ballots alone (no barrier inside).
-constexpr int TKR_DIGIT = 11;
+constexpr int TKR_DIGIT = 13;
 constexpr int TKR_BINS = 1 << TKR_DIGIT;
+constexpr int TKR_BPT = TKR_BINS / TK_THREADS;       // histogram bins per thread
 
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
 #pragma unroll
@@ -146,10 +147,14 @@ __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
 template <int V4>
 __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
     constexpr int SEG = 256 * V4;
-    static_assert(TK_THREADS * 2 == TKR_BINS, "two histogram bins per thread");
-    __shared__ uint32_t hist[TKR_BINS];
+    static_assert(TKR_BPT * TK_THREADS == TKR_BINS && TKR_BPT % 4 == 0, "whole 16-byte groups of bins per thread");
+    __shared__ __attribute__((aligned(16))) uint32_t hist[TKR_BINS];
     __shared__ uint32_t wave_a[TK_WAVES], wave_b[TK_WAVES];
-    __shared__ uint32_t sh_bin, sh_need;
+    __shared__ uint32_t sh_bin, sh_need, sh_cnt, sh_ncand;
+    // the elements that fell into the first pass's bin, if they are few enough: the later passes
+    // then walk over this list instead of sweeping the registers again
+    constexpr int CAND_MAX = 4096;
+    __shared__ uint32_t cand[CAND_MAX];
 
     const int n = p.n;
     const int tid = threadIdx.x;
@@ -209,17 +214,35 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
     uint32_t prefix = hi >= 31 ? 0u : ((kmax >> (hi + 1)) << (hi + 1));
     uint32_t need = (uint32_t)p.k;
     // register groups of this lane that still hold an element matching the prefix: all of them in
-    // the first pass, next to none later (a bin of the first pass holds n/2048 elements on
+    // the first pass, next to none later (a bin of the first pass holds n/8192 elements on
     // average), so that the later passes skip almost all of their work, whole waves at a time
     uint32_t live = nv >= 32 ? 0xFFFFFFFFu : ((1u << nv) - 1u);
+    bool first_pass = true, listed = false;
+    uint32_t ncand = 0;
     while (hi >= 0) {
         const int width = hi + 1 < TKR_DIGIT ? hi + 1 : TKR_DIGIT;
         const int shift = hi + 1 - width;
-        hist[tid] = 0u;
-        hist[tid + TK_THREADS] = 0u;
+#pragma unroll
+        for (int b = 0; b < TKR_BPT / 4; ++b) *(u32x4*)&hist[TKR_BPT * tid + 4 * b] = u32x4{0u, 0u, 0u, 0u};
         __syncthreads();
         const uint32_t limit = 1u << width;
-        if (__ballot(live != 0u) != 0ull) {
+        if (first_pass) {
+            // every key agrees with the prefix above the first digit by construction: no test per
+            // element (a test per element is a predicated region per element, and those, not the
+            // atomics, are what a sweep over the registers costs)
+#pragma unroll
+            for (int i = 0; i < V4; ++i) {
+                if (i < nv) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) atomicAdd(&hist[(key[i][c] ^ prefix) >> shift], 1u);
+                }
+            }
+        } else if (listed) {
+            for (uint32_t j = tid; j < ncand; j += TK_THREADS) {
+                const uint32_t x = (cand[j] ^ prefix) >> shift;
+                if (x < limit) atomicAdd(&hist[x], 1u);
+            }
+        } else if (__ballot(live != 0u) != 0ull) {
             uint32_t still = 0u;
 #pragma unroll
             for (int i = 0; i < V4; ++i) {
@@ -238,9 +261,14 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
         }
         __syncthreads();
         // the digit of the k-th largest: the highest bin b with count(bins >= b) >= need.
-        // Thread t looks at bins 2t and 2t+1; `above` = count of all bins beyond 2t+1.
-        const uint32_t h0 = hist[2 * tid], h1 = hist[2 * tid + 1];
-        uint32_t suffix = h0 + h1;                     // inclusive suffix sum over the lanes of the wave
+        // Thread t looks at bins TKR_BPT*t .. +TKR_BPT-1; `above` = count of all bins beyond them.
+        uint32_t mine = 0;
+#pragma unroll
+        for (int b = 0; b < TKR_BPT / 4; ++b) {
+            const u32x4 v = *(const u32x4*)&hist[TKR_BPT * tid + 4 * b];
+            mine += (v[0] + v[1]) + (v[2] + v[3]);
+        }
+        uint32_t suffix = mine;                        // inclusive suffix sum over the lanes of the wave
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
             const uint32_t o = __shfl_down(suffix, d);
@@ -248,16 +276,46 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
         }
         if (lane == 0) wave_a[wave] = suffix;
         __syncthreads();
-        uint32_t above = suffix - (h0 + h1);
+        uint32_t above = suffix - mine;
 #pragma unroll
         for (int w = 0; w < TK_WAVES; ++w) above += (w > wave) ? wave_a[w] : 0u;
-        const uint32_t from1 = above + h1, from0 = from1 + h0;
-        if (above < need && from1 >= need) { sh_bin = 2 * tid + 1; sh_need = need - above; }
-        else if (from1 < need && from0 >= need) { sh_bin = 2 * tid; sh_need = need - from1; }
+        if (above < need && above + mine >= need) {        // one thread: the bin is among its own
+            // (its counts are read again here rather than kept in registers across the scan)
+            for (int b = TKR_BPT - 1; b >= 0; --b) {
+                const uint32_t hb = hist[TKR_BPT * tid + b];
+                if (above + hb >= need) {
+                    sh_bin = TKR_BPT * tid + b; sh_need = need - above; sh_cnt = hb; sh_ncand = 0u;
+                    break;
+                }
+                above += hb;
+            }
+        }
         __syncthreads();
         prefix |= sh_bin << shift;
         need = sh_need;
         hi = shift - 1;
+        if (first_pass && hi >= 0 && sh_cnt <= (uint32_t)CAND_MAX) {
+            // one more sweep over the registers, the last: whoever agrees with the prefix down to
+            // the first digit goes on the list (in any order: the passes only count)
+#pragma unroll
+            for (int i = 0; i < V4; ++i) {
+                bool hit[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) hit[c] = ((key[i][c] ^ prefix) >> shift) == 0u;
+                if (i < nv && (hit[0] || hit[1] || hit[2] || hit[3])) {         // rare: one region per group
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        if (hit[c]) {
+                            const uint32_t at = atomicAdd(&sh_ncand, 1u);
+                            if (at < (uint32_t)CAND_MAX) cand[at] = key[i][c];      // guard: holds by construction (sh_cnt counted them)
+                        }
+                }
+            }
+            listed = true;
+            ncand = sh_cnt;
+            // (the next pass's first barrier stands between these writes and its reads of the list)
+        }
+        first_pass = false;
         // (hist, wave_a, sh_bin are rewritten only behind the next pass's first barrier or, after
         //  the last pass, behind the barrier below)
     }
