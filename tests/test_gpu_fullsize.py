@@ -150,3 +150,31 @@ def test_full_size_groupwise_sampled_groups(name, G, keep):
         want = oracle.sparse_attention_masked(qg, kh, vh, row)
         assert_close(O[0, h, lo:hi], want, "bf16", f"{name} attn head {h} group {u}")
     say(f"ok, near-tie flips {flips}")
+
+
+def test_twice_the_largest_workload_context():
+    """128K context (8 heads): beyond every configured workload -- rows longer than the
+    register-resident top-k holds (the streaming kernel runs at full size), twice as many query
+    blocks per head in the queues.  Sampled query rows against the oracle; every planted heavy
+    key column must be selected."""
+    B, H, n, d, keep = 1, 8, 131072, 128, 0.05
+    say("128K context: generating")
+    g = torch.Generator(device="cpu")
+    g.manual_seed(20813)
+    Q, K, V = (torch.randn(B, H, n, d, generator=g).to(torch.bfloat16) for _ in range(3))
+    K[:, :, ::17] *= 2.5                              # 7711 heavy columns, more than the k = 6553 kept
+    k = oracle.num_keep(n, keep)
+    with pc.Context(B, H, n, d, torch.bfloat16) as ctx:
+        q, k_, v = Q.to(DEV), K.to(DEV), V.to(DEV)
+        idx = ctx.select(q, k_, keep, refresh=True)
+        O = ctx.attn(q, k_, v, idx)
+        torch.cuda.synchronize()
+    idx_h = idx.cpu().numpy()
+    assert idx_h.shape == (B, H, 1, k)
+    assert (idx_h[..., 1:] > idx_h[..., :-1]).all() and idx_h.min() >= 0 and idx_h.max() < n
+    assert (idx_h % 17 == 0).all()                    # only heavy columns can be among the top 5%
+    rows = sample_rows(n, 6, seed=3)
+    for h in (0, 5, 7):
+        say(f"128K context: oracle rows of head {h}")
+        want = oracle.sparse_attention_masked(f64(Q[0, h, rows]), f64(K[0, h]), f64(V[0, h]), idx_h[0, h])
+        assert_close(O[0, h, rows], want, "bf16", f"128K head {h}")
