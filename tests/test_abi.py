@@ -63,6 +63,13 @@ def test_status_strings():
     (dict(strides=(0, 0, 136)), pc.OK),
     (dict(scale=-1.0), pc.ERR_INVALID_ARG),
     (dict(scale=float("nan")), pc.ERR_INVALID_ARG),
+    # the kernels address a head's rows with 32-bit byte offsets formed by 24-bit multiplies
+    (dict(seq=1 << 23), pc.OK),                                         # 8M rows x 256 B = 2 GiB per head
+    (dict(seq=1 << 24), pc.ERR_UNSUPPORTED),                            # row number needs 25 bits
+    (dict(seq=1 << 20, strides=(0, 0, 2040)), pc.OK),                   # just under 4 GiB per head
+    (dict(seq=1 << 20, strides=(0, 0, 2048)), pc.ERR_UNSUPPORTED),      # 4 GiB per head
+    (dict(seq=64, strides=(0, 0, 1 << 23)), pc.ERR_UNSUPPORTED),        # row stride of 2^24 bytes
+    (dict(seq=1 << 20, kv_heads=8, kv_strides=(0, 0, 2048)), pc.ERR_UNSUPPORTED),
 ])
 def test_validate_shape(kw, want):
     args = dict(batch=1, heads=32, seq=4096, head_dim=128, dtype=pc.BF16, group_size=0, strides=(0, 0, 0), scale=0.0)
