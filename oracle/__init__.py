@@ -16,7 +16,8 @@ from .pulsecol_oracle import (  # noqa: F401
     refresh_schedule_random,
     row_softmax,
     select_columns,
+    sparse_attention_chunked,
+    sparse_attention_gathered,
     sparse_attention_masked,
-    sparse_attention_tiled,
     topk_columns,
 )

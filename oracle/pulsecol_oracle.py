@@ -12,7 +12,8 @@ may be processed a slab at a time (``row_chunk``), which changes no value.
 
 Pins (tests/test_oracle_pins.py): closed-form softmax examples, the textbook
 dense attention of an independent library, row-stochastic invariants, brute
-force over all column subsets (Eq. 7), Eq. 2 against Alg. 1, hand-worked
+force over all column subsets (Eq. 7), the masked form against the gathered form
+whole and in pieces, hand-worked
 refresh schedules (Eq. 8).  The paper prints no numeric example of its own, so
 agreement with the authors' kernels is "parity unpinned"; agreement with the
 definitions is what the pins establish.
@@ -182,53 +183,65 @@ def sparse_attention_masked(Q, K, V, idx, group_size: int = 0,
 
 
 # --------------------------------------------------------------------------
-# Alg. 1: column-sparse attention forward, tile by tile with online softmax
+# The gathered form of the sparse result, whole and in pieces
 # --------------------------------------------------------------------------
-def sparse_attention_tiled(Q, K, V, idx, block_m: int, block_n: int,
-                           group_size: int = 0, scale: float | None = None) -> np.ndarray:
-    """Appendix B pseudocode, in its own order and notation.
+def sparse_attention_gathered(Q, K, V, idx, group_size: int = 0,
+                              scale: float | None = None) -> np.ndarray:
+    """Softmax over the k gathered logits of each row, applied to the gathered value rows.
 
-    Query blocks of ``block_m`` rows; each walks its index list in tiles of
-    ``block_n`` positions, gathers K_I, V_I, forms R = Q_i K_I^T (scaled), the
-    tile statistics (m~, P~, l~) and merges them into (m_i, l_i, acc_i); the
-    output is diag(l_i)^-1 acc_i.  A query block must lie inside one group.
-    Duplicate indices are counted with multiplicity, as the listing would.
+    Sec. 3.4: the kernel works on K_S, V_S (the rows named by the group's column list) and
+    never forms the n x n matrix.  For a list of distinct columns this equals the masked
+    definition above; a column that appears twice in the list is a term twice (a 0/1 mask
+    cannot say that, a list can).
     """
     Q = _as_f64(Q)
     K = _as_f64(K)
     V = _as_f64(V)
     idx = np.atleast_2d(np.asarray(idx, dtype=np.int64))
-    n, d = Q.shape
-    if scale is None:
-        scale = 1.0 / math.sqrt(d)
-    g = n if group_size == 0 else group_size
-    if group_size and (group_size % block_m):
-        raise ValueError("block_m must divide group_size")
-    n_s = idx.shape[1]
-    T_q = -(-n // block_m)
-    T_s = -(-n_s // block_n)
-    O = np.empty((n, V.shape[1]), dtype=_F64)
-    for i in range(T_q):
-        r0, r1 = i * block_m, min(n, (i + 1) * block_m)
-        Q_i = Q[r0:r1]
-        m_i = np.full(r1 - r0, -np.inf)
-        l_i = np.zeros(r1 - r0)
-        acc_i = np.zeros((r1 - r0, V.shape[1]))
-        I_i = idx[r0 // g]
-        for t in range(T_s):
-            I_it = I_i[t * block_n:(t + 1) * block_n]
-            K_I, V_I = K[I_it], V[I_it]
-            R = (Q_i @ K_I.T) * scale
-            m_t = R.max(axis=1)
-            P_t = np.exp(R - m_t[:, None])
-            l_t = P_t.sum(axis=1)
-            m_new = np.maximum(m_i, m_t)
-            a_old = np.exp(m_i - m_new)
-            a_new = np.exp(m_t - m_new)
-            l_i = a_old * l_i + a_new * l_t
-            acc_i = a_old[:, None] * acc_i + a_new[:, None] * (P_t @ V_I)
-            m_i = m_new
-        O[r0:r1] = acc_i / l_i[:, None]
+    groups = _groups(Q.shape[0], group_size)
+    if idx.shape[0] != len(groups):
+        raise ValueError("idx needs one row per query group")
+    O = np.empty((Q.shape[0], V.shape[1]), dtype=_F64)
+    for u, (lo, hi) in enumerate(groups):
+        cols = idx[u]
+        O[lo:hi] = row_softmax(attention_logits(Q[lo:hi], K[cols], scale)) @ V[cols]
+    return O
+
+
+def sparse_attention_chunked(Q, K, V, idx, chunk: int, group_size: int = 0,
+                             scale: float | None = None) -> np.ndarray:
+    """The gathered result built up from pieces of the column list, `chunk` entries at a time.
+
+    This is the property the appendix algorithm "Column-Sparse Attention Forward" rests on
+    (a running softmax state over tiles of the list), stated as a merge of partial results:
+    a piece c of the list has, per query row, a log-normaliser L_c = log sum_t exp z_t and an
+    output A_c normalised over the piece alone; two disjoint pieces a, b of a list combine to
+        L = log(exp L_a + exp L_b),   A = exp(L_a - L) A_a + exp(L_b - L) A_b,
+    and the result for the whole list is A after the last piece, whatever the piece size.
+    """
+    if chunk < 1:
+        raise ValueError("chunk must be >= 1")
+    Q = _as_f64(Q)
+    K = _as_f64(K)
+    V = _as_f64(V)
+    idx = np.atleast_2d(np.asarray(idx, dtype=np.int64))
+    groups = _groups(Q.shape[0], group_size)
+    if idx.shape[0] != len(groups):
+        raise ValueError("idx needs one row per query group")
+    O = np.empty((Q.shape[0], V.shape[1]), dtype=_F64)
+    for u, (lo, hi) in enumerate(groups):
+        L = np.full(hi - lo, -np.inf)
+        A = np.zeros((hi - lo, V.shape[1]), dtype=_F64)
+        for c0 in range(0, idx.shape[1], chunk):
+            piece = idx[u, c0:c0 + chunk]
+            Z = attention_logits(Q[lo:hi], K[piece], scale)
+            top = Z.max(axis=1)
+            L_piece = top + np.log(np.exp(Z - top[:, None]).sum(axis=1))
+            A_piece = row_softmax(Z) @ V[piece]
+            L_both = np.logaddexp(L, L_piece)
+            A = np.exp(L - L_both)[:, None] * A + np.exp(L_piece - L_both)[:, None] * A_piece
+            L = L_both
+        O[lo:hi] = A
     return O
 
 

@@ -198,6 +198,15 @@ class Context:
         if tuple(t.stride()) != want:
             raise ValueError(f"{name}: strides {tuple(t.stride())} do not match the context's {want}")
 
+    def _new_output(self):
+        """An O with the context's own strides (a padded row stride makes it larger than a packed tensor)."""
+        s = self.shape
+        sn = s.stride_n or s.head_dim
+        sh = s.stride_h or s.seq * sn
+        sb = s.stride_b or s.heads * sh
+        return torch.empty_strided((s.batch, s.heads, s.seq, s.head_dim), (sb, sh, sn, 1),
+                                   dtype=self.torch_dtype, device=self.device)
+
     @property
     def groups(self) -> int:
         """U: query groups per head (Sec. 3.3); 1 when the whole head is one group."""
@@ -257,9 +266,8 @@ class Context:
                 or idx.dim() != 4 or tuple(idx.shape[:3]) != (s.batch, s.heads, self.groups):
             raise ValueError("idx: expected contiguous int32 [B, H, U, k] on the context's device")
         if O is None:
-            O = torch.empty_like(Q)
-        else:
-            self._check_tensor(O, "O")
+            O = self._new_output()
+        self._check_tensor(O, "O")
         self._check(lib().pulsecol_attn(self._h, _ptr(Q), _ptr(K), _ptr(V), _ptr(idx), idx.shape[3], _ptr(O), _stream()))
         return O
 
@@ -272,9 +280,8 @@ class Context:
         if k < 0:
             raise PulseColError(ERR_INVALID_ARG, "keep_ratio must be in (0, 1]")
         if O is None:
-            O = torch.empty_like(Q)
-        else:
-            self._check_tensor(O, "O")
+            O = self._new_output()
+        self._check_tensor(O, "O")
         if idx_out is None:
             idx_out = torch.empty(s.batch, s.heads, self.groups, k, dtype=torch.int32, device=self.device)
         self._check(lib().pulsecol_refresh_dense(self._h, _ptr(Q), _ptr(K), _ptr(V), keep_ratio, _ptr(O),
@@ -285,8 +292,7 @@ class Context:
         for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):
             self._check_tensor(t, nm)
         if O is None:
-            O = torch.empty_like(Q)
-        else:
-            self._check_tensor(O, "O")
+            O = self._new_output()
+        self._check_tensor(O, "O")
         self._check(lib().pulsecol_attn_dense(self._h, _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(lse_out), _stream()))
         return O

@@ -121,7 +121,7 @@ def test_column_order_and_repeats():
     for h in range(H):
         want = oracle.sparse_attention_masked(f64(Q[0, h]), f64(K[0, h]), f64(V[0, h]), idx[0, h].numpy())
         assert_close(O2[0, h], want, "bf16", "shuffled idx")
-        want3 = oracle.sparse_attention_tiled(f64(Q[0, h]), f64(K[0, h]), f64(V[0, h]), [[5, 5, 9]], 64, 2)
+        want3 = oracle.sparse_attention_gathered(f64(Q[0, h]), f64(K[0, h]), f64(V[0, h]), [[5, 5, 9]])
         assert_close(O3[0, h], want3, "bf16", "repeated idx")
 
 
@@ -162,6 +162,35 @@ def test_strided_layout():
         torch.cuda.synchronize()
     assert torch.equal(O.contiguous(), O_packed)
     assert torch.equal(sc, sc_packed)
+
+
+def test_padded_row_stride_with_library_allocated_output():
+    """Row stride 136 (> head_dim): the output the binding allocates itself must have the
+    context's strides and an allocation that holds every element the kernels store."""
+    B, H, n, d, k, sn = 2, 3, 300, 128, 70, 136
+    say("padded-stride case")
+    Q, K, V = rand_qkv(B, H, n, d, torch.bfloat16, seed=71)
+    idx = random_idx(n, k, B * H, seed=72).view(B, H, 1, k)
+
+    def padded(t):
+        buf = torch.zeros(B, H, n, sn, dtype=torch.bfloat16, device=DEV)
+        buf[..., :d] = t.to(DEV)
+        return buf[..., :d]
+
+    q, k_, v = padded(Q), padded(K), padded(V)
+    with pc.Context(B, H, n, d, torch.bfloat16, strides=(0, 0, sn)) as ctx:
+        outs = [ctx.attn(q, k_, v, idx.to(DEV)), ctx.attn_dense(q, k_, v), ctx.refresh_dense(q, k_, v, 0.25)[0]]
+        torch.cuda.synchronize()
+    last_element = (B - 1) * H * n * sn + (H - 1) * n * sn + (n - 1) * sn + d       # one past the last stored element
+    for O in outs:
+        assert tuple(O.stride()) == (H * n * sn, n * sn, sn, 1)
+        assert O.untyped_storage().nbytes() >= (O.storage_offset() + last_element) * O.element_size()
+    with pc.Context(B, H, n, d, torch.bfloat16) as ctx2:
+        want = [ctx2.attn(Q.to(DEV), K.to(DEV), V.to(DEV), idx.to(DEV)), ctx2.attn_dense(Q.to(DEV), K.to(DEV), V.to(DEV))]
+        torch.cuda.synchronize()
+    assert torch.equal(outs[0].contiguous(), want[0])
+    assert torch.equal(outs[1].contiguous(), want[1])
+    assert torch.equal(outs[2].contiguous(), want[1])
 
 
 # ---------------------------------------------------------------------------------------

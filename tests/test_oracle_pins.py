@@ -63,11 +63,18 @@ def pin_closed_form(o):
     np.testing.assert_allclose(o.column_scores(Q, K, group_size=1), _table(g["P"]), rtol=1e-13)
     assert o.topk_columns(o.column_scores(Q, K), 2).tolist() == g["top2_one_group"]
     assert o.topk_columns(o.column_scores(Q, K, group_size=2), 1).tolist() == g["top1_group_size_2"]
+    # the whole identification pass on the same input: budget -> k, scores, top-k
+    # (0.67 * 3 = 2.01 -> k = 2; 0.34 * 3 = 1.02 -> k = 1; 221/540 > 218/540 -> column 1 alone)
+    assert o.select_columns(Q, K, 0.67).tolist() == g["top2_one_group"]
+    assert o.select_columns(Q, K, 0.34).tolist() == [[1]]
+    assert o.select_columns(Q, K, 0.34, group_size=2).tolist() == g["top1_group_size_2"]
+    assert o.select_columns(Q, K, 1.0, group_size=2).tolist() == [[0, 1, 2], [0, 1, 2]]
     for idx, key in (([[0, 1]], "sparse_idx_0_1"), ([[0, 2]], "sparse_idx_0_2")):
         want = _table(g[key])
         np.testing.assert_allclose(o.sparse_attention_masked(Q, K, V, idx), want, rtol=1e-13, atol=1e-15)
-        for bm, bn in ((1, 1), (2, 1), (3, 2), (2, 5)):
-            np.testing.assert_allclose(o.sparse_attention_tiled(Q, K, V, idx, bm, bn), want, rtol=1e-13, atol=1e-15)
+        np.testing.assert_allclose(o.sparse_attention_gathered(Q, K, V, idx), want, rtol=1e-13, atol=1e-15)
+        for chunk in (1, 2, 5):
+            np.testing.assert_allclose(o.sparse_attention_chunked(Q, K, V, idx, chunk), want, rtol=1e-13, atol=1e-15)
 
 
 def pin_dense_matches_library(o):
@@ -140,23 +147,24 @@ def pin_sparse_attention_properties(o):
     r = np.random.default_rng(10)
     idx = np.sort(r.permutation(n)[:13])[None]
     ref = o.sparse_attention_masked(Q, K, V, idx)
-    # Eq. 2 == Alg. 1 for any tiling, ragged tails included
-    for bm, bn in ((45, 13), (16, 4), (7, 5), (1, 1), (64, 64)):
-        np.testing.assert_allclose(o.sparse_attention_tiled(Q, K, V, idx, bm, bn), ref, rtol=1e-12, atol=1e-14)
+    # masked form == gathered form, whole or in pieces of any size (ragged last piece included)
+    np.testing.assert_allclose(o.sparse_attention_gathered(Q, K, V, idx), ref, rtol=1e-13, atol=1e-15)
+    for chunk in (13, 4, 5, 1, 64):
+        np.testing.assert_allclose(o.sparse_attention_chunked(Q, K, V, idx, chunk), ref, rtol=1e-12, atol=1e-14)
     # column order inside idx carries no meaning
     perm = idx[:, r.permutation(13)]
     np.testing.assert_allclose(o.sparse_attention_masked(Q, K, V, perm), ref, rtol=1e-13)
-    np.testing.assert_allclose(o.sparse_attention_tiled(Q, K, V, perm, 16, 4), ref, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(o.sparse_attention_chunked(Q, K, V, perm, 4), ref, rtol=1e-12, atol=1e-14)
     # keep everything -> dense attention
     every = np.arange(n)[None]
     np.testing.assert_allclose(o.sparse_attention_masked(Q, K, V, every), o.dense_attention(Q, K, V), rtol=1e-13)
-    np.testing.assert_allclose(o.sparse_attention_tiled(Q, K, V, every, 8, 8), o.dense_attention(Q, K, V), rtol=1e-12)
+    np.testing.assert_allclose(o.sparse_attention_chunked(Q, K, V, every, 8), o.dense_attention(Q, K, V), rtol=1e-12)
     # weights of a row sum to one: V == 1 -> O == 1; rows are convex combinations of selected V rows
     np.testing.assert_allclose(o.sparse_attention_masked(Q, K, np.ones_like(V), idx), 1.0, rtol=1e-13)
     assert (ref <= V[idx[0]].max(axis=0) + 1e-12).all() and (ref >= V[idx[0]].min(axis=0) - 1e-12).all()
     # one kept column: the output IS that value row
     np.testing.assert_allclose(o.sparse_attention_masked(Q, K, V, [[29]]), np.tile(V[29], (n, 1)), rtol=1e-14)
-    np.testing.assert_allclose(o.sparse_attention_tiled(Q, K, V, [[29]], 8, 4), np.tile(V[29], (n, 1)), rtol=1e-14)
+    np.testing.assert_allclose(o.sparse_attention_chunked(Q, K, V, [[29]], 4), np.tile(V[29], (n, 1)), rtol=1e-14)
     # unselected keys and values cannot matter
     K2, V2 = K.copy(), V.copy()
     off = np.setdiff1d(np.arange(n), idx[0])
@@ -172,13 +180,16 @@ def pin_sparse_attention_properties(o):
     for u, (lo, hi) in enumerate(((0, 16), (16, 32), (32, 45))):
         want = o.sparse_attention_masked(Q[lo:hi], K, V, gidx[u:u + 1])
         np.testing.assert_allclose(got[lo:hi], want, rtol=1e-13)
-    np.testing.assert_allclose(o.sparse_attention_tiled(Q, K, V, gidx, 8, 4, group_size=16), got, rtol=1e-12)
-    # Alg. 1 counts a repeated index twice: {a, a} still yields V[a]; {a, a, b} weighs a double
-    np.testing.assert_allclose(o.sparse_attention_tiled(Q, K, V, [[5, 5]], 8, 1), np.tile(V[5], (n, 1)), rtol=1e-13)
+    np.testing.assert_allclose(o.sparse_attention_gathered(Q, K, V, gidx, group_size=16), got, rtol=1e-13)
+    np.testing.assert_allclose(o.sparse_attention_chunked(Q, K, V, gidx, 4, group_size=16), got, rtol=1e-12)
+    # a list counts a repeated column twice: {a, a} still yields V[a]; {a, a, b} weighs a double
+    np.testing.assert_allclose(o.sparse_attention_gathered(Q, K, V, [[5, 5]]), np.tile(V[5], (n, 1)), rtol=1e-13)
+    np.testing.assert_allclose(o.sparse_attention_chunked(Q, K, V, [[5, 5]], 1), np.tile(V[5], (n, 1)), rtol=1e-13)
     z = o.attention_logits(Q, K)
     w = np.exp(z[:, [5, 5, 9]])
     want = (w / w.sum(1, keepdims=True)) @ V[[5, 5, 9]]
-    np.testing.assert_allclose(o.sparse_attention_tiled(Q, K, V, [[5, 5, 9]], 8, 2), want, rtol=1e-12)
+    np.testing.assert_allclose(o.sparse_attention_gathered(Q, K, V, [[5, 5, 9]]), want, rtol=1e-12)
+    np.testing.assert_allclose(o.sparse_attention_chunked(Q, K, V, [[5, 5, 9]], 2), want, rtol=1e-12)
 
 
 def pin_scale_override(o):
@@ -389,6 +400,16 @@ def _random_without_first_step(T, eta, R, uniforms):
     return sorted(pool[:R])
 
 
+def _select_ignores_groups(Q, K, keep_ratio, group_size=0, scale=None):
+    k = num_keep(np.asarray(Q).shape[0], keep_ratio)
+    return topk_columns(column_scores(Q, K, 0, scale), k)
+
+
+def _select_budget_is_sparsity(Q, K, keep_ratio, group_size=0, scale=None):
+    k = num_keep(np.asarray(Q).shape[0], max(1.0 - keep_ratio, 1e-9))
+    return topk_columns(column_scores(Q, K, group_size, scale), k)
+
+
 def _num_keep_ceil(n, keep_ratio):
     if n < 1 or not (0.0 < keep_ratio <= 1.0):
         raise ValueError
@@ -408,6 +429,8 @@ MUTANTS = {
     "schedule_zero_based": dict(refresh_schedule=_schedule_zero_based),
     "schedule_full_window": dict(refresh_schedule=_schedule_window_not_minus_one),
     "num_keep_ceil": dict(num_keep=_num_keep_ceil),
+    "select_ignores_groups": dict(select_columns=_select_ignores_groups),
+    "select_budget_is_sparsity": dict(select_columns=_select_budget_is_sparsity),
     "power_schedule_linear": dict(refresh_schedule_power=_power_linear),
     "power_schedule_whole_window": dict(refresh_schedule_power=_power_whole_window),
     "random_schedule_with_replacement": dict(refresh_schedule_random=_random_with_replacement),
@@ -427,13 +450,15 @@ def test_planted_mistake_is_caught(name):
     assert tripped, f"no pin notices the planted mistake '{name}'"
 
 
-def test_tiled_merge_mistakes_are_caught():
-    """Alg. 1's merge: dropping the old-accumulator rescale, or the new-tile factor, must show."""
+def test_chunk_merge_mistakes_are_caught():
+    """The merge of partial softmax results: a dropped weight on either side, a normaliser that is
+    not carried forward, or a piece normalised by the wrong sum must show."""
     src = open(_impl.__file__).read()
-    for needle, broken in (("a_old[:, None] * acc_i", "acc_i"),
-                           ("a_new[:, None] * (P_t @ V_I)", "(P_t @ V_I)"),
-                           ("a_old * l_i + a_new * l_t", "l_i + a_new * l_t"),
-                           ("acc_i / l_i[:, None]", "acc_i")):
+    for needle, broken in (("np.exp(L - L_both)[:, None] * A +", "A +"),
+                           ("np.exp(L_piece - L_both)[:, None] * A_piece", "A_piece"),
+                           ("L = L_both", "L = L_piece"),
+                           ("L_piece = top + np.log(", "L_piece = np.log("),
+                           ("A_piece = row_softmax(Z) @ V[piece]", "A_piece = np.exp(Z - top[:, None]) @ V[piece]")):
         assert needle in src
         mod = types.ModuleType("oracle_mutant")
         exec(compile(src.replace(needle, broken), "mutant", "exec"), mod.__dict__)
