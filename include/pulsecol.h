@@ -92,14 +92,19 @@ typedef struct {
     int64_t kv_stride_b; /* element strides of K and V (0 = packed [B, kv_heads, n, d]; with       */
     int64_t kv_stride_h; /* kv_heads == 0 and all three 0: the strides of Q).  Same alignment and  */
     int64_t kv_stride_n; /* size rules as stride_b/h/n                                             */
+    double max_keep_ratio; /* the largest keep_ratio pulsecol_select / pulsecol_refresh_dense will be
+                         * called with on this context: sizes the cached pattern (Sec. 3.3: the
+                         * pattern is stored between refreshes) at pulsecol_num_keep(seq,
+                         * max_keep_ratio) columns per group.  0 = 1.0 (room for every column)     */
 } pulsecol_shape;
 
 /* Host-only check of a shape against the rules above.  Touches no device. */
 PULSECOL_API pulsecol_status pulsecol_validate_shape(const pulsecol_shape* shape);
 
 /* Create a context on HIP device `device`: copies `shape`, allocates the scratch
- * (4*B*H*seq bytes of row statistics, 4*B*H*U*seq bytes of scores, 4*B*H*U*seq bytes for the
- * cached pattern, a few KB of counters).  *out is set only on PULSECOL_OK. */
+ * (4*B*H*seq bytes of row statistics, 4*B*H*U*seq bytes of scores, 4*B*H*U*k_max bytes for the
+ * cached pattern with k_max = pulsecol_num_keep(seq, max_keep_ratio), 256 bytes of counters).
+ * *out is set only on PULSECOL_OK. */
 PULSECOL_API pulsecol_status pulsecol_create(pulsecol_ctx** out, const pulsecol_shape* shape, int device);
 
 /* Validation mode (off by default; on at creation if the environment variable
@@ -122,6 +127,7 @@ PULSECOL_API int32_t pulsecol_num_keep(int32_t seq, double keep_ratio);
  *                 attention matrix, keep the k = pulsecol_num_keep(seq, keep_ratio) highest
  *                 columns of every group (equal scores: lower column index wins), write them
  *                 ascending to idx_out[B, H, U, k] and cache them in the context.
+ *                 PULSECOL_ERR_INVALID_ARG if k exceeds what max_keep_ratio left room for.
  *   refresh == 0: Q and K are ignored (may be NULL); the cached pattern is copied to idx_out.
  *                 PULSECOL_ERR_NO_PATTERN if nothing is cached or k differs. */
 PULSECOL_API pulsecol_status pulsecol_select(pulsecol_ctx* ctx, const void* Q, const void* K, double keep_ratio,

@@ -738,18 +738,37 @@ struct AttnWave {
 // Work distribution.  The grid is a fixed set of workgroups (as many as fit the chip at once)
 // that take query blocks from eight queues, one per XCD: queue y holds the query blocks of the
 // heads 8*hh + y in order, so that at any time an XCD works on one or two heads whose gathered
-// K/V rows fit its L2, and a workgroup takes from the queue of the XCD it runs on (consecutive
-// workgroup ids are dealt round-robin over the XCDs).  The XCDs of one chip do not run at the
-// same speed (a few percent apart under this load): a workgroup whose queue is empty goes on
-// with the next non-empty one instead of idling until the slowest XCD is done.
-// Counters: work[y] = next item of queue y, work[8] = workgroups that have finished.  All are
-// zero when the kernel starts, and the last workgroup to finish zeroes them again.
+// K/V rows fit its L2, and a workgroup takes from the queue of the XCD it runs on (read from the
+// hardware's XCC id register, so nothing is assumed about the order in which workgroups are dealt
+// to the XCDs).  The XCDs of one chip do not run at the same speed (a few percent apart under this
+// load): a workgroup whose queue is empty goes on with the next non-empty one instead of idling
+// until the slowest XCD is done.
+// Counters: work[y] = (launch stamp << 32) | next item of queue y.  The stamp is a number the host
+// gives every launch on a context; a counter that carries another stamp is whatever an earlier
+// launch left behind (finished, aborted, or never run) and is restarted by the first workgroup
+// that notices.  So a launch depends on no state of the launches before it, and nothing has to be
+// cleared between launches.
 struct WorkQueues {
-    int32_t* work;
+    unsigned long long* work;
+    uint32_t stamp;
     int bh_total, nqb;
     __device__ __forceinline__ int items(int y) const { return y < bh_total ? ((bh_total - y + 7) >> 3) * nqb : 0; }
-    static __device__ __forceinline__ int take(int32_t* counter) {
-        return __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __device__ __forceinline__ int take(int q) const {
+        unsigned long long* const counter = work + q;
+        unsigned long long v = __hip_atomic_fetch_add(counter, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        while ((uint32_t)(v >> 32) != stamp) {
+            unsigned long long cur = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((uint32_t)(cur >> 32) == stamp) {
+                v = __hip_atomic_fetch_add(counter, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                continue;
+            }
+            // restart the counter at item 1 and keep item 0 (fails if another workgroup was faster, or
+            // has just added to the stale value: look again)
+            const unsigned long long fresh = ((unsigned long long)stamp << 32) | 1ull;
+            if (__hip_atomic_compare_exchange_strong(counter, &cur, fresh, __ATOMIC_RELAXED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+                return 0;
+        }
+        return (int)(uint32_t)v;
     }
     // One thread: item j taken from queue q is good, or else the first item that the following
     // queues still have; j = -1 when every queue has been found empty.
@@ -757,10 +776,13 @@ struct WorkQueues {
         while (j >= items(q)) {
             q = (q + 1) & 7;
             if (q == home) { j = -1; return; }
-            j = take(work + q);
+            j = take(q);
         }
     }
 };
+
+// the XCD this wave runs on: bits 3:0 of the XCC id hardware register
+__device__ __forceinline__ int xcc_id() { return __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 7; }
 
 template <int D, int MODE>
 __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
@@ -788,13 +810,13 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     asm volatile("" : : "s"(p.q), "s"(p.k), "s"(p.v), "s"(p.o), "s"(p.idx), "s"(p.lse), "s"(p.lse_base2),
                          "s"(p.td.sb), "s"(p.td.sh), "s"(p.td.sn), "s"(p.td_kv.sb), "s"(p.td_kv.sh), "s"(p.td_kv.sn),
                          "s"(p.kv_heads), "s"(p.batch), "s"(p.heads), "s"(p.n), "s"(p.ns), "s"(p.groups),
-                         "s"(p.group_size), "s"(p.scale), "s"(p.work));
+                         "s"(p.group_size), "s"(p.scale), "s"(p.work), "s"(p.work_stamp));
     const int nqb = (p.n + BM - 1) / BM;
-    const WorkQueues queues{p.work, p.batch * p.heads, nqb};
+    const WorkQueues queues{p.work, p.work_stamp, p.batch * p.heads, nqb};
     __shared__ int32_t lds_item[2];          // the workgroup's next item: queue, index in the queue
-    const int home = blockIdx.x & 7;
+    const int home = xcc_id();
     if (threadIdx.x == 0) {
-        int q = home, j = WorkQueues::take(p.work + home);
+        int q = home, j = queues.take(home);
         queues.settle(home, q, j);
         lds_item[0] = q;
         lds_item[1] = j;
@@ -1039,7 +1061,7 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     // that have nothing left to do, and early enough for the answer to be there when the output
     // tile has been staged (nothing else is in flight in between).
     int early_j = 0;
-    if (threadIdx.x == 0) early_j = WorkQueues::take(p.work + cur_q);
+    if (threadIdx.x == 0) early_j = queues.take(cur_q);
     w.general_step(nhalf - 1, lds_k, lds_v, SB, SA, PA, PB);
 
     w.pv_all(lds_v + (HAS_V ? (((nhalf - 1) >> 1) % NBUF_V) * TILE_BYTES : 0), (nhalf - 1) & 1, PB);
@@ -1144,14 +1166,6 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     }
   }
 
-    // ---- the last workgroup to get here leaves the counters as it found them
-    if (threadIdx.x == 0) {
-        const int done = __hip_atomic_fetch_add(p.work + 8, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        if (done == (int)gridDim.x - 1) {
-#pragma unroll
-            for (int y = 0; y <= 8; ++y) __hip_atomic_store(p.work + y, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
 }
 
 // workgroups that one CU holds at a time (LDS and registers): the row pass fits two

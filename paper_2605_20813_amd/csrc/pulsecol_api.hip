@@ -26,8 +26,10 @@ struct pulsecol_ctx {
     float* scores = nullptr;        // [B*H*U, n]
     int32_t* cached_idx = nullptr;  // [B*H*U, cached_k]
     int32_t cached_k = 0;           // 0 = nothing cached
+    int32_t k_max = 0;              // columns per group the cache has room for
     int32_t* bad_count = nullptr;   // one device counter for the validation mode (first word of a small block)
-    int32_t* work = nullptr;        // work counters of the bf16 attention kernels (same block), zero between launches
+    unsigned long long* work = nullptr;   // work counters of the bf16 attention kernels (same block)
+    uint32_t work_stamp = 0;        // stamp of the last launch that used them (every launch takes the next one)
     bool validate = false;          // check column numbers in front of every pulsecol_attn
     std::string last_error;
 };
@@ -72,6 +74,7 @@ pulsecol_status check_shape(const pulsecol_shape* s, std::string* why) {
     if (s->batch < 1 || s->heads < 1 || s->seq < 1) { *why = "batch, heads and seq must be >= 1"; return PULSECOL_ERR_INVALID_ARG; }
     if (s->group_size < 0) { *why = "group_size must be >= 0"; return PULSECOL_ERR_INVALID_ARG; }
     if (s->scale < 0.f || !std::isfinite(s->scale)) { *why = "scale must be finite and >= 0"; return PULSECOL_ERR_INVALID_ARG; }
+    if (!(s->max_keep_ratio >= 0.0) || !(s->max_keep_ratio <= 1.0)) { *why = "max_keep_ratio must be 0 or in (0, 1]"; return PULSECOL_ERR_INVALID_ARG; }
     if (s->stride_b < 0 || s->stride_h < 0 || s->stride_n < 0) { *why = "strides must be >= 0"; return PULSECOL_ERR_INVALID_ARG; }
     if (s->dtype != PULSECOL_BF16 && s->dtype != PULSECOL_F32) { *why = "dtype must be PULSECOL_BF16 or PULSECOL_F32"; return PULSECOL_ERR_UNSUPPORTED; }
     if (s->head_dim != 64 && s->head_dim != 128) { *why = "head_dim must be 64 or 128"; return PULSECOL_ERR_UNSUPPORTED; }
@@ -110,6 +113,26 @@ pulsecol_status check_shape(const pulsecol_shape* s, std::string* why) {
     return PULSECOL_OK;
 }
 
+// the fields of a context that follow from the shape alone (host only)
+void derive_from_shape(pulsecol_ctx* c, const pulsecol_shape* shape, int device) {
+    c->shape = *shape;
+    c->device = device;
+    c->groups = (shape->group_size == 0 || shape->group_size >= shape->seq)
+                    ? 1 : (shape->seq + shape->group_size - 1) / shape->group_size;
+    c->scale = shape->scale > 0.f ? shape->scale : 1.0f / std::sqrt((float)shape->head_dim);
+    c->td.sn = shape->stride_n ? shape->stride_n : shape->head_dim;
+    c->td.sh = shape->stride_h ? shape->stride_h : (int64_t)shape->seq * c->td.sn;
+    c->td.sb = shape->stride_b ? shape->stride_b : (int64_t)shape->heads * c->td.sh;
+    c->kv_heads = shape->kv_heads ? shape->kv_heads : shape->heads;
+    if (kv_follows_q(shape)) {
+        c->td_kv = c->td;
+    } else {
+        c->td_kv.sn = shape->kv_stride_n ? shape->kv_stride_n : shape->head_dim;
+        c->td_kv.sh = shape->kv_stride_h ? shape->kv_stride_h : (int64_t)shape->seq * c->td_kv.sn;
+        c->td_kv.sb = shape->kv_stride_b ? shape->kv_stride_b : (int64_t)c->kv_heads * c->td_kv.sh;
+    }
+}
+
 struct DeviceGuard {
     int prev = -1;
     bool switched = false;
@@ -124,7 +147,7 @@ struct DeviceGuard {
     ~DeviceGuard() { if (switched) (void)hipSetDevice(prev); }
 };
 
-pulsecol::AttnParams attn_params(const pulsecol_ctx* c, const void* Q, const void* K, const void* V, void* O,
+pulsecol::AttnParams attn_params(pulsecol_ctx* c, const void* Q, const void* K, const void* V, void* O,
                                  const int32_t* idx, int32_t ns, float* lse, int lse_base2) {
     pulsecol::AttnParams p{};
     p.q = Q; p.k = K; p.v = V; p.o = O; p.idx = idx; p.lse = lse; p.lse_base2 = lse_base2;
@@ -133,6 +156,8 @@ pulsecol::AttnParams attn_params(const pulsecol_ctx* c, const void* Q, const voi
     p.groups = c->groups; p.group_size = c->shape.group_size;
     p.scale = c->scale;
     p.work = c->work;
+    if (++c->work_stamp == 0) c->work_stamp = 1;       // freshly cleared counters carry stamp 0
+    p.work_stamp = c->work_stamp;
     return p;
 }
 
@@ -225,22 +250,7 @@ pulsecol_status pulsecol_create(pulsecol_ctx** out, const pulsecol_shape* shape,
 
     pulsecol_ctx* c = new (std::nothrow) pulsecol_ctx();
     if (!c) return fail(nullptr, PULSECOL_ERR_OOM, "pulsecol_create: host allocation failed");
-    c->shape = *shape;
-    c->device = device;
-    c->groups = (shape->group_size == 0 || shape->group_size >= shape->seq)
-                    ? 1 : (shape->seq + shape->group_size - 1) / shape->group_size;
-    c->scale = shape->scale > 0.f ? shape->scale : 1.0f / std::sqrt((float)shape->head_dim);
-    c->td.sn = shape->stride_n ? shape->stride_n : shape->head_dim;
-    c->td.sh = shape->stride_h ? shape->stride_h : (int64_t)shape->seq * c->td.sn;
-    c->td.sb = shape->stride_b ? shape->stride_b : (int64_t)shape->heads * c->td.sh;
-    c->kv_heads = shape->kv_heads ? shape->kv_heads : shape->heads;
-    if (kv_follows_q(shape)) {
-        c->td_kv = c->td;
-    } else {
-        c->td_kv.sn = shape->kv_stride_n ? shape->kv_stride_n : shape->head_dim;
-        c->td_kv.sh = shape->kv_stride_h ? shape->kv_stride_h : (int64_t)shape->seq * c->td_kv.sn;
-        c->td_kv.sb = shape->kv_stride_b ? shape->kv_stride_b : (int64_t)c->kv_heads * c->td_kv.sh;
-    }
+    derive_from_shape(c, shape, device);
 
     DeviceGuard guard(device);
     if (guard.err != hipSuccess) { delete c; return fail_hip(nullptr, guard.err, "pulsecol_create: hipSetDevice"); }
@@ -248,11 +258,12 @@ pulsecol_status pulsecol_create(pulsecol_ctx** out, const pulsecol_shape* shape,
     const size_t row_bytes = (size_t)shape->seq * sizeof(float);
     hipError_t e1 = hipMalloc((void**)&c->lse, rows * row_bytes);
     hipError_t e2 = e1 == hipSuccess ? hipMalloc((void**)&c->scores, rows * c->groups * row_bytes) : e1;
-    hipError_t e3 = e2 == hipSuccess ? hipMalloc((void**)&c->cached_idx, rows * c->groups * row_bytes) : e2;
-    static_assert(64 + pulsecol::kWorkCounters * sizeof(int32_t) <= 256, "counter block");
+    c->k_max = shape->max_keep_ratio > 0.0 ? pulsecol_num_keep(shape->seq, shape->max_keep_ratio) : shape->seq;
+    hipError_t e3 = e2 == hipSuccess ? hipMalloc((void**)&c->cached_idx, rows * c->groups * (size_t)c->k_max * sizeof(int32_t)) : e2;
+    static_assert(64 + pulsecol::kWorkCounters * sizeof(unsigned long long) <= 256, "counter block");
     if (e3 == hipSuccess) e3 = hipMalloc((void**)&c->bad_count, 256);
     if (e3 == hipSuccess) e3 = hipMemset(c->bad_count, 0, 256);
-    if (e3 == hipSuccess) c->work = c->bad_count + 16;
+    if (e3 == hipSuccess) c->work = reinterpret_cast<unsigned long long*>(c->bad_count + 16);
     if (e3 != hipSuccess) {
         if (c->lse) (void)hipFree(c->lse);
         if (c->scores) (void)hipFree(c->scores);
@@ -316,6 +327,7 @@ pulsecol_status pulsecol_select(pulsecol_ctx* ctx, const void* Q, const void* K,
     if (!idx_out) return fail(ctx, PULSECOL_ERR_INVALID_ARG, "pulsecol_select: idx_out is NULL");
     const int32_t k = pulsecol_num_keep(ctx->shape.seq, keep_ratio);
     if (k < 0) return fail(ctx, PULSECOL_ERR_INVALID_ARG, "pulsecol_select: keep_ratio must be in (0, 1]");
+    if (k > ctx->k_max) return fail(ctx, PULSECOL_ERR_INVALID_ARG, "pulsecol_select: keep_ratio exceeds the context's max_keep_ratio");
     const size_t idx_bytes = (size_t)ctx->shape.batch * ctx->shape.heads * ctx->groups * (size_t)k * sizeof(int32_t);
     hipStream_t s = (hipStream_t)stream;
     if (!refresh) {
@@ -342,6 +354,7 @@ pulsecol_status pulsecol_refresh_dense(pulsecol_ctx* ctx, const void* Q, const v
     if (!idx_out) return fail(ctx, PULSECOL_ERR_INVALID_ARG, "pulsecol_refresh_dense: idx_out is NULL");
     const int32_t k = pulsecol_num_keep(ctx->shape.seq, keep_ratio);
     if (k < 0) return fail(ctx, PULSECOL_ERR_INVALID_ARG, "pulsecol_refresh_dense: keep_ratio must be in (0, 1]");
+    if (k > ctx->k_max) return fail(ctx, PULSECOL_ERR_INVALID_ARG, "pulsecol_refresh_dense: keep_ratio exceeds the context's max_keep_ratio");
     pulsecol_status st = check_ptrs(ctx, {Q, K, V, O}, "pulsecol_refresh_dense");
     if (st != PULSECOL_OK) return st;
     DeviceGuard guard(ctx->device);

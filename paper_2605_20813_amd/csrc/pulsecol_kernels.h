@@ -25,12 +25,14 @@ struct AttnParams {
     int32_t groups;          // U query groups per head (1 = the whole head)
     int32_t group_size;      // rows per group, a multiple of the kernel's query block (unused when U = 1)
     float scale;             // logit scale
-    // bf16 kernel with 256-row query blocks only: kWorkCounters ints of device memory, all zero between
-    // launches (the kernel leaves them so), through which its workgroups hand out the query blocks
-    int32_t* work;
+    // bf16 kernel with 256-row query blocks only: kWorkCounters 64-bit words of device memory through
+    // which its workgroups hand out the query blocks, and a stamp that differs from the one of the last
+    // launch that used the same words (any contents are fine: counters with another stamp are restarted)
+    unsigned long long* work;
+    uint32_t work_stamp;
 };
 
-constexpr int kWorkCounters = 16;
+constexpr int kWorkCounters = 8;
 
 struct ScoreParams {
     const void* q;

@@ -33,7 +33,8 @@ class Shape(ctypes.Structure):
                 ("dtype", c_int32), ("group_size", c_int32),
                 ("stride_b", c_int64), ("stride_h", c_int64), ("stride_n", c_int64),
                 ("scale", c_float), ("kv_heads", c_int32),
-                ("kv_stride_b", c_int64), ("kv_stride_h", c_int64), ("kv_stride_n", c_int64)]
+                ("kv_stride_b", c_int64), ("kv_stride_h", c_int64), ("kv_stride_n", c_int64),
+                ("max_keep_ratio", c_double)]
 
 
 class PulseColError(RuntimeError):
@@ -88,8 +89,9 @@ def _dtype_code(dtype) -> int:
 
 
 def make_shape(batch, heads, seq, head_dim, dtype, group_size=0, strides=(0, 0, 0), scale=0.0,
-               kv_heads=0, kv_strides=(0, 0, 0)) -> Shape:
-    return Shape(batch, heads, seq, head_dim, _dtype_code(dtype), group_size, *strides, scale, kv_heads, *kv_strides)
+               kv_heads=0, kv_strides=(0, 0, 0), max_keep_ratio=0.0) -> Shape:
+    return Shape(batch, heads, seq, head_dim, _dtype_code(dtype), group_size, *strides, scale, kv_heads, *kv_strides,
+                 max_keep_ratio)
 
 
 def validate_shape(shape: Shape) -> int:
@@ -148,8 +150,9 @@ class Context:
     """Owns one pulsecol_ctx.  Tensors are [B, H, n, d] on the context's device."""
 
     def __init__(self, batch, heads, seq, head_dim, dtype, group_size=0, strides=(0, 0, 0), scale=0.0, device=0,
-                 kv_heads=0, kv_strides=(0, 0, 0)):
-        self.shape = make_shape(batch, heads, seq, head_dim, dtype, group_size, strides, scale, kv_heads, kv_strides)
+                 kv_heads=0, kv_strides=(0, 0, 0), max_keep_ratio=0.0):
+        self.shape = make_shape(batch, heads, seq, head_dim, dtype, group_size, strides, scale, kv_heads, kv_strides,
+                                max_keep_ratio)
         self.torch_dtype = torch.bfloat16 if self.shape.dtype == BF16 else torch.float32
         self.device = torch.device("cuda", device)
         self._h = c_void_p()

@@ -97,6 +97,39 @@ def test_num_keep_matches_the_oracle_rule():
     assert pc.num_keep(8, float("nan")) == -1
 
 
+def test_num_keep_sweep_over_decimal_ratios():
+    """Every ratio with one to four decimal digits at the workloads' context lengths (and a few
+    lengths that are not powers of two): the library's floating-point floor against the oracle's
+    exact rational one (Sec. 3.1, sparsity-budget constraint)."""
+    from fractions import Fraction
+    L = pc.lib()
+    lengths = (256, 4096, 16384, 32768, 65536, 131072, 1000, 777, 12345)
+    bad = []
+    for digits in (1, 2, 3, 4):
+        den = 10 ** digits
+        for num in range(1, den + 1):
+            r = num / den
+            for n in lengths:
+                want = max(1, (Fraction(num, den) * n).__floor__())
+                got = L.pulsecol_num_keep(n, r)
+                if got != want:
+                    bad.append((n, r, got, want))
+    assert not bad, bad[:10]
+    # the oracle's own rule on a sample of the same grid (it reads the ratio as the decimal written)
+    for num in range(1, 10001, 37):
+        for n in (4096, 65536, 777):
+            assert oracle.num_keep(n, num / 10000) == max(1, (Fraction(num, 10000) * n).__floor__())
+
+
+def test_max_keep_ratio_is_validated():
+    args = dict(batch=1, heads=2, seq=512, head_dim=128, dtype=pc.BF16)
+    assert pc.validate_shape(pc.make_shape(**args, max_keep_ratio=0.25)) == pc.OK
+    assert pc.validate_shape(pc.make_shape(**args, max_keep_ratio=1.0)) == pc.OK
+    assert pc.validate_shape(pc.make_shape(**args, max_keep_ratio=1.5)) == pc.ERR_INVALID_ARG
+    assert pc.validate_shape(pc.make_shape(**args, max_keep_ratio=-0.1)) == pc.ERR_INVALID_ARG
+    assert pc.validate_shape(pc.make_shape(**args, max_keep_ratio=float("nan"))) == pc.ERR_INVALID_ARG
+
+
 def test_refresh_schedule_matches_golden_and_oracle():
     with open(os.path.join(ROOT, "tests", "golden", "eq8_schedules.json")) as f:
         for c in json.load(f)["cases"]:

@@ -350,6 +350,19 @@ def test_error_paths_on_device():
         assert torch.isfinite(O.float()).all()
     with pytest.raises(pc.PulseColError):
         pc.Context(1, 2, 256, 128, torch.bfloat16, device=99)
+    # a cache sized for keep <= 0.25: larger ratios are refused, smaller ones select and reuse as usual
+    with pc.Context(B, H, n, d, torch.bfloat16, max_keep_ratio=0.25) as small, pc.Context(B, H, n, d, torch.bfloat16) as full:
+        with pytest.raises(pc.PulseColError) as e:
+            small.select(Q, K, 0.5)
+        assert e.value.status == pc.ERR_INVALID_ARG and "max_keep_ratio" in str(e.value)
+        with pytest.raises(pc.PulseColError) as e:
+            small.refresh_dense(Q, K, V, 0.26)
+        assert e.value.status == pc.ERR_INVALID_ARG
+        a = small.select(Q, K, 0.25)
+        b = small.select(None, None, 0.25, refresh=False)
+        c = full.select(Q, K, 0.25)
+        torch.cuda.synchronize()
+        assert torch.equal(a, b) and torch.equal(a, c)
 
 
 # ---------------------------------------------------------------------------------------
