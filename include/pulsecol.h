@@ -159,6 +159,21 @@ PULSECOL_API pulsecol_status pulsecol_attn(pulsecol_ctx* ctx, const void* Q, con
 PULSECOL_API pulsecol_status pulsecol_attn_dense(pulsecol_ctx* ctx, const void* Q, const void* K, const void* V,
                                     void* O, float* lse_out, void* stream);
 
+/* pulsecol_select(refresh != 0) for callers that cannot allocate device memory or hold a context
+ * that did: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same computation and same idx_out[B, H, U, k] as pulsecol_select on a context of this shape, on
+ * the CURRENT device; nothing is cached (there is no context to cache in).  The row statistics,
+ * the scores and the work counters live in a static device array of 16 MiB + 256 bytes that each
+ * GPU the library runs on holds until the process ends; its address is looked up at the first call
+ * on a device.  Limit: batch * heads * seq * (1 + U) <= 4 * 2^20 fp32 words (exactly the 64K-context,
+ * 32-head, one-group-per-head shape), else PULSECOL_ERR_UNSUPPORTED with nothing launched.  The call
+ * issues no hipMalloc / hipFree / hipMemset, only kernel launches on `stream`.  All calls on one GPU
+ * share that GPU's array (it keeps the last call's contents; nothing in it has to start at zero):
+ * two calls that overlap in time on one GPU race, whatever their streams.  With no context, the
+ * text of a failure is read with pulsecol_last_error(NULL). */
+PULSECOL_API pulsecol_status pulsecol_select_noalloc(const pulsecol_shape* shape, const void* Q, const void* K,
+                                        double keep_ratio, int32_t* idx_out, void* stream);
+
 /* Refresh step that keeps the dense output (Sec. 3.3: at an identification or refresh step the
  * method "computes full attention" and collects the attention matrix): O = softmax(Q K^T *
  * scale) V as pulsecol_attn_dense, and idx_out / the cached pattern as

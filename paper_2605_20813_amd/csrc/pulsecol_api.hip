@@ -8,6 +8,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstdio>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -228,6 +229,39 @@ pulsecol_status run_topk(pulsecol_ctx* ctx, const float* scores, int32_t k, int3
     return PULSECOL_OK;
 }
 
+// ---- scratch of the entry point that allocates nothing (pulsecol_select_noalloc)
+// A file-scope device array, one copy per GPU, held until the process ends: 256 bytes of work
+// counters, then room for kNoallocFloats fp32 words (row log-sum-exp [B*H, n], then scores
+// [B*H*U, n]).  The array's name is only a host-side stand-in for the symbol; the address of a
+// device's copy comes from hipGetSymbolAddress, asked once per device with that device current.
+constexpr size_t kNoallocFloats = (size_t)4 << 20;                 // 16 MiB
+constexpr size_t kNoallocCounterBytes = 256;
+static __device__ __align__(256) unsigned char scratch[kNoallocCounterBytes + kNoallocFloats * sizeof(float)];
+
+struct NoallocDevice {
+    unsigned char* ptr = nullptr;     // this device's copy of `scratch`
+    uint32_t stamp = 0;               // stamp of the last launch that used its work counters
+};
+constexpr int kMaxDevices = 64;
+NoallocDevice g_noalloc[kMaxDevices];
+std::mutex g_noalloc_mutex;
+
+// the current device's copy of the scratch array (nullptr + *err on failure)
+NoallocDevice* noalloc_device(int dev, hipError_t* err) {
+    std::lock_guard<std::mutex> lock(g_noalloc_mutex);
+    NoallocDevice* d = &g_noalloc[dev];
+    if (d->ptr == nullptr) {
+        unsigned char* ptr = nullptr;
+        *err = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+        if (*err != hipSuccess || ptr == nullptr) {
+            if (*err == hipSuccess) *err = hipErrorInvalidSymbol;
+            return nullptr;
+        }
+        d->ptr = ptr;
+    }
+    return d;
+}
+
 }  // namespace
 
 extern "C" {
@@ -346,6 +380,42 @@ pulsecol_status pulsecol_select(pulsecol_ctx* ctx, const void* Q, const void* K,
     st = run_scores(ctx, Q, K, ctx->scores, s);
     if (st != PULSECOL_OK) return st;
     return select_from_scores(ctx, k, idx_out, s, "pulsecol_select");
+}
+
+pulsecol_status pulsecol_select_noalloc(const pulsecol_shape* shape, const void* Q, const void* K, double keep_ratio,
+                                        int32_t* idx_out, void* stream) {
+    std::string why;
+    pulsecol_status st = check_shape(shape, &why);
+    if (st != PULSECOL_OK) return fail(nullptr, st, "pulsecol_select_noalloc: " + why);
+    if (!idx_out) return fail(nullptr, PULSECOL_ERR_INVALID_ARG, "pulsecol_select_noalloc: idx_out is NULL");
+    const int32_t k = pulsecol_num_keep(shape->seq, keep_ratio);
+    if (k < 0) return fail(nullptr, PULSECOL_ERR_INVALID_ARG, "pulsecol_select_noalloc: keep_ratio must be in (0, 1]");
+    st = check_ptrs(nullptr, {Q, K}, "pulsecol_select_noalloc");
+    if (st != PULSECOL_OK) return st;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(nullptr, e, "pulsecol_select_noalloc: hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(nullptr, PULSECOL_ERR_UNSUPPORTED, "pulsecol_select_noalloc: device number out of range");
+
+    pulsecol_ctx c;                                   // host-side bookkeeping only; owns no device memory
+    derive_from_shape(&c, shape, dev);
+    const size_t rows = (size_t)shape->batch * shape->heads;
+    const size_t need = rows * (size_t)shape->seq * (1 + (size_t)c.groups);
+    if (need > kNoallocFloats)
+        return fail(nullptr, PULSECOL_ERR_UNSUPPORTED,
+                    "pulsecol_select_noalloc: batch*heads*seq*(1 + groups) = " + std::to_string(need) +
+                    " exceeds the static scratch of " + std::to_string(kNoallocFloats) + " fp32 words");
+    NoallocDevice* d = noalloc_device(dev, &e);
+    if (!d) return fail_hip(nullptr, e, "pulsecol_select_noalloc: hipGetSymbolAddress");
+    c.work = reinterpret_cast<unsigned long long*>(d->ptr);
+    c.work_stamp = d->stamp;                          // the launch takes the next stamp: stale counters restart themselves
+    c.lse = reinterpret_cast<float*>(d->ptr + kNoallocCounterBytes);
+    c.scores = c.lse + rows * (size_t)shape->seq;
+    st = run_scores(&c, Q, K, c.scores, (hipStream_t)stream);
+    d->stamp = c.work_stamp;
+    if (st == PULSECOL_OK) st = run_topk(&c, c.scores, k, idx_out, (hipStream_t)stream);
+    if (st != PULSECOL_OK) g_last_error = "pulsecol_select_noalloc: " + c.last_error;
+    return st;
 }
 
 pulsecol_status pulsecol_refresh_dense(pulsecol_ctx* ctx, const void* Q, const void* K, const void* V,

@@ -22,7 +22,7 @@ BF16, F32 = 0, 1
 EXPORTS = (
     "pulsecol_validate_shape", "pulsecol_create", "pulsecol_destroy", "pulsecol_set_validation", "pulsecol_num_keep",
     "pulsecol_select", "pulsecol_scores", "pulsecol_topk", "pulsecol_attn", "pulsecol_attn_dense",
-    "pulsecol_refresh_dense",
+    "pulsecol_refresh_dense", "pulsecol_select_noalloc",
     "pulsecol_refresh_schedule", "pulsecol_refresh_schedule_power", "pulsecol_refresh_schedule_random",
     "pulsecol_attn_tile_shape", "pulsecol_status_str", "pulsecol_last_error",
 )
@@ -65,6 +65,7 @@ def lib() -> ctypes.CDLL:
         L.pulsecol_attn.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_void_p]
         L.pulsecol_attn_dense.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
         L.pulsecol_refresh_dense.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_double, c_void_p, c_void_p, c_void_p]
+        L.pulsecol_select_noalloc.argtypes = [POINTER(Shape), c_void_p, c_void_p, c_double, c_void_p, c_void_p]
         L.pulsecol_refresh_schedule.argtypes = [c_int32, c_double, c_int32, POINTER(c_int32)]
         L.pulsecol_refresh_schedule.restype = c_int32
         L.pulsecol_refresh_schedule_power.argtypes = [c_int32, c_double, c_int32, POINTER(c_int32)]
@@ -144,6 +145,14 @@ def _ptr(t):
 
 def _stream():
     return c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def select_noalloc(shape: Shape, Q, K, keep_ratio: float, idx_out):
+    """pulsecol_select_noalloc on the current device: the caller brings idx_out [B, H, U, k] (int32)."""
+    st = lib().pulsecol_select_noalloc(ctypes.byref(shape), _ptr(Q), _ptr(K), keep_ratio, _ptr(idx_out), _stream())
+    if st != OK:
+        raise PulseColError(st, last_error(None))
+    return idx_out
 
 
 class Context:
