@@ -1,5 +1,5 @@
 """Compile csrc/*.hip for gfx950 and link libpulsecol.so next to this file (plus the
-stand-alone probe/roofline_probe).
+stand-alone roofline probe that sits beside bench.py at the repository root).
 
 Usage: ``python -m paper_2605_20813_amd.build`` (cross-compiles without a GPU).
 """
@@ -17,8 +17,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libpulsecol.so")
-PROBE_SRC = os.path.join(HERE, "probe", "roofline_probe.hip")
-PROBE_PATH = os.path.join(HERE, "roofline_probe")
+PROBE_SRC = os.path.join(os.path.dirname(HERE), "roofline_probe.hip")
+PROBE_PATH = os.path.join(os.path.dirname(HERE), "roofline_probe.bin")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
@@ -63,9 +63,11 @@ def build(verbose: bool = False) -> str:
             if verbose and out.strip():
                 print(out)
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH, *objs])
-    # the stand-alone roofline probe that bench.py starts as a child process
-    _run([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
-          "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-o", PROBE_PATH, PROBE_SRC])
+    # the stand-alone roofline probe that bench.py starts as a child process (a measurement aid,
+    # not part of the library: it lives beside bench.py)
+    if os.path.exists(PROBE_SRC):
+        _run([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+              "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-o", PROBE_PATH, PROBE_SRC])
     return LIB_PATH
 
 

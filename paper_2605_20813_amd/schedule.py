@@ -47,7 +47,8 @@ class LayerStack:
         if 0 not in self.refresh:
             raise ValueError("step 0 must identify the pattern")
         self.dense_at_refresh = dense_at_refresh
-        self.ctx = [pc.Context(batch, heads, seq, head_dim, dtype, group_size=group_size, device=device)
+        self.ctx = [pc.Context(batch, heads, seq, head_dim, dtype, group_size=group_size, device=device,
+                               max_keep_ratio=keep_ratio)
                     for _ in range(layers)]
         self.idx = [None] * layers
 

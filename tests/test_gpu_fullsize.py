@@ -127,47 +127,71 @@ def test_full_size_groupwise_sampled_groups(name, G, keep):
     U = -(-n // G)
     say(f"{name} G={G} keep={keep}: generating {H} heads x {n}")
     Q, K, V = wl.make_qkv(w)
-    with pc.Context(w.batch, H, n, w.head_dim, w.torch_dtype, group_size=G) as ctx:
+    check_groups_against_oracle(name, Q, K, V, G, keep, ((0, 0), (3, U // 2), (H - 1, U - 1), (17, 1)))
+
+
+def check_groups_against_oracle(name, Q, K, V, G, keep, sampled):
+    """Scores, selection and attention of the sampled (head, group) pairs.  The attention runs
+    through the ORACLE's column sets on those groups (written over the GPU's before the call), so
+    nothing the oracle consumes comes from the GPU."""
+    _, H, n, d = Q.shape
+    k = oracle.num_keep(n, keep)
+    U = -(-n // G)
+    s64, oidx = {}, {}
+    for h, u in sampled:
+        lo, hi = u * G, min((u + 1) * G, n)
+        say(f"oracle: scores of head {h} group {u} (rows {lo}..{hi - 1})")
+        s64[h, u] = oracle.column_scores(f64(Q[0, h, lo:hi]), f64(K[0, h]))[0]       # the group's rows as one group
+        oidx[h, u] = oracle.topk_columns(s64[h, u][None], k)[0]
+    with pc.Context(1, H, n, d, torch.bfloat16, group_size=G) as ctx:
         q, k_, v = Q.to(DEV), K.to(DEV), V.to(DEV)
         say("GPU select + scores + attn")
         sc = ctx.scores(q, k_)
         idx = ctx.select(q, k_, keep)
-        O = ctx.attn(q, k_, v, idx)
+        idx_in = idx.clone()
+        for (h, u), cols in oidx.items():
+            idx_in[0, h, u] = torch.from_numpy(cols).to(torch.int32).to(DEV)
+        O = ctx.attn(q, k_, v, idx_in)
         torch.cuda.synchronize()
         assert sc.shape == (1, H, U, n) and idx.shape == (1, H, U, k)
         assert (sc.sum(dim=-1) - 1.0).abs().max().item() < 1e-4
     flips = 0
-    for h, u in ((0, 0), (3, U // 2), (H - 1, U - 1), (17, 1)):
+    for h, u in sampled:
         lo, hi = u * G, min((u + 1) * G, n)
-        say(f"oracle: head {h} group {u} (rows {lo}..{hi - 1})")
-        qg, kh, vh = f64(Q[0, h, lo:hi]), f64(K[0, h]), f64(V[0, h])
-        s64 = oracle.column_scores(qg, kh)[0]                    # the group's rows as one group
-        rel = np.abs(f64(sc[0, h, u]) - s64) / s64
+        rel = np.abs(f64(sc[0, h, u]) - s64[h, u]) / s64[h, u]
         assert rel.max() < 2e-5, f"scores head {h} group {u}: {rel.max():.3e}"
-        row = idx[0, h, u].cpu().numpy()
-        flips += assert_idx_matches(row, s64, k, f"{name} head {h} group {u}")
-        # the attention of the GPU's validated set, rows of this group only
-        want = oracle.sparse_attention_masked(qg, kh, vh, row)
+        flips += assert_idx_matches(idx[0, h, u].cpu().numpy(), s64[h, u], k, f"{name} head {h} group {u}")
+        say(f"oracle: attention of head {h} group {u}")
+        want = oracle.sparse_attention_masked(f64(Q[0, h, lo:hi]), f64(K[0, h]), f64(V[0, h]), oidx[h, u])
         assert_close(O[0, h, lo:hi], want, "bf16", f"{name} attn head {h} group {u}")
     say(f"ok, near-tie flips {flips}")
+
+
+def heads_128k():
+    B, H, n, d = 1, 8, 131072, 128
+    g = torch.Generator(device="cpu")
+    g.manual_seed(20813)
+    Q, K, V = (torch.randn(B, H, n, d, generator=g).to(torch.bfloat16) for _ in range(3))
+    K[:, :, ::17] *= 2.5                              # 7711 heavy columns, more than the k = 6553 kept at 5%
+    return Q, K, V
 
 
 def test_twice_the_largest_workload_context():
     """128K context (8 heads): beyond every configured workload -- rows longer than the
     register-resident top-k holds (the streaming kernel runs at full size), twice as many query
-    blocks per head in the queues.  Sampled query rows against the oracle; every planted heavy
-    key column must be selected."""
+    blocks per head in the queues.  Attention on seeded random column sets, sampled query rows
+    against the oracle; the selection is checked through properties here (ascending, in range,
+    heavy columns only: fewer are kept than were planted) and against the oracle's own scores in the
+    group-wise test below."""
     B, H, n, d, keep = 1, 8, 131072, 128, 0.05
     say("128K context: generating")
-    g = torch.Generator(device="cpu")
-    g.manual_seed(20813)
-    Q, K, V = (torch.randn(B, H, n, d, generator=g).to(torch.bfloat16) for _ in range(3))
-    K[:, :, ::17] *= 2.5                              # 7711 heavy columns, more than the k = 6553 kept
+    Q, K, V = heads_128k()
     k = oracle.num_keep(n, keep)
+    idx_in = random_idx(n, k, H, seed=131072).view(B, H, 1, k)
     with pc.Context(B, H, n, d, torch.bfloat16) as ctx:
         q, k_, v = Q.to(DEV), K.to(DEV), V.to(DEV)
         idx = ctx.select(q, k_, keep, refresh=True)
-        O = ctx.attn(q, k_, v, idx)
+        O = ctx.attn(q, k_, v, idx_in.to(DEV))
         torch.cuda.synchronize()
     idx_h = idx.cpu().numpy()
     assert idx_h.shape == (B, H, 1, k)
@@ -176,5 +200,50 @@ def test_twice_the_largest_workload_context():
     rows = sample_rows(n, 6, seed=3)
     for h in (0, 5, 7):
         say(f"128K context: oracle rows of head {h}")
-        want = oracle.sparse_attention_masked(f64(Q[0, h, rows]), f64(K[0, h]), f64(V[0, h]), idx_h[0, h])
+        want = oracle.sparse_attention_masked(f64(Q[0, h, rows]), f64(K[0, h]), f64(V[0, h]), idx_in[0, h].numpy())
         assert_close(O[0, h, rows], want, "bf16", f"128K head {h}")
+
+
+def test_128k_context_groupwise_selection_against_oracle_scores():
+    """The same 128K heads with one column set per 128 query rows: a group's fp64 scores are cheap,
+    so the selection (streaming top-k over 8192 rows of 131072 scores) is checked completely on
+    sampled groups: every differing column must be a near-tie of the oracle's own scores."""
+    say("128K context, G = 128: generating")
+    Q, K, V = heads_128k()
+    check_groups_against_oracle("128K", Q, K, V, 128, 0.05, ((0, 0), (5, 517), (7, 1023)))
+
+
+def test_refresh_after_drift_selects_on_the_drifted_inputs():
+    """The drifting schedule (16K workload, two of its heads): 16 steps of 0.05 N(0,1) noise on the
+    fp32 masters between the identification step and the first refresh.  The refreshed pattern must
+    be the oracle's selection on the DRIFTED inputs (near-tie rule), must replace the cached one,
+    and the stale pattern must fail that same check -- a refresh that handed back the old pattern
+    would not pass."""
+    w = wl.WORKLOADS["llada_16k"]
+    heads = [0, 5]
+    n, d, keep = w.seq, w.head_dim, w.keep_ratios[0]
+    k = oracle.num_keep(n, keep)
+    say(f"{w.name} drift: generating heads {heads}")
+    masters = list(wl.make_qkv(w, heads=heads, master=True))
+    Q0, K0 = (m.to(torch.bfloat16) for m in masters[:2])
+    for step in range(1, w.refresh_steps[1] + 1):
+        wl.drift_(masters, w, step)
+    Q1, K1 = (m.to(torch.bfloat16) for m in masters[:2])
+    assert not torch.equal(K0, K1)
+    with pc.Context(1, len(heads), n, d, torch.bfloat16, max_keep_ratio=keep) as ctx:
+        first = ctx.select(Q0.to(DEV), K0.to(DEV), keep, refresh=True).clone()
+        reused = ctx.select(None, None, keep, refresh=False).clone()
+        fresh = ctx.select(Q1.to(DEV), K1.to(DEV), keep, refresh=True).clone()
+        cached = ctx.select(None, None, keep, refresh=False).clone()
+        torch.cuda.synchronize()
+    assert torch.equal(first, reused) and torch.equal(fresh, cached)
+    moved = [int(np.setdiff1d(fresh[0, i, 0].cpu().numpy(), first[0, i, 0].cpu().numpy()).size) for i in range(len(heads))]
+    say(f"{w.name} drift: columns replaced by the refresh, per head: {moved} of {k}")
+    assert min(moved) > 0
+    i = 1
+    say(f"{w.name} drift: oracle column scores of head {heads[i]} on the drifted inputs")
+    s64 = oracle.column_scores(f64(Q1[0, i]), f64(K1[0, i]))[0]
+    flips = assert_idx_matches(fresh[0, i, 0].cpu().numpy(), s64, k, f"{w.name} drifted head {heads[i]}")
+    say(f"near-tie flips {flips}")
+    with pytest.raises(AssertionError):
+        assert_idx_matches(first[0, i, 0].cpu().numpy(), s64, k, "stale pattern")

@@ -97,21 +97,23 @@ def test_group_select_then_attention(n, d, dtype, G, keep):
     K[:, :, 5::13] *= 2.5
     U = -(-n // G)
     k = oracle.num_keep(n, keep)
+    # the oracle's own scores and column sets first: the attention below runs through THEM, so
+    # nothing the oracle consumes comes from the GPU
+    s64 = [oracle.column_scores(f64(Q[0, h]), f64(K[0, h]), group_size=G) for h in range(H)]
+    oidx = np.stack([oracle.topk_columns(s64[h], k) for h in range(H)])[None]
     with pc.Context(B, H, n, d, dtype, group_size=G) as ctx:
         q, k_, v = Q.to(DEV), K.to(DEV), V.to(DEV)
         idx = ctx.select(q, k_, keep)
         again = ctx.select(None, None, keep, refresh=False)          # reuse step: the cached pattern
-        O = ctx.attn(q, k_, v, idx)
+        O = ctx.attn(q, k_, v, torch.from_numpy(oidx).to(torch.int32).to(DEV))
         torch.cuda.synchronize()
     assert idx.shape == (B, H, U, k)
     assert torch.equal(idx, again)
     idx_host = idx.cpu().numpy()
     for h in range(H):
-        s64 = oracle.column_scores(f64(Q[0, h]), f64(K[0, h]), group_size=G)
         for u in range(U):
-            assert_idx_matches(idx_host[0, h, u], s64[u], k, f"select head {h} group {u}")
-        # the attention output of the GPU's own (validated) column sets
-        want = oracle.sparse_attention_masked(f64(Q[0, h]), f64(K[0, h]), f64(V[0, h]), idx_host[0, h], group_size=G)
+            assert_idx_matches(idx_host[0, h, u], s64[h][u], k, f"select head {h} group {u}")
+        want = oracle.sparse_attention_masked(f64(Q[0, h]), f64(K[0, h]), f64(V[0, h]), oidx[0, h], group_size=G)
         assert_close(O[0, h], want, kind_of(dtype), f"group select+attn head {h}")
 
 

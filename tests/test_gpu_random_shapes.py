@@ -68,22 +68,24 @@ def test_random_configuration(seed):
     K[:, :, 3::7] *= 2.0
     k = oracle.num_keep(n, keep)
     rep = H // Hkv
+    # the oracle's scores and column sets come first; the attention runs through the oracle's sets
+    s64 = [oracle.column_scores(f64(Q[0, h]), f64(K[0, h // rep]), group_size=G) for h in range(H)]
+    oidx = np.stack([oracle.topk_columns(s64[h], k) for h in range(H)])[None]
     with pc.Context(1, H, n, d, torch.bfloat16, group_size=G, kv_heads=Hkv) as ctx:
         U = ctx.groups
         q, k_, v = Q.to(DEV), K.to(DEV), V.to(DEV)
         idx = ctx.select(q, k_, keep)
-        O = ctx.attn(q, k_, v, idx)
+        O = ctx.attn(q, k_, v, torch.from_numpy(oidx).to(torch.int32).to(DEV))
         Od, idx2 = ctx.refresh_dense(q, k_, v, keep)
         torch.cuda.synchronize()
     assert idx.shape == (1, H, U, k)
     idx_host = idx.cpu().numpy()
     for h in range(H):
         qh, kh, vh = f64(Q[0, h]), f64(K[0, h // rep]), f64(V[0, h // rep])
-        s64 = oracle.column_scores(qh, kh, group_size=G)
         for u in range(U):
-            assert_idx_matches(idx_host[0, h, u], s64[u], k, f"seed {seed} head {h} group {u}")
-            assert_idx_matches(idx2[0, h, u].cpu().numpy(), s64[u], k, f"seed {seed} refresh_dense head {h} group {u}")
-        want = oracle.sparse_attention_masked(qh, kh, vh, idx_host[0, h], group_size=G)
+            assert_idx_matches(idx_host[0, h, u], s64[h][u], k, f"seed {seed} head {h} group {u}")
+            assert_idx_matches(idx2[0, h, u].cpu().numpy(), s64[h][u], k, f"seed {seed} refresh_dense head {h} group {u}")
+        want = oracle.sparse_attention_masked(qh, kh, vh, oidx[0, h], group_size=G)
         assert_close(O[0, h], want, "bf16", f"seed {seed} attn head {h}")
         assert_close(Od[0, h], oracle.dense_attention(qh, kh, vh), "bf16", f"seed {seed} dense head {h}")
 
