@@ -19,7 +19,8 @@
  *     padding mask.
  *   - Column sets are DEVICE int32 arrays idx[batch, heads, U, k]; U is the number of query
  *     groups per head (U = 1 when group_size == 0: one column set per head).  Entries lie in
- *     [0, seq) and are unique within a row; pulsecol_select emits them ascending.  The
+ *     [0, seq) and are unique within a row; pulsecol_select emits them ascending.  (With
+ *     variable-length batches, see pulsecol_set_seq_lens, the unused tail of a row is -1.)  The
  *     sparse kernel counts a repeated entry twice, as the appendix listing would.  An entry
  *     outside [0, seq) addresses memory outside K and V: a caller that cannot vouch for its
  *     indices turns the validation mode on (pulsecol_set_validation).
@@ -112,6 +113,24 @@ PULSECOL_API pulsecol_status pulsecol_create(pulsecol_ctx** out, const pulsecol_
  * every entry of idx lies in [0, seq), waits for the answer (it synchronises the stream) and
  * returns PULSECOL_ERR_BAD_INDEX without launching the attention kernel if one does not. */
 PULSECOL_API pulsecol_status pulsecol_set_validation(pulsecol_ctx* ctx, int on);
+
+/* Variable-length batches: a padded batch whose elements have their own lengths.  seq_lens is a HOST
+ * array of `batch` ints, 1 <= seq_lens[b] <= seq, copied by the call (it rides in the arguments of
+ * small launches on `stream`: no host-to-device copy, no synchronisation); NULL returns the context
+ * to fixed length.  From then on batch element b consists of rows 0 .. seq_lens[b]-1 of its slabs of
+ * Q, K, V, O -- Sec. 3.1's n is the element's own length -- and the rest is padding that no call
+ * reads or writes:
+ *   - scores:  scores_out[b, h, u, j] is written for j < seq_lens[b] and the groups u that hold a real
+ *              row (U_b = ceil(seq_lens[b] / group_size)); everything else is left untouched;
+ *   - select / refresh_dense / topk: element b keeps k_b = max(1, floor(keep_ratio * seq_lens[b]))
+ *              columns (pulsecol_topk: min(k, seq_lens[b])): idx_out[b, h, u, 0..k_b) ascending, then
+ *              -1 up to the row length k = pulsecol_num_keep(seq, keep_ratio); rows of groups beyond
+ *              U_b are all -1;
+ *   - attn:    of idx[b, ...] the leading non-negative entries count (read off the first column set of
+ *              the element; every set of an element holds the same number), rows >= seq_lens[b] of O
+ *              are not written; attn_dense likewise attends to the element's own keys only.
+ * Drops a cached pattern (it belongs to the lengths it was selected with). */
+PULSECOL_API pulsecol_status pulsecol_set_seq_lens(pulsecol_ctx* ctx, const int32_t* seq_lens, void* stream);
 
 /* Free the scratch.  The caller must have synchronised the streams it used.  NULL is OK. */
 PULSECOL_API pulsecol_status pulsecol_destroy(pulsecol_ctx* ctx);

@@ -752,7 +752,16 @@ struct WorkQueues {
     unsigned long long* work;
     uint32_t stamp;
     int bh_total, nqb;
+    const int32_t* varlen;      // per batch element: its own sequence length (variable-length batches), or nullptr
+    int heads;
     __device__ __forceinline__ int items(int y) const { return y < bh_total ? ((bh_total - y + 7) >> 3) * nqb : 0; }
+    // item j of queue q is a query block that lies wholly in the padding of its batch element
+    __device__ __forceinline__ bool is_padding(int q, int j) const {
+        if (varlen == nullptr) return false;
+        const int head_block = j / nqb;
+        const int qblk = j - head_block * nqb;
+        return qblk * BM >= varlen[(head_block * 8 + q) / heads];
+    }
     __device__ __forceinline__ int take(int q) const {
         unsigned long long* const counter = work + q;
         unsigned long long v = __hip_atomic_fetch_add(counter, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -773,10 +782,14 @@ struct WorkQueues {
     // One thread: item j taken from queue q is good, or else the first item that the following
     // queues still have; j = -1 when every queue has been found empty.
     __device__ __forceinline__ void settle(int home, int& q, int& j) const {
-        while (j >= items(q)) {
-            q = (q + 1) & 7;
-            if (q == home) { j = -1; return; }
-            j = take(q);
+        for (;;) {
+            while (j >= items(q)) {
+                q = (q + 1) & 7;
+                if (q == home) { j = -1; return; }
+                j = take(q);
+            }
+            if (!is_padding(q, j)) return;
+            j = take(q);            // nothing to do for a block of padding rows: on to the next item
         }
     }
 };
@@ -810,9 +823,9 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     asm volatile("" : : "s"(p.q), "s"(p.k), "s"(p.v), "s"(p.o), "s"(p.idx), "s"(p.lse), "s"(p.lse_base2),
                          "s"(p.td.sb), "s"(p.td.sh), "s"(p.td.sn), "s"(p.td_kv.sb), "s"(p.td_kv.sh), "s"(p.td_kv.sn),
                          "s"(p.kv_heads), "s"(p.batch), "s"(p.heads), "s"(p.n), "s"(p.ns), "s"(p.groups),
-                         "s"(p.group_size), "s"(p.scale), "s"(p.work), "s"(p.work_stamp));
+                         "s"(p.group_size), "s"(p.scale), "s"(p.work), "s"(p.work_stamp), "s"(p.varlen));
     const int nqb = (p.n + BM - 1) / BM;
-    const WorkQueues queues{p.work, p.work_stamp, p.batch * p.heads, nqb};
+    const WorkQueues queues{p.work, p.work_stamp, p.batch * p.heads, nqb, p.varlen, p.heads};
     __shared__ int32_t lds_item[2];          // the workgroup's next item: queue, index in the queue
     const int home = xcc_id();
     if (threadIdx.x == 0) {
@@ -832,7 +845,18 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     wq.ntiles = (p.ns + BN - 1) / BN;
     wq.lrow = wq.lane / W::PIECES;
     wq.idx = nullptr;
-    const int n = p.n;
+    // Rows and attended columns of a head: the context's, or (variable-length batches) those of the
+    // head's batch element: its own length, and of its column sets the leading `kept` entries.
+    auto lens_of = [&](int bh, int& rows, int& cols) {
+        rows = p.n;
+        cols = p.ns;
+        if (p.varlen != nullptr) {
+            const int b = bh / p.heads;
+            rows = p.varlen[b];
+            const int kept = p.varlen[p.batch + b];
+            cols = W::GATHER ? (kept < p.ns ? kept : p.ns) : rows;
+        }
+    };
     // item (queue, index) -> head and query block; pointers of a head
     auto decode = [&](int q, int j, int& bh, int& qblk) {
         const int head_block = j / nqb;
@@ -860,10 +884,12 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     static_assert(PRO_TILES == 3, "the prologue is written out for three tiles");
     constexpr int Q_LOADS = HAS_V ? TILE_BYTES / 1024 : 0;        // direct-to-LDS loads of a wave's share of Q
     const byte* req_q = nullptr;          // the requested block's head of Q, and its first row for this wave
-    int req_q0 = 0;
+    int req_q0 = 0, req_n = p.n;          // ... and the rows of that head
     auto request_rows = [&](int q, int j) {
         int bh, qblk;
         decode(q, j, bh, qblk);
+        lens_of(bh, req_n, wq.ns);
+        wq.ntiles = (wq.ns + BN - 1) / BN;
         const byte* const pattern = pattern_of(bh, qblk);
         wq.load_rows(pattern, 0, rows_0);
         wq.load_rows(pattern, 1, rows_1);
@@ -895,7 +921,7 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
 #pragma unroll
             for (int t = t0; t < t1; ++t) {
                 int row = row0 + t * RPC;
-                row = row < n ? row : n - 1;
+                row = row < req_n ? row : req_n - 1;
                 uint32_t off;
                 if (t % 4 == 0) {
                     asm volatile("s_add_i32 m0, %1, %2\n\tv_mad_u32_u24 %0, %3, %4, %5"
@@ -925,11 +951,11 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     w.wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     w.lq = w.lane & 31;
     w.lh = w.lane >> 5;
-    w.n = p.n;
-    w.ns = p.ns;
-    w.ntiles = (p.ns + BN - 1) / BN;
+    lens_of(bh, w.n, w.ns);
+    const int n = w.n;
+    w.ntiles = (w.ns + BN - 1) / BN;
     w.nhalf = 2 * w.ntiles;
-    w.ragged = (p.ns & (BN - 1)) != 0;
+    w.ragged = (w.ns & (BN - 1)) != 0;
     w.row_bytes = (uint32_t)p.td_kv.sn * 2u;
     w.wave_lds = __builtin_amdgcn_readfirstlane(lds_address(lds_k) + w.wave * CH * 1024);
     w.idx = nullptr;
@@ -1079,7 +1105,7 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
         l_tot[qb] = half_sum(w.l_run[qb]);
         const int row = q0 + qb * 32 + w.lq;
         if (p.lse != nullptr && w.lh == 0 && row < n)
-            p.lse[(int64_t)bh * n + row] = (w.mc[qb] + fast_log2(l_tot[qb])) * (p.lse_base2 ? 1.0f : kLn2);
+            p.lse[(int64_t)bh * p.n + row] = (w.mc[qb] + fast_log2(l_tot[qb])) * (p.lse_base2 ? 1.0f : kLn2);
     }
     constexpr int OUT_GROUPS = 64 / W::ROWS_PER_CHUNK;
     const int out_lrow = w.lane / W::PIECES, out_lpiece = w.lane % W::PIECES;

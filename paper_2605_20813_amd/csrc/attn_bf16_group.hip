@@ -101,9 +101,15 @@ attn_bf16_group_kernel(AttnParams p) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lq = lane & 31;       // query column (and K/V row) this lane owns inside a 32-block
     const int lh = lane >> 5;       // which half of the wave
-    const int ns = p.ns;
+    // variable-length batches: the batch element's own length, and the leading `kept` entries of its sets
+    int n = p.n, ns = p.ns;
+    if (p.varlen != nullptr) {
+        n = p.varlen[b];
+        const int kept = p.varlen[p.batch + b];
+        ns = kept < ns ? kept : ns;
+        if (qblk * BM >= n) return;         // a block of padding rows
+    }
     const int ntiles = (ns + BN - 1) / BN;
-    const int n = p.n;
     const uint32_t row_bytes = (uint32_t)p.td_kv.sn * 2u;
 
     // ---- Q fragments: B operand, [query lq][d = kk*16 + 8*lh .. +7]

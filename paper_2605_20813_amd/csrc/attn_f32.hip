@@ -47,7 +47,14 @@ __global__ void __launch_bounds__(NTHREADS) attn_f32_kernel(AttnParams p) {
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int lq = lane & 31, lh = lane >> 5;
-    const int n = p.n, ns = p.ns;
+    // variable-length batches: the batch element's own length, and the leading `kept` entries of its sets
+    int n = p.n, ns = p.ns;
+    if (p.varlen != nullptr) {
+        n = p.varlen[b];
+        const int kept = p.varlen[p.batch + b];
+        ns = GATHER ? (kept < ns ? kept : ns) : n;
+        if (qblk * BM >= n) return;         // a block of padding rows
+    }
     const int ntiles = (ns + BN - 1) / BN;
 
     // ---- Q fragment: B operand, lane holds Q[query lq][d = 2*kk + lh]
@@ -162,7 +169,7 @@ __global__ void __launch_bounds__(NTHREADS) attn_f32_kernel(AttnParams p) {
                 }
         }
         if (p.lse != nullptr && lh == 0)
-            p.lse[(int64_t)bh * n + row] = (m_run * c2 + log2f(l_tot)) * (p.lse_base2 ? 1.0f : kLn2);
+            p.lse[(int64_t)bh * p.n + row] = (m_run * c2 + log2f(l_tot)) * (p.lse_base2 ? 1.0f : kLn2);
     }
 }
 

@@ -87,17 +87,19 @@ __global__ void __launch_bounds__(NTHREADS) colmass_bf16_kernel(ScoreParams p) {
     constexpr int SLOT_BYTES = TILE_BYTES + QT * 4;
     __shared__ __attribute__((aligned(1024))) byte lds_s0[SLOT_BYTES], lds_s1[SLOT_BYTES], lds_s2[SLOT_BYTES];
 
-    const int n = p.n;
-    const int nkb = (n + KEYS_PER_WG - 1) / KEYS_PER_WG;
+    const int nkb = (p.n + KEYS_PER_WG - 1) / KEYS_PER_WG;
     int bh, kblk;
     if (!xcd_tile(blockIdx.x, nkb, p.batch * p.heads, &bh, &kblk)) return;
     const int b = bh / p.heads, h = bh - b * p.heads;
+    // variable-length batches: queries and keys of this batch element end at its own length
+    const int n = p.varlen != nullptr ? p.varlen[b] : p.n;
+    if (kblk * KEYS_PER_WG >= n) return;    // a block of padding keys: its scores are left untouched
     const int64_t head_off = (int64_t)b * p.td.sb + (int64_t)h * p.td.sh;
     // grouped-query layout: query head h reads K/V head h / (heads / kv_heads)
     const int64_t kv_off = (int64_t)b * p.td_kv.sb + (int64_t)(h / (p.heads / p.kv_heads)) * p.td_kv.sh;
     const byte* __restrict__ Q = (const byte*)((const __bf16*)p.q + head_off);
     const __bf16* __restrict__ K = (const __bf16*)p.k + kv_off;
-    const float* __restrict__ lse = p.lse + (int64_t)bh * n;
+    const float* __restrict__ lse = p.lse + (int64_t)bh * p.n;
     const uint32_t row_bytes = (uint32_t)p.td.sn * 2u;
 
     const int tid = threadIdx.x;
@@ -204,7 +206,7 @@ __global__ void __launch_bounds__(NTHREADS) colmass_bf16_kernel(ScoreParams p) {
                 const int g_first = p.groups > 1 ? u * p.group_size : 0;
                 const int g_rows = rows_seen - g_first;
                 const float inv = 1.0f / (float)g_rows;
-                float* __restrict__ out = p.scores + ((int64_t)bh * p.groups + u) * n;
+                float* __restrict__ out = p.scores + ((int64_t)bh * p.groups + u) * p.n;
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb) {
                     const float v = half_sum(((acc_long[kb][0] + acc_short[kb][0]) + (acc_long[kb][1] + acc_short[kb][1])) +

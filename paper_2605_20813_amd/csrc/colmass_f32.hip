@@ -27,17 +27,19 @@ __global__ void __launch_bounds__(NTHREADS) colmass_f32_kernel(ScoreParams p) {
     __shared__ __attribute__((aligned(16))) float lds_q[QT * LDW];
     __shared__ float lds_lse[QT];
 
-    const int n = p.n;
-    const int nkb = (n + KEYS_PER_WG - 1) / KEYS_PER_WG;
+    const int nkb = (p.n + KEYS_PER_WG - 1) / KEYS_PER_WG;
     int bh, kblk;
     if (!xcd_tile(blockIdx.x, nkb, p.batch * p.heads, &bh, &kblk)) return;
     const int b = bh / p.heads, h = bh - b * p.heads;
+    // variable-length batches: queries and keys of this batch element end at its own length
+    const int n = p.varlen != nullptr ? p.varlen[b] : p.n;
+    if (kblk * KEYS_PER_WG >= n) return;    // a block of padding keys: its scores are left untouched
     const int64_t head_off = (int64_t)b * p.td.sb + (int64_t)h * p.td.sh;
     // grouped-query layout: query head h reads K/V head h / (heads / kv_heads)
     const int64_t kv_off = (int64_t)b * p.td_kv.sb + (int64_t)(h / (p.heads / p.kv_heads)) * p.td_kv.sh;
     const float* __restrict__ Q = (const float*)p.q + head_off;
     const float* __restrict__ K = (const float*)p.k + kv_off;
-    const float* __restrict__ lse = p.lse + (int64_t)bh * n;
+    const float* __restrict__ lse = p.lse + (int64_t)bh * p.n;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -112,7 +114,7 @@ __global__ void __launch_bounds__(NTHREADS) colmass_f32_kernel(ScoreParams p) {
             const int g_first = p.groups > 1 ? u * p.group_size : 0;
             const int g_rows = (rows_done < n ? rows_done : n) - g_first;
             const float inv = 1.0f / (float)g_rows;
-            float* __restrict__ out = p.scores + ((int64_t)bh * p.groups + u) * n;
+            float* __restrict__ out = p.scores + ((int64_t)bh * p.groups + u) * p.n;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 float v = acc_long[r] + acc_short[r];

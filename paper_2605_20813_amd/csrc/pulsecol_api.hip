@@ -32,6 +32,8 @@ struct pulsecol_ctx {
     unsigned long long* work = nullptr;   // work counters of the bf16 attention kernels (same block)
     uint32_t work_stamp = 0;        // stamp of the last launch that used them (every launch takes the next one)
     bool validate = false;          // check column numbers in front of every pulsecol_attn
+    int32_t* varlen = nullptr;      // [2 * batch] device words of variable-length batches: lengths, kept counts
+    bool varlen_on = false;         // pulsecol_set_seq_lens has given per-element lengths
     std::string last_error;
 };
 
@@ -156,6 +158,7 @@ pulsecol::AttnParams attn_params(pulsecol_ctx* c, const void* Q, const void* K, 
     p.batch = c->shape.batch; p.heads = c->shape.heads; p.n = c->shape.seq; p.ns = ns;
     p.groups = c->groups; p.group_size = c->shape.group_size;
     p.scale = c->scale;
+    p.varlen = c->varlen_on ? c->varlen : nullptr;
     p.work = c->work;
     if (++c->work_stamp == 0) c->work_stamp = 1;       // freshly cleared counters carry stamp 0
     p.work_stamp = c->work_stamp;
@@ -192,6 +195,7 @@ pulsecol_status run_colmass(pulsecol_ctx* ctx, const void* Q, const void* K, flo
     sp.q = Q; sp.k = K; sp.lse = ctx->lse; sp.scores = out; sp.td = ctx->td; sp.td_kv = ctx->td_kv; sp.kv_heads = ctx->kv_heads;
     sp.batch = ctx->shape.batch; sp.heads = ctx->shape.heads; sp.n = ctx->shape.seq; sp.scale = ctx->scale;
     sp.groups = ctx->groups; sp.group_size = ctx->shape.group_size;
+    sp.varlen = ctx->varlen_on ? ctx->varlen : nullptr;
     const hipError_t e = ctx->shape.dtype == PULSECOL_BF16 ? pulsecol::launch_colmass_bf16(sp, ctx->shape.head_dim, s)
                                                            : pulsecol::launch_colmass_f32(sp, ctx->shape.head_dim, s);
     if (e != hipSuccess) return fail_hip(ctx, e, "column-mass kernel");
@@ -209,7 +213,12 @@ pulsecol_status run_scores(pulsecol_ctx* ctx, const void* Q, const void* K, floa
 // top-k of ctx->scores into idx_out, and into the context's cache
 pulsecol_status run_topk(pulsecol_ctx* ctx, const float* scores, int32_t k, int32_t* out, hipStream_t s);
 
-pulsecol_status select_from_scores(pulsecol_ctx* ctx, int32_t k, int32_t* idx_out, hipStream_t s, const char* who) {
+pulsecol_status select_from_scores(pulsecol_ctx* ctx, double keep_ratio, int32_t k, int32_t* idx_out, hipStream_t s, const char* who) {
+    if (ctx->varlen_on) {
+        // every batch element keeps max(1, floor(keep_ratio * its own length)) columns
+        const hipError_t ev = pulsecol::launch_varlen_kept_from_ratio(ctx->varlen, ctx->shape.batch, keep_ratio, s);
+        if (ev != hipSuccess) return fail_hip(ctx, ev, (std::string(who) + ": per-element keep counts").c_str());
+    }
     pulsecol_status st = run_topk(ctx, ctx->scores, k, idx_out, s);
     if (st != PULSECOL_OK) return st;
     ctx->cached_k = 0;
@@ -224,6 +233,9 @@ pulsecol_status run_topk(pulsecol_ctx* ctx, const float* scores, int32_t k, int3
     pulsecol::TopkParams tp{};
     tp.scores = scores; tp.idx = out;
     tp.rows = ctx->shape.batch * ctx->shape.heads * ctx->groups; tp.n = ctx->shape.seq; tp.k = k;
+    tp.varlen = ctx->varlen_on ? ctx->varlen : nullptr;
+    tp.batch = ctx->shape.batch; tp.rows_per_batch = ctx->shape.heads * ctx->groups;
+    tp.groups = ctx->groups; tp.group_size = ctx->shape.group_size;
     const hipError_t e = pulsecol::launch_topk(tp, s);
     if (e != hipSuccess) return fail_hip(ctx, e, "top-k kernel");
     return PULSECOL_OK;
@@ -295,6 +307,7 @@ pulsecol_status pulsecol_create(pulsecol_ctx** out, const pulsecol_shape* shape,
     c->k_max = shape->max_keep_ratio > 0.0 ? pulsecol_num_keep(shape->seq, shape->max_keep_ratio) : shape->seq;
     hipError_t e3 = e2 == hipSuccess ? hipMalloc((void**)&c->cached_idx, rows * c->groups * (size_t)c->k_max * sizeof(int32_t)) : e2;
     static_assert(64 + pulsecol::kWorkCounters * sizeof(unsigned long long) <= 256, "counter block");
+    if (e3 == hipSuccess) e3 = hipMalloc((void**)&c->varlen, 2 * (size_t)shape->batch * sizeof(int32_t));
     if (e3 == hipSuccess) e3 = hipMalloc((void**)&c->bad_count, 256);
     if (e3 == hipSuccess) e3 = hipMemset(c->bad_count, 0, 256);
     if (e3 == hipSuccess) c->work = reinterpret_cast<unsigned long long*>(c->bad_count + 16);
@@ -303,6 +316,7 @@ pulsecol_status pulsecol_create(pulsecol_ctx** out, const pulsecol_shape* shape,
         if (c->scores) (void)hipFree(c->scores);
         if (c->cached_idx) (void)hipFree(c->cached_idx);
         if (c->bad_count) (void)hipFree(c->bad_count);
+        if (c->varlen) (void)hipFree(c->varlen);
         (void)hipGetLastError();
         delete c;
         return e3 == hipErrorOutOfMemory ? fail(nullptr, PULSECOL_ERR_OOM, "pulsecol_create: scratch allocation failed")
@@ -320,6 +334,30 @@ pulsecol_status pulsecol_set_validation(pulsecol_ctx* ctx, int on) {
     return PULSECOL_OK;
 }
 
+pulsecol_status pulsecol_set_seq_lens(pulsecol_ctx* ctx, const int32_t* seq_lens, void* stream) {
+    if (!ctx) return fail(nullptr, PULSECOL_ERR_INVALID_ARG, "pulsecol_set_seq_lens: ctx is NULL");
+    if (!seq_lens) { ctx->varlen_on = false; return PULSECOL_OK; }
+    const int32_t B = ctx->shape.batch;
+    for (int32_t b = 0; b < B; ++b)
+        if (seq_lens[b] < 1 || seq_lens[b] > ctx->shape.seq)
+            return fail(ctx, PULSECOL_ERR_INVALID_ARG, "pulsecol_set_seq_lens: need 1 <= seq_lens[b] <= seq");
+    DeviceGuard guard(ctx->device);
+    if (guard.err != hipSuccess) return fail_hip(ctx, guard.err, "pulsecol_set_seq_lens: hipSetDevice");
+    // The lengths travel inside launch arguments, 64 at a time: nothing is read from the caller's array
+    // after this call returns, and nothing synchronises.  The kept counts start at the lengths.
+    for (int32_t first = 0; first < B; first += 64) {
+        pulsecol::VarlenChunk chunk{};
+        const int32_t count = B - first < 64 ? B - first : 64;
+        for (int32_t i = 0; i < count; ++i) chunk.v[i] = seq_lens[first + i];
+        hipError_t e = pulsecol::launch_varlen_store(ctx->varlen, first, count, chunk, (hipStream_t)stream);
+        if (e == hipSuccess) e = pulsecol::launch_varlen_store(ctx->varlen, B + first, count, chunk, (hipStream_t)stream);
+        if (e != hipSuccess) { ctx->varlen_on = false; return fail_hip(ctx, e, "pulsecol_set_seq_lens: storing the lengths"); }
+    }
+    ctx->varlen_on = true;
+    ctx->cached_k = 0;            // a cached pattern belongs to the lengths it was selected with
+    return PULSECOL_OK;
+}
+
 pulsecol_status pulsecol_destroy(pulsecol_ctx* ctx) {
     if (!ctx) return PULSECOL_OK;
     DeviceGuard guard(ctx->device);
@@ -327,6 +365,7 @@ pulsecol_status pulsecol_destroy(pulsecol_ctx* ctx) {
     (void)hipFree(ctx->scores);
     (void)hipFree(ctx->cached_idx);
     (void)hipFree(ctx->bad_count);
+    (void)hipFree(ctx->varlen);
     delete ctx;
     return PULSECOL_OK;
 }
@@ -352,6 +391,10 @@ pulsecol_status pulsecol_topk(pulsecol_ctx* ctx, const float* scores, int32_t k,
     if (k < 1 || k > ctx->shape.seq) return fail(ctx, PULSECOL_ERR_INVALID_ARG, "pulsecol_topk: need 1 <= k <= seq");
     DeviceGuard guard(ctx->device);
     if (guard.err != hipSuccess) return fail_hip(ctx, guard.err, "pulsecol_topk: hipSetDevice");
+    if (ctx->varlen_on) {
+        const hipError_t ev = pulsecol::launch_varlen_kept_from_k(ctx->varlen, ctx->shape.batch, k, (hipStream_t)stream);
+        if (ev != hipSuccess) return fail_hip(ctx, ev, "pulsecol_topk: per-element keep counts");
+    }
     return run_topk(ctx, scores, k, idx_out, (hipStream_t)stream);
 }
 
@@ -379,7 +422,7 @@ pulsecol_status pulsecol_select(pulsecol_ctx* ctx, const void* Q, const void* K,
     if (guard.err != hipSuccess) return fail_hip(ctx, guard.err, "pulsecol_select: hipSetDevice");
     st = run_scores(ctx, Q, K, ctx->scores, s);
     if (st != PULSECOL_OK) return st;
-    return select_from_scores(ctx, k, idx_out, s, "pulsecol_select");
+    return select_from_scores(ctx, keep_ratio, k, idx_out, s, "pulsecol_select");
 }
 
 pulsecol_status pulsecol_select_noalloc(const pulsecol_shape* shape, const void* Q, const void* K, double keep_ratio,
@@ -436,7 +479,7 @@ pulsecol_status pulsecol_refresh_dense(pulsecol_ctx* ctx, const void* Q, const v
     if (e != hipSuccess) return fail_hip(ctx, e, "dense attention kernel");
     st = run_colmass(ctx, Q, K, ctx->scores, s);
     if (st != PULSECOL_OK) return st;
-    return select_from_scores(ctx, k, idx_out, s, "pulsecol_refresh_dense");
+    return select_from_scores(ctx, keep_ratio, k, idx_out, s, "pulsecol_refresh_dense");
 }
 
 pulsecol_status pulsecol_attn(pulsecol_ctx* ctx, const void* Q, const void* K, const void* V, const int32_t* idx,
@@ -448,10 +491,19 @@ pulsecol_status pulsecol_attn(pulsecol_ctx* ctx, const void* Q, const void* K, c
     if (k < 1 || k > ctx->shape.seq) return fail(ctx, PULSECOL_ERR_INVALID_ARG, "pulsecol_attn: need 1 <= k <= seq");
     DeviceGuard guard(ctx->device);
     if (guard.err != hipSuccess) return fail_hip(ctx, guard.err, "pulsecol_attn: hipSetDevice");
+    const int64_t per_batch = (int64_t)ctx->shape.heads * ctx->groups * k;
+    if (ctx->varlen_on) {
+        // how many leading entries of an element's column sets count is read off the sets themselves
+        // (their unused tail is -1), so the call depends on no earlier one
+        const hipError_t ev = pulsecol::launch_varlen_kept_from_idx(ctx->varlen, ctx->shape.batch, idx, per_batch, k, (hipStream_t)stream);
+        if (ev != hipSuccess) return fail_hip(ctx, ev, "pulsecol_attn: per-element keep counts");
+    }
     if (ctx->validate) {
         // the one mode that synchronises: the answer has to be known before anything is gathered
-        const int64_t count = (int64_t)ctx->shape.batch * ctx->shape.heads * ctx->groups * k;
-        hipError_t ev = pulsecol::launch_index_range_check(idx, count, ctx->shape.seq, ctx->bad_count, (hipStream_t)stream);
+        const int64_t count = (int64_t)ctx->shape.batch * per_batch;
+        hipError_t ev = pulsecol::launch_index_range_check(idx, count, ctx->shape.seq, ctx->bad_count,
+                                                           ctx->varlen_on ? ctx->varlen : nullptr, ctx->shape.batch, per_batch, k,
+                                                           (hipStream_t)stream);
         int32_t bad = 0;
         if (ev == hipSuccess) ev = hipMemcpyAsync(&bad, ctx->bad_count, sizeof(bad), hipMemcpyDeviceToHost, (hipStream_t)stream);
         if (ev == hipSuccess) ev = hipStreamSynchronize((hipStream_t)stream);

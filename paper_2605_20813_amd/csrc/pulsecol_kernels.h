@@ -30,6 +30,10 @@ struct AttnParams {
     // launch that used the same words (any contents are fine: counters with another stamp are restarted)
     unsigned long long* work;
     uint32_t work_stamp;
+    // variable-length batches: device array [2 * batch] -- per batch element its own sequence length
+    // (<= n), then the number of leading entries of its column sets that count (<= ns); nullptr: every
+    // element has n rows and ns columns.  Rows and key positions beyond an element's length are padding.
+    const int32_t* varlen;
 };
 
 constexpr int kWorkCounters = 8;
@@ -46,12 +50,19 @@ struct ScoreParams {
     int32_t groups;          // U query groups per head (1 = the whole head)
     int32_t group_size;      // rows per group, a multiple of the kernel's query tile (unused when U = 1)
     float scale;
+    const int32_t* varlen;   // as in AttnParams (only the lengths are read); scores beyond them are left untouched
 };
 
 struct TopkParams {
     const float* scores;     // [rows, n]
     int32_t* idx;            // [rows, k]
     int32_t rows, n, k;
+    // variable-length batches (else nullptr): rows = batch * rows_per_batch; row r belongs to batch
+    // element b = r / rows_per_batch and is group u = r % groups of its head; it selects varlen[batch + b]
+    // of its first varlen[b] scores and pads the rest of its k entries with -1; rows of groups that lie
+    // wholly beyond the element's length are padded altogether
+    const int32_t* varlen;
+    int32_t batch, rows_per_batch, groups, group_size;
 };
 
 enum AttnMode { kSparse = 0, kDense = 1, kLseOnly = 2 };
@@ -72,7 +83,22 @@ hipError_t launch_attn_f32(const AttnParams& p, int head_dim, AttnMode mode, hip
 hipError_t launch_colmass_bf16(const ScoreParams& p, int head_dim, hipStream_t s);
 hipError_t launch_colmass_f32(const ScoreParams& p, int head_dim, hipStream_t s);
 hipError_t launch_topk(const TopkParams& p, hipStream_t s);
-// *bad_count (device) = number of wavefront-lanes that saw an entry of idx[0..count) outside [0, n); 0 if none
-hipError_t launch_index_range_check(const int32_t* idx, int64_t count, int32_t n, int32_t* bad_count, hipStream_t s);
+// *bad_count (device) = number of wavefront-lanes that saw an entry of idx[0..count) outside [0, n); 0 if none.
+// Variable-length batches (varlen != nullptr, per_batch = entries of idx per batch element, k = entries per
+// row): of each row only the leading varlen[batch + b] entries are checked, against [0, varlen[b]).
+hipError_t launch_index_range_check(const int32_t* idx, int64_t count, int32_t n, int32_t* bad_count,
+                                    const int32_t* varlen, int32_t batch, int64_t per_batch, int32_t k, hipStream_t s);
+
+// ---- variable-length batches: the per-batch words the kernels read (device array [2 * batch])
+// lens[0..count) -> varlen[first .. first+count) for count <= 64 values carried in the launch itself
+struct VarlenChunk { int32_t v[64]; };
+hipError_t launch_varlen_store(int32_t* varlen, int32_t first, int32_t count, const VarlenChunk& values, hipStream_t s);
+// kept[b] = max(1, floor(keep_ratio * len_b)) (the keep-count rule on the element's own length)
+hipError_t launch_varlen_kept_from_ratio(int32_t* varlen, int32_t batch, double keep_ratio, hipStream_t s);
+// kept[b] = min(k, len_b)
+hipError_t launch_varlen_kept_from_k(int32_t* varlen, int32_t batch, int32_t k, hipStream_t s);
+// kept[b] = number of leading non-negative entries of the first column set of batch element b (at most
+// min(k, len_b)); per_batch = entries of idx per batch element
+hipError_t launch_varlen_kept_from_idx(int32_t* varlen, int32_t batch, const int32_t* idx, int64_t per_batch, int32_t k, hipStream_t s);
 
 }  // namespace pulsecol

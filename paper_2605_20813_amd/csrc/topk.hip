@@ -26,6 +26,27 @@ __device__ __forceinline__ uint32_t order_key_of_bits(uint32_t u) {
 }
 __device__ __forceinline__ uint32_t order_key(float x) { return order_key_of_bits(__float_as_uint(x)); }
 
+// Elements and kept columns of score row `row`: the context's n and k, or (variable-length batches)
+// the length of the row's batch element and its kept count; a row whose query group lies wholly in
+// the padding of its element has neither (0, 0).
+__device__ __forceinline__ void row_geometry(const TopkParams& p, int row, int& n_row, int& k_row) {
+    n_row = p.n;
+    k_row = p.k;
+    if (p.varlen != nullptr) {
+        const int b = row / p.rows_per_batch;
+        const int u = row % p.groups;                   // rows are ordered [batch, head, group]
+        const int len = p.varlen[b];
+        const int kept = p.varlen[p.batch + b];
+        const bool padding = p.groups > 1 && u * p.group_size >= len;
+        n_row = padding ? 0 : len;
+        k_row = padding ? 0 : (kept < p.k ? kept : p.k);
+    }
+}
+// entries [from, k) of an output row are padding: -1
+__device__ __forceinline__ void pad_row(int32_t* __restrict__ out, int from, int k, int tid) {
+    for (int j = from + tid; j < k; j += TK_THREADS) out[j] = -1;
+}
+
 __global__ void __launch_bounds__(TK_THREADS) topk_kernel(TopkParams p) {
     __shared__ uint32_t hist[256];
     __shared__ uint32_t sh_prefix, sh_need;
@@ -34,13 +55,16 @@ __global__ void __launch_bounds__(TK_THREADS) topk_kernel(TopkParams p) {
     const int row = blockIdx.x;
     const float* __restrict__ s = p.scores + (int64_t)row * p.n;
     int32_t* __restrict__ out = p.idx + (int64_t)row * p.k;
-    const int n = p.n;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
+    int n, k_row;
+    row_geometry(p, row, n, k_row);
+    pad_row(out, k_row, p.k, tid);
+    if (k_row == 0) return;                             // uniform: the whole workgroup
 
     // ---- radix select: after the loop `prefix` is the key of the k-th largest element and
     //      `need` how many elements equal to it belong to the top-k
-    uint32_t prefix = 0, mask = 0, need = (uint32_t)p.k;
+    uint32_t prefix = 0, mask = 0, need = (uint32_t)k_row;
     for (int pass = 0; pass < 4; ++pass) {
         const int shift = 24 - 8 * pass;
         if (tid < 256) hist[tid] = 0;
@@ -102,7 +126,7 @@ __global__ void __launch_bounds__(TK_THREADS) topk_kernel(TopkParams p) {
         }
         if (sel) {
             const uint32_t pos = sel_before + sel_lane;
-            if (pos < (uint32_t)p.k) out[pos] = j;     // guard: holds by construction
+            if (pos < (uint32_t)k_row) out[pos] = j;     // guard: holds by construction
         }
         eq_seen += eq_total;
         out_pos += sel_total;
@@ -156,13 +180,18 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
     constexpr int CAND_MAX = 4096;
     __shared__ uint32_t cand[CAND_MAX];
 
-    const int n = p.n;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int first = wave * SEG + lane * 4;          // this lane's first element
-    // load instructions of this lane that lie inside the row (n % 4 == 0: a lane's four elements
-    // are inside or outside together)
-    const int nv = first >= n ? 0 : ((n - first + 255) / 256 < V4 ? (n - first + 255) / 256 : V4);
+    // load instructions of this lane that reach into a row of n_row elements (the row stride p.n is a
+    // multiple of 4, so a 16-byte load never leaves the row's storage; with a fixed length a lane's four
+    // elements are inside or outside together, with variable lengths the last group may straddle the end)
+    auto groups_inside = [&](int n_row) {
+        return first >= n_row ? 0 : ((n_row - first + 255) / 256 < V4 ? (n_row - first + 255) / 256 : V4);
+    };
+    int n, k_row;
+    row_geometry(p, blockIdx.x, n, k_row);
+    int nv = groups_inside(n);
 
     // The workgroup walks over rows blockIdx.x, + gridDim.x, ...; the scores of the next row are
     // requested while the running row is written out (each register group as soon as the
@@ -174,7 +203,7 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
 #pragma unroll
     for (int i = 0; i < V4; ++i) {
         u32x4 v = {0u, 0u, 0u, 0u};                          // outside the row: never looked at, every use is guarded by nv
-        if (i < nv) v = *(const u32x4*)(bits + (int64_t)blockIdx.x * n + first + i * 256);
+        if (i < nv) v = *(const u32x4*)(bits + (int64_t)blockIdx.x * p.n + first + i * 256);
 #pragma unroll
         for (int c = 0; c < 4; ++c) key[i][c] = v[c];
     }
@@ -182,7 +211,26 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
   for (int row = blockIdx.x; row < p.rows; row += gridDim.x) {
     int32_t* __restrict__ out = p.idx + (int64_t)row * p.k;
     const bool more = row + (int)gridDim.x < p.rows;
-    const uint32_t* __restrict__ next_bits = bits + (int64_t)(more ? row + (int)gridDim.x : row) * n + first;
+    const uint32_t* __restrict__ next_bits = bits + (int64_t)(more ? row + (int)gridDim.x : row) * p.n + first;
+    // this row's geometry was settled when its load was issued; the next row's decides what is fetched for it
+    int n_next = 0, k_next = 0;
+    if (more) row_geometry(p, row + (int)gridDim.x, n_next, k_next);
+    const int nv_next = more ? groups_inside(n_next) : 0;
+    pad_row(out, k_row, p.k, tid);
+    if (k_row == 0) {
+        // a row of padding (uniform over the workgroup): nothing to select, only the next row's load
+#pragma unroll
+        for (int i = 0; i < V4; ++i) {
+            if (i < nv_next) {
+                const u32x4 v = *(const u32x4*)(next_bits + i * 256);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) key[i][c] = v[c];
+            }
+        }
+        n = n_next; k_row = k_next; nv = nv_next;
+        continue;
+    }
+    const bool straddles = (n & 3) != 0;              // uniform: variable-length rows only
 
     uint32_t kmax = 0u, kmin = 0xFFFFFFFFu;
 #pragma unroll
@@ -190,7 +238,7 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             key[i][c] = order_key_of_bits(key[i][c]);
-            if (i < nv) {
+            if (i < nv && (!straddles || first + i * 256 + c < n)) {
                 kmax = key[i][c] > kmax ? key[i][c] : kmax;
                 kmin = key[i][c] < kmin ? key[i][c] : kmin;
             }
@@ -206,13 +254,23 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
         kmin = wave_b[w] < kmin ? wave_b[w] : kmin;
     }
     __syncthreads();                                   // wave_a / wave_b are reused below
+    if (straddles) {
+        // the elements a 16-byte load brought in from behind the row's end take the row's smallest key: they
+        // follow every real element in index order, so the selection (k_row <= n real elements) never reaches them
+#pragma unroll
+        for (int i = 0; i < V4; ++i) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (i < nv && first + i * 256 + c >= n) key[i][c] = kmin;
+        }
+    }
 
     // ---- radix select: afterwards `prefix` is the key of the k-th largest element and `need`
     //      how many elements equal to it belong to the top-k.  Bits above `hi` are the same in
     //      every key of the row.
     int hi = 31 - __clz((int)(kmax ^ kmin));           // -1 if all keys are equal
     uint32_t prefix = hi >= 31 ? 0u : ((kmax >> (hi + 1)) << (hi + 1));
-    uint32_t need = (uint32_t)p.k;
+    uint32_t need = (uint32_t)k_row;
     // register groups of this lane that still hold an element matching the prefix: all of them in
     // the first pass, next to none later (a bin of the first pass holds n/8192 elements on
     // average), so that the later passes skip almost all of their work, whole waves at a time
@@ -355,7 +413,7 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
     };
 #pragma unroll
     for (int i = 0; i < V4; ++i) {
-        if (wave * SEG + i * 256 >= n) break;          // uniform: nothing of this wave lies beyond
+      if (wave * SEG + i * 256 < n) {                  // uniform: nothing of this wave lies beyond
         const bool in = i < nv;
         // elements equal to the threshold are rare (ties at the k-th value): the four ballots that
         // rank them are taken only if the wave holds one in this register group
@@ -384,19 +442,21 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             if (sel[c]) {
-                if (pos < (uint32_t)p.k) out[pos] = first + i * 256 + c;     // guard: holds by construction
+                if (pos < (uint32_t)k_row) out[pos] = first + i * 256 + c;     // guard: holds by construction
                 ++pos;
             }
         }
         eq_seen += eq_all;
         out_pos += sel_all;
-        if (more && in) {
+      }
+        // the compaction is done with this register group: refill it with the next row's scores
+        if (i < nv_next) {
             const u32x4 v = *(const u32x4*)(next_bits + i * 256);
 #pragma unroll
             for (int c = 0; c < 4; ++c) key[i][c] = v[c];
         }
     }
-    // register groups beyond this wave's share of the row were skipped above; they hold nothing
+    n = n_next; k_row = k_next; nv = nv_next;
     __syncthreads();                                   // wave_a / wave_b are rewritten by the next row
   }
 }

@@ -7,13 +7,22 @@ namespace pulsecol {
 namespace {
 
 __global__ void __launch_bounds__(256) index_range_kernel(const int32_t* __restrict__ idx, int64_t count, int32_t n,
-                                                          int32_t* __restrict__ bad_count) {
+                                                          int32_t* __restrict__ bad_count,
+                                                          const int32_t* __restrict__ varlen, int32_t batch,
+                                                          int64_t per_batch, int32_t k) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     int bad = 0;
     for (; i < count; i += stride) {
         const int32_t c = idx[i];
-        bad += (c < 0 || c >= n) ? 1 : 0;
+        if (varlen == nullptr) {
+            bad += (c < 0 || c >= n) ? 1 : 0;
+        } else {
+            // variable-length batch: the leading `kept` entries of a row count, against the element's own length
+            const int b = (int)(i / per_batch);
+            const int pos = (int)(i % k);
+            bad += (pos < varlen[batch + b] && (c < 0 || c >= varlen[b])) ? 1 : 0;
+        }
     }
     // one atomic per wavefront that saw a bad entry (vector atomics; the count only needs to be non-zero)
     const unsigned long long any = __ballot(bad != 0);
@@ -22,12 +31,13 @@ __global__ void __launch_bounds__(256) index_range_kernel(const int32_t* __restr
 
 }  // namespace
 
-hipError_t launch_index_range_check(const int32_t* idx, int64_t count, int32_t n, int32_t* bad_count, hipStream_t s) {
+hipError_t launch_index_range_check(const int32_t* idx, int64_t count, int32_t n, int32_t* bad_count,
+                                    const int32_t* varlen, int32_t batch, int64_t per_batch, int32_t k, hipStream_t s) {
     hipError_t e = hipMemsetAsync(bad_count, 0, sizeof(int32_t), s);
     if (e != hipSuccess) return e;
     const int64_t blocks = (count + 255) / 256;
     const int grid = (int)(blocks < 4096 ? (blocks < 1 ? 1 : blocks) : 4096);
-    hipLaunchKernelGGL(index_range_kernel, dim3(grid), dim3(256), 0, s, idx, count, n, bad_count);
+    hipLaunchKernelGGL(index_range_kernel, dim3(grid), dim3(256), 0, s, idx, count, n, bad_count, varlen, batch, per_batch, k);
     return hipGetLastError();
 }
 

@@ -20,7 +20,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_ALIGNMENT, ERR_NO_PATTERN, ERR_OOM, ER
 BF16, F32 = 0, 1
 
 EXPORTS = (
-    "pulsecol_validate_shape", "pulsecol_create", "pulsecol_destroy", "pulsecol_set_validation", "pulsecol_num_keep",
+    "pulsecol_validate_shape", "pulsecol_create", "pulsecol_destroy", "pulsecol_set_validation", "pulsecol_set_seq_lens", "pulsecol_num_keep",
     "pulsecol_select", "pulsecol_scores", "pulsecol_topk", "pulsecol_attn", "pulsecol_attn_dense",
     "pulsecol_refresh_dense", "pulsecol_select_noalloc",
     "pulsecol_refresh_schedule", "pulsecol_refresh_schedule_power", "pulsecol_refresh_schedule_random",
@@ -57,6 +57,7 @@ def lib() -> ctypes.CDLL:
         L.pulsecol_create.argtypes = [POINTER(c_void_p), POINTER(Shape), c_int]
         L.pulsecol_destroy.argtypes = [c_void_p]
         L.pulsecol_set_validation.argtypes = [c_void_p, c_int]
+        L.pulsecol_set_seq_lens.argtypes = [c_void_p, POINTER(c_int32), c_void_p]
         L.pulsecol_num_keep.argtypes = [c_int32, c_double]
         L.pulsecol_num_keep.restype = c_int32
         L.pulsecol_select.argtypes = [c_void_p, c_void_p, c_void_p, c_double, c_int, c_void_p, c_void_p]
@@ -230,6 +231,16 @@ class Context:
     def set_validation(self, on: bool = True):
         """Check column numbers on the device in front of every attn call (synchronises)."""
         self._check(lib().pulsecol_set_validation(self._h, int(bool(on))))
+
+    def set_seq_lens(self, seq_lens=None):
+        """Variable-length batch: per-element lengths (a sequence of `batch` ints), or None for fixed length."""
+        if seq_lens is None:
+            self._check(lib().pulsecol_set_seq_lens(self._h, None, _stream()))
+            return
+        lens = [int(x) for x in seq_lens]
+        if len(lens) != self.shape.batch:
+            raise ValueError("seq_lens: one length per batch element")
+        self._check(lib().pulsecol_set_seq_lens(self._h, (c_int32 * len(lens))(*lens), _stream()))
 
     def tile_shape(self):
         bm, bn = c_int32(), c_int32()
