@@ -130,7 +130,7 @@ def main():
     O = torch.empty_like(Q)
     idx = torch.empty(B, H, 1, k, dtype=torch.int32, device=dev)
     ctx = pc.Context(B, H, n, d, w.torch_dtype, max_keep_ratio=keep)
-    block_m, block_n = ctx.tile_shape()
+    block_m, block_n = ctx.tile_shape(k)
 
     if a.copy_gib > 0:
         src = torch.zeros(int(a.copy_gib * 2**30) // 4, dtype=torch.float32, device=dev)
@@ -199,7 +199,8 @@ def main():
     achieved = kept_flop / (attn_ms * 1e-3) * 1e-12
     algorithmic_bytes = B * H * (2 * n * d + 2 * k * d) * Q.element_size() + B * H * 4 * k     # Q, O, selected K and V rows once, idx
     traffic, traffic_source = measured_traffic(w.name, keep)
-    kernel = (f"attn_bf16_kernel<{d}, sparse> ({block_m}-row query blocks, {block_n}-column tiles)" if w.dtype == "bf16"
+    kernel = (f"{'attn_bf16_kernel' if block_m == 256 else 'attn_bf16_group_kernel'}<{d}, sparse> ({block_m}-row query blocks, "
+              f"{block_n}-column tiles)" if w.dtype == "bf16"
               else f"attn_f32_kernel<{d}, sparse> ({block_m}-row query blocks, {block_n}-column tiles)")
 
     out = {
@@ -308,8 +309,10 @@ def reuse_config(pc, wl, torch, dev, name):
     attn_ms = timed(torch, lambda: ctx.attn(Q, K, V, idx, O=O), 50)
     select_ms = timed(torch, lambda: ctx.select(Q, K, keep, refresh=True, idx_out=idx), 5)
     dense_ms = timed(torch, lambda: ctx.attn_dense(Q, K, V, O=O), 10)
+    block_m, block_n = ctx.tile_shape(k)
     ctx.close()
     return {"workload": name, "seq": n, "keep": keep, "k": k, "steps": w.steps, "refresh_steps": [0],
+            "block_m": block_m, "block_n": block_n,
             "total_ms": round(total_ms, 4), "ms_per_step": round(total_ms / w.steps, 4),
             "attn_ms": round(attn_ms, 4), "select_ms": round(select_ms, 4), "dense_ms": round(dense_ms, 4),
             "kept_tflops": round(4.0 * B * H * n * k * d / (attn_ms * 1e-3) * 1e-12, 2),

@@ -114,6 +114,13 @@ PULSECOL_API pulsecol_status pulsecol_create(pulsecol_ctx** out, const pulsecol_
  * returns PULSECOL_ERR_BAD_INDEX without launching the attention kernel if one does not. */
 PULSECOL_API pulsecol_status pulsecol_set_validation(pulsecol_ctx* ctx, int on);
 
+/* Which kernel pulsecol_attn runs when the context has one column set per head (bf16): 256 = the
+ * hand-scheduled kernel with 256-row query blocks, 128 = the plain kernel with 128-row blocks,
+ * 0 (the default) = whichever a small cost model expects to finish first for the call's k (the plain
+ * kernel for short jobs, a few query blocks per compute unit; the scheduled one otherwise).  Results
+ * agree within the tolerance of the method either way.  Ignored for group-wise sets and fp32. */
+PULSECOL_API pulsecol_status pulsecol_set_attn_block(pulsecol_ctx* ctx, int32_t block_m);
+
 /* Variable-length batches: a padded batch whose elements have their own lengths.  seq_lens is a HOST
  * array of `batch` ints, 1 <= seq_lens[b] <= seq, copied by the call (it rides in the arguments of
  * small launches on `stream`: no host-to-device copy, no synchronisation); NULL returns the context
@@ -222,9 +229,9 @@ PULSECOL_API int32_t pulsecol_refresh_schedule_power(int32_t T, double eta, int3
 PULSECOL_API int32_t pulsecol_refresh_schedule_random(int32_t T, double eta, int32_t R, const double* uniforms,
                                          int32_t* steps_out);
 
-/* Launch geometry of the sparse kernel for this context (for reports): query rows per
- * workgroup (B_M) and gathered columns per tile (B_N).  Host only. */
-PULSECOL_API pulsecol_status pulsecol_attn_tile_shape(const pulsecol_ctx* ctx, int32_t* block_m, int32_t* block_n);
+/* Launch geometry of the kernel that pulsecol_attn runs on this context with k kept columns (for
+ * reports): query rows per workgroup (B_M) and gathered columns per tile (B_N).  Host only. */
+PULSECOL_API pulsecol_status pulsecol_attn_tile_shape(const pulsecol_ctx* ctx, int32_t k, int32_t* block_m, int32_t* block_n);
 
 PULSECOL_API const char* pulsecol_status_str(pulsecol_status status);
 PULSECOL_API const char* pulsecol_last_error(const pulsecol_ctx* ctx);

@@ -34,6 +34,7 @@ struct pulsecol_ctx {
     bool validate = false;          // check column numbers in front of every pulsecol_attn
     int32_t* varlen = nullptr;      // [2 * batch] device words of variable-length batches: lengths, kept counts
     bool varlen_on = false;         // pulsecol_set_seq_lens has given per-element lengths
+    int attn_block = 0;             // 0: the cost model picks the one-set-per-head kernel; 256 / 128: the caller has
     std::string last_error;
 };
 
@@ -165,18 +166,30 @@ pulsecol::AttnParams attn_params(pulsecol_ctx* c, const void* Q, const void* K, 
     return p;
 }
 
-// query rows per workgroup of the column-sparse kernel this context uses: the largest block
-// that divides the group size
-int sparse_block_m(const pulsecol_ctx* c) {
+// Query rows per workgroup of the column-sparse kernel a call with ns kept columns runs in.  Group-wise
+// sets: the largest block that divides the group size.  One set per head: the hand-scheduled kernel
+// with 256-row blocks, except for short jobs, where its fixed costs (one workgroup per CU, a long
+// start-up per launch and per query block) outweigh its faster steady state and the plain kernel
+// with 128-row blocks, three to a CU, finishes first.  The rule is a two-line cost model fitted to
+// launches at 4K to 16K context (microseconds; R = 256-row blocks per CU, t = 64-column tiles):
+//   scheduled: 33 + R (8.7 + 1.64 t)      plain: 12.6 + R (3.1 + 2.23 t)
+int sparse_block_m(const pulsecol_ctx* c, int32_t ns) {
     if (c->shape.dtype != PULSECOL_BF16) return pulsecol::kBlockM_f32;
-    if (c->groups == 1) return pulsecol::kBlockM_bf16;
+    if (c->groups == 1) {
+        if (c->attn_block != 0) return c->attn_block;
+        const double blocks = (double)((c->shape.seq + 255) / 256) * c->shape.batch * c->shape.heads;
+        const double R = blocks / (double)pulsecol::compute_units();
+        const double t = (double)((ns + 63) / 64);
+        const double scheduled = 33.0 + R * (8.7 + 1.64 * t), plain = 12.6 + R * (3.1 + 2.23 * t);
+        return plain < scheduled ? 128 : pulsecol::kBlockM_bf16;
+    }
     for (int bm : {256, 128, 64}) if (c->shape.group_size % bm == 0) return bm;
     return 32;
 }
 
 hipError_t launch_attn(const pulsecol_ctx* c, const pulsecol::AttnParams& p, pulsecol::AttnMode mode, hipStream_t s) {
-    if (mode == pulsecol::kSparse && c->shape.dtype == PULSECOL_BF16 && sparse_block_m(c) < pulsecol::kBlockM_bf16)
-        return pulsecol::launch_attn_bf16_group(p, c->shape.head_dim, sparse_block_m(c), s);
+    if (mode == pulsecol::kSparse && c->shape.dtype == PULSECOL_BF16 && sparse_block_m(c, p.ns) < pulsecol::kBlockM_bf16)
+        return pulsecol::launch_attn_bf16_group(p, c->shape.head_dim, sparse_block_m(c, p.ns), s);
     return c->shape.dtype == PULSECOL_BF16 ? pulsecol::launch_attn_bf16(p, c->shape.head_dim, mode, s)
                                            : pulsecol::launch_attn_f32(p, c->shape.head_dim, mode, s);
 }
@@ -331,6 +344,14 @@ pulsecol_status pulsecol_create(pulsecol_ctx** out, const pulsecol_shape* shape,
 pulsecol_status pulsecol_set_validation(pulsecol_ctx* ctx, int on) {
     if (!ctx) return fail(nullptr, PULSECOL_ERR_INVALID_ARG, "pulsecol_set_validation: ctx is NULL");
     ctx->validate = on != 0;
+    return PULSECOL_OK;
+}
+
+pulsecol_status pulsecol_set_attn_block(pulsecol_ctx* ctx, int32_t block_m) {
+    if (!ctx) return fail(nullptr, PULSECOL_ERR_INVALID_ARG, "pulsecol_set_attn_block: ctx is NULL");
+    if (block_m != 0 && block_m != 128 && block_m != 256)
+        return fail(ctx, PULSECOL_ERR_INVALID_ARG, "pulsecol_set_attn_block: block_m must be 0, 128 or 256");
+    ctx->attn_block = block_m;
     return PULSECOL_OK;
 }
 
@@ -569,10 +590,11 @@ int32_t pulsecol_refresh_schedule_random(int32_t T, double eta, int32_t R, const
     return R;
 }
 
-pulsecol_status pulsecol_attn_tile_shape(const pulsecol_ctx* ctx, int32_t* block_m, int32_t* block_n) {
+pulsecol_status pulsecol_attn_tile_shape(const pulsecol_ctx* ctx, int32_t k, int32_t* block_m, int32_t* block_n) {
     if (!ctx || !block_m || !block_n) return fail(nullptr, PULSECOL_ERR_INVALID_ARG, "pulsecol_attn_tile_shape: NULL pointer");
+    if (k < 1 || k > ctx->shape.seq) return fail(nullptr, PULSECOL_ERR_INVALID_ARG, "pulsecol_attn_tile_shape: need 1 <= k <= seq");
     const bool bf = ctx->shape.dtype == PULSECOL_BF16;
-    *block_m = sparse_block_m(ctx);
+    *block_m = sparse_block_m(ctx, k);
     *block_n = !bf ? pulsecol::kBlockN_f32 : (*block_m < pulsecol::kBlockM_bf16 ? 32 : pulsecol::kBlockN_bf16);
     return PULSECOL_OK;
 }

@@ -20,7 +20,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_ALIGNMENT, ERR_NO_PATTERN, ERR_OOM, ER
 BF16, F32 = 0, 1
 
 EXPORTS = (
-    "pulsecol_validate_shape", "pulsecol_create", "pulsecol_destroy", "pulsecol_set_validation", "pulsecol_set_seq_lens", "pulsecol_num_keep",
+    "pulsecol_validate_shape", "pulsecol_create", "pulsecol_destroy", "pulsecol_set_validation", "pulsecol_set_attn_block", "pulsecol_set_seq_lens", "pulsecol_num_keep",
     "pulsecol_select", "pulsecol_scores", "pulsecol_topk", "pulsecol_attn", "pulsecol_attn_dense",
     "pulsecol_refresh_dense", "pulsecol_select_noalloc",
     "pulsecol_refresh_schedule", "pulsecol_refresh_schedule_power", "pulsecol_refresh_schedule_random",
@@ -44,6 +44,9 @@ class PulseColError(RuntimeError):
 
 
 _lib = None
+# block size every new Context asks for with one set per head (0 = the library's own choice); the test-suite
+# sets it to run the same cases through both kernels
+DEFAULT_ATTN_BLOCK = 0
 
 
 def lib() -> ctypes.CDLL:
@@ -57,6 +60,7 @@ def lib() -> ctypes.CDLL:
         L.pulsecol_create.argtypes = [POINTER(c_void_p), POINTER(Shape), c_int]
         L.pulsecol_destroy.argtypes = [c_void_p]
         L.pulsecol_set_validation.argtypes = [c_void_p, c_int]
+        L.pulsecol_set_attn_block.argtypes = [c_void_p, c_int32]
         L.pulsecol_set_seq_lens.argtypes = [c_void_p, POINTER(c_int32), c_void_p]
         L.pulsecol_num_keep.argtypes = [c_int32, c_double]
         L.pulsecol_num_keep.restype = c_int32
@@ -73,7 +77,7 @@ def lib() -> ctypes.CDLL:
         L.pulsecol_refresh_schedule_power.restype = c_int32
         L.pulsecol_refresh_schedule_random.argtypes = [c_int32, c_double, c_int32, POINTER(c_double), POINTER(c_int32)]
         L.pulsecol_refresh_schedule_random.restype = c_int32
-        L.pulsecol_attn_tile_shape.argtypes = [c_void_p, POINTER(c_int32), POINTER(c_int32)]
+        L.pulsecol_attn_tile_shape.argtypes = [c_void_p, c_int32, POINTER(c_int32), POINTER(c_int32)]
         L.pulsecol_status_str.argtypes = [c_int]
         L.pulsecol_status_str.restype = c_char_p
         L.pulsecol_last_error.argtypes = [c_void_p]
@@ -170,6 +174,8 @@ class Context:
         if st != OK:
             self._h = None
             raise PulseColError(st, last_error(None))
+        if DEFAULT_ATTN_BLOCK:
+            self.set_attn_block(DEFAULT_ATTN_BLOCK)
 
     # -- lifetime
     def close(self):
@@ -232,6 +238,10 @@ class Context:
         """Check column numbers on the device in front of every attn call (synchronises)."""
         self._check(lib().pulsecol_set_validation(self._h, int(bool(on))))
 
+    def set_attn_block(self, block_m: int = 0):
+        """Kernel of attn with one set per head: 256 scheduled, 128 plain, 0 the library's choice."""
+        self._check(lib().pulsecol_set_attn_block(self._h, int(block_m)))
+
     def set_seq_lens(self, seq_lens=None):
         """Variable-length batch: per-element lengths (a sequence of `batch` ints), or None for fixed length."""
         if seq_lens is None:
@@ -242,9 +252,10 @@ class Context:
             raise ValueError("seq_lens: one length per batch element")
         self._check(lib().pulsecol_set_seq_lens(self._h, (c_int32 * len(lens))(*lens), _stream()))
 
-    def tile_shape(self):
+    def tile_shape(self, k: int):
+        """(B_M, B_N) of the kernel that attn runs with k kept columns."""
         bm, bn = c_int32(), c_int32()
-        self._check(lib().pulsecol_attn_tile_shape(self._h, ctypes.byref(bm), ctypes.byref(bn)))
+        self._check(lib().pulsecol_attn_tile_shape(self._h, k, ctypes.byref(bm), ctypes.byref(bn)))
         return bm.value, bn.value
 
     # -- the calls of include/pulsecol.h

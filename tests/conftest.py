@@ -27,3 +27,24 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+# With one column set per head the library picks between two attention kernels by job size, and small
+# test shapes would all land in one of them: these modules run every test through both.
+BOTH_ATTN_KERNELS = {"test_gpu_parity", "test_gpu_random_shapes", "test_gpu_logit_range", "test_gpu_gqa",
+                     "test_gpu_varlen"}
+
+
+@pytest.fixture(autouse=True)
+def attn_kernel(request):
+    block = getattr(request, "param", 0)
+    from paper_2605_20813_amd import pulsecol as pc
+    old = pc.DEFAULT_ATTN_BLOCK
+    pc.DEFAULT_ATTN_BLOCK = block
+    yield block
+    pc.DEFAULT_ATTN_BLOCK = old
+
+
+def pytest_generate_tests(metafunc):
+    if metafunc.module.__name__.split(".")[-1] in BOTH_ATTN_KERNELS:
+        metafunc.parametrize("attn_kernel", [256, 128], indirect=True, ids=["scheduled", "plain"])

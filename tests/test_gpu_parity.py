@@ -85,7 +85,7 @@ def test_dense_attention_and_lse_match_oracle(B, H, n, d, dtype):
             np.testing.assert_allclose(f64(lse[b, h]), want_lse, rtol=0, atol=2e-5 * max(1.0, np.abs(want_lse).max()))
 
 
-def test_keep_everything_equals_dense_on_gpu_and_oracle():
+def test_keep_everything_equals_dense_on_gpu_and_oracle(attn_kernel):
     B, H, n, d = 1, 2, 640, 128
     say("keep=1 case")
     Q, K, V = rand_qkv(B, H, n, d, torch.bfloat16, seed=31)
@@ -95,7 +95,10 @@ def test_keep_everything_equals_dense_on_gpu_and_oracle():
         Os = ctx.attn(q, k_, v, every.to(DEV))
         Od = ctx.attn_dense(q, k_, v)
         torch.cuda.synchronize()
-    assert torch.equal(Os, Od)      # same tiles in the same order: bit-identical
+    if attn_kernel == 256:
+        assert torch.equal(Os, Od)      # the dense kernel is the scheduled one: same tiles in the same order, bit-identical
+    else:
+        assert (Os.float() - Od.float()).abs().max().item() <= TOL["bf16"]["max_abs"]
     for h in range(H):
         assert_close(Os[0, h], oracle.dense_attention(f64(Q[0, h]), f64(K[0, h]), f64(V[0, h])), "bf16", "keep=1")
 
