@@ -1,7 +1,8 @@
-"""Static check of the hand-scheduled attention kernel's generated code (no GPU needed).
+"""Static check of the generated code of the kernels that issue loads from inline assembly (no GPU needed).
 
-attn_bf16.hip issues some loads from inline assembly (row numbers of the next tile, LDS fragment
-reads), which the compiler takes for ordinary instructions whose result is there at once.  Two
+attn_bf16.hip (row numbers of the next tile, LDS fragment reads) and colmass_bf16.hip (LDS fragment and
+log-sum-exp reads) issue some loads from inline assembly, which the compiler takes for ordinary
+instructions whose result is there at once.  Two
 things must therefore hold in the generated code, and neither is visible in the source:
 
   * nothing reads or overwrites the destination registers of such a load before a wait that
@@ -151,19 +152,29 @@ def test_checker_sees_a_copy_behind_an_asynchronous_load():
     assert len(bad) == 1 and "offset:0x400" in bad[0][1]
 
 
-@pytest.mark.skipif(shutil.which("hipcc") is None and not os.path.exists("/opt/rocm/bin/hipcc"), reason="needs hipcc")
-def test_no_instruction_touches_an_assembly_issued_load_in_flight():
+def _assembly_of(source):
     from paper_2605_20813_amd import build
     hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
     flags = [f for f in build.HIPCC_FLAGS if f not in ("-fPIC", "-fvisibility=hidden")]
     with tempfile.TemporaryDirectory() as tmp:
-        out = os.path.join(tmp, "attn_bf16.s")
-        subprocess.run([hipcc, *flags, "-S", "--cuda-device-only", "-o", out, os.path.join(CSRC, "attn_bf16.hip")],
+        out = os.path.join(tmp, "kernel.s")
+        subprocess.run([hipcc, *flags, "-S", "--cuda-device-only", "-o", out, os.path.join(CSRC, source)],
                        check=True, capture_output=True)
-        text = open(out).read()
+        return open(out).read()
+
+
+# file, kernel name, instantiations expected (attention: three modes x two head dimensions; column pass: two
+# head dimensions)
+CHECKED = [("attn_bf16.hip", "attn_bf16_kernel", 6), ("colmass_bf16.hip", "colmass_bf16_kernel", 2)]
+
+
+@pytest.mark.skipif(shutil.which("hipcc") is None and not os.path.exists("/opt/rocm/bin/hipcc"), reason="needs hipcc")
+@pytest.mark.parametrize("source,kernel,count", CHECKED)
+def test_no_instruction_touches_an_assembly_issued_load_in_flight(source, kernel, count):
+    text = _assembly_of(source)
     found = 0
-    for name, lines in kernels_of(text, "attn_bf16_kernel"):
+    for name, lines in kernels_of(text, kernel):
         found += 1
         bad = check_function(lines)
         assert not bad, "%s: %d hazards, first: line %d `%s` touches %s" % (name, len(bad), bad[0][0], bad[0][1], bad[0][2])
-    assert found >= 6          # three modes x two head dimensions
+    assert found >= count
