@@ -464,20 +464,27 @@ def groupwise_config(pc, torch, dev, w, keep, G, host_qkv):
     extra = {}
     if G >= 256:
         # In-house block-sparse point at the same budget (the paper's Sec. 3.1 block mask
-        # S(i,j) = G(b(i), b(j)) with query blocks = the groups and key blocks of 64): the same
-        # kernel fed whole key blocks, chosen by block mass.  Index bookkeeping with torch ops --
-        # this is a comparison input, not part of the product path.  "mass" = share of the
-        # group's softmax mass that the kept columns carry (the scores of a group sum to one).
-        kb = max(1, k // 64)
-        blocks = scores.view(B, H, U, n // 64, 64).sum(-1).topk(kb, dim=-1).indices.sort(dim=-1).values
-        bs_idx = (blocks[..., None] * 64 + torch.arange(64, device=dev)).view(B, H, U, kb * 64).to(torch.int32).contiguous()
-        bs_ms = timed(torch, lambda: ctx.attn(Q, K, V, bs_idx, O=O), 10)
+        # S(i,j) = G(b(i), b(j)) with query blocks = the groups and key blocks of 64): the library's block
+        # selection (key blocks by block mass) and its block-sparse kernel (a tile = one key block, fetched
+        # as 64 consecutive rows from one block number), beside the same sets expanded to columns and fed
+        # to the column-sparse kernel.  "mass" = share of a group's softmax mass that the kept columns
+        # carry (the scores of a group sum to one), from the scores with torch ops (a report, not the path).
+        kb = pc.num_keep_blocks(n, keep)
+        blk = torch.empty(B, H, U, kb, dtype=torch.int32, device=dev)
+        bs_select_ms = timed(torch, lambda: ctx.select_blocks(Q, K, keep, block_idx_out=blk), 1)
+        bs_ms = timed(torch, lambda: ctx.attn_block(Q, K, V, blk, O=O), 10)
+        bs_idx = (blk[..., None].long() * 64 + torch.arange(64, device=dev)).view(B, H, U, kb * 64).to(torch.int32).contiguous()
+        bs_cols_ms = timed(torch, lambda: ctx.attn(Q, K, V, bs_idx, O=O), 10)
+        ctx.scores(Q, K, scores_out=scores)
         mass_cs = scores.gather(-1, idx.long()).sum(-1).mean().item()
         mass_bs = scores.gather(-1, bs_idx.long()).sum(-1).mean().item()
-        extra = {"block_sparse_same_budget": {"key_block": 64, "kept_columns": kb * 64, "attn_ms": round(bs_ms, 4),
+        extra = {"block_sparse_same_budget": {"key_block": 64, "kept_blocks": kb, "kept_columns": kb * 64,
+                                              "select_blocks_ms": round(bs_select_ms, 3), "attn_block_ms": round(bs_ms, 4),
+                                              "kept_tflops": round(4.0 * B * H * n * kb * 64 * d / (bs_ms * 1e-3) * 1e-12, 2),
+                                              "same_sets_through_column_kernel_ms": round(bs_cols_ms, 4),
                                               "mass_kept": round(mass_bs, 4)},
                  "column_sparse_mass_kept": round(mass_cs, 4)}
-        del blocks, bs_idx
+        del blk, bs_idx
     topk_bytes = B * H * U * (4 * n + 4 * k)
     gather_bytes = B * H * U * 2 * k * d * 2 + 2 * B * H * n * d * 2      # K and V rows per group, Q, O
     res = {"group_size": G, "groups_per_head": U, "k": k,

@@ -180,6 +180,27 @@ PULSECOL_API pulsecol_status pulsecol_topk(pulsecol_ctx* ctx, const float* score
 PULSECOL_API pulsecol_status pulsecol_attn(pulsecol_ctx* ctx, const void* Q, const void* K, const void* V,
                               const int32_t* idx, int32_t k, void* O, void* stream);
 
+/* Block-sparse attention, the formulation the paper contrasts column sparsity with (Sec. 3.1, block-mask
+ * equation S(i, j) = G(b(i), b(j))): query blocks are the context's query groups (the whole head, or
+ * group_size rows, a multiple of 256), key blocks are 64 consecutive keys.  block_idx[B, H, U, kb] (device,
+ * int32) names the key blocks each query block attends to, unique and in [0, seq / 64); the result is
+ * softmax(Z + M(S)) V with that mask.  One kernel with the column-sparse one: a tile is a whole key block,
+ * fetched as 64 consecutive rows from one block number instead of 64 gathered rows.  bf16 contexts with
+ * seq a multiple of 64 and fixed-length batches, else PULSECOL_ERR_UNSUPPORTED. */
+PULSECOL_API pulsecol_status pulsecol_attn_block(pulsecol_ctx* ctx, const void* Q, const void* K, const void* V,
+                                    const int32_t* block_idx, int32_t kb, void* O, void* stream);
+
+/* Key blocks kept at a ratio: max(1, floor(keep_ratio * seq / 64)) (the same budget rule on blocks); -1 on
+ * seq not a multiple of 64 or a ratio outside (0, 1].  Host only. */
+PULSECOL_API int32_t pulsecol_num_keep_blocks(int32_t seq, double keep_ratio);
+
+/* Block selection for pulsecol_attn_block, by the same evidence as the column selection: the mass of a
+ * key block is the sum of the column scores (Sec. 3.3, score equation) of its 64 keys, and every query
+ * block keeps the kb = pulsecol_num_keep_blocks(seq, keep_ratio) heaviest key blocks (equal masses: lower
+ * block number wins), written ascending to block_idx_out[B, H, U, kb].  Nothing is cached. */
+PULSECOL_API pulsecol_status pulsecol_select_blocks(pulsecol_ctx* ctx, const void* Q, const void* K, double keep_ratio,
+                                       int32_t* block_idx_out, void* stream);
+
 /* Dense attention baseline O = softmax(Q K^T * scale) V (Sec. 3.1).  If lse_out is not NULL
  * it receives the row log-sum-exp of the scaled logits, fp32 [B, H, seq]. */
 PULSECOL_API pulsecol_status pulsecol_attn_dense(pulsecol_ctx* ctx, const void* Q, const void* K, const void* V,

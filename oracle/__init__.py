@@ -8,6 +8,9 @@ check and the benchmark's ``cpu_baseline`` leg may use it.
 
 from .pulsecol_oracle import (  # noqa: F401
     attention_logits,
+    block_columns,
+    block_scores,
+    block_sparse_attention,
     column_scores,
     dense_attention,
     num_keep,
@@ -15,6 +18,7 @@ from .pulsecol_oracle import (  # noqa: F401
     refresh_schedule_power,
     refresh_schedule_random,
     row_softmax,
+    select_blocks,
     select_columns,
     sparse_attention_chunked,
     sparse_attention_gathered,

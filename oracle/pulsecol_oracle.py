@@ -246,6 +246,53 @@ def sparse_attention_chunked(Q, K, V, idx, chunk: int, group_size: int = 0,
 
 
 # --------------------------------------------------------------------------
+# Eq. 4: block-sparse attention (the formulation column sparsity is contrasted with)
+# --------------------------------------------------------------------------
+def block_columns(block_idx, key_block: int) -> np.ndarray:
+    """The key columns of the key blocks in ``block_idx[U, kb]``: block c holds columns
+    c * key_block .. (c + 1) * key_block - 1.  Returns int64 ``[U, kb * key_block]``."""
+    blocks = np.atleast_2d(np.asarray(block_idx, dtype=np.int64))
+    if key_block < 1:
+        raise ValueError("key_block must be >= 1")
+    return (blocks[:, :, None] * key_block + np.arange(key_block)[None, None, :]).reshape(blocks.shape[0], -1)
+
+
+def block_sparse_attention(Q, K, V, block_idx, key_block: int, group_size: int = 0,
+                           scale: float | None = None, rows=None) -> np.ndarray:
+    """A~ = softmax(Z + M(S)) V with the block mask S(i, j) = G(b(i), b(j)).
+
+    Sec. 3.1, block-mask equation: b(.) maps a position to its block, G is a 0/1 matrix over
+    (query block, key block).  Query blocks are the contiguous groups of ``group_size`` rows (0: all
+    rows are one block), key blocks are ``key_block`` consecutive keys; row u of ``block_idx`` lists
+    the key blocks c with G[u, c] = 1.  The sequence length must be a multiple of ``key_block``.
+    """
+    K = _as_f64(K)
+    if K.shape[0] % key_block:
+        raise ValueError("the key count must be a multiple of key_block")
+    return sparse_attention_masked(Q, K, V, block_columns(block_idx, key_block), group_size, scale, rows)
+
+
+def block_scores(Q, K, key_block: int, group_size: int = 0, scale: float | None = None) -> np.ndarray:
+    """Mass of every key block for every query group: the sum of the group's column scores (Sec. 3.3,
+    score equation) over the block's keys.  Returns float64 ``[U, n / key_block]``; each row sums to 1."""
+    s = column_scores(Q, K, group_size, scale)
+    U, n = s.shape
+    if n % key_block:
+        raise ValueError("the key count must be a multiple of key_block")
+    return s.reshape(U, n // key_block, key_block).sum(axis=2)
+
+
+def select_blocks(Q, K, keep_ratio: float, key_block: int, group_size: int = 0,
+                  scale: float | None = None) -> np.ndarray:
+    """Key blocks kept under the same budget rule applied to blocks: the
+    max(1, floor(keep_ratio * n / key_block)) heaviest blocks per query group, ascending."""
+    n = np.asarray(K).shape[0]
+    if n % key_block:
+        raise ValueError("the key count must be a multiple of key_block")
+    return topk_columns(block_scores(Q, K, key_block, group_size, scale), num_keep(n // key_block, keep_ratio))
+
+
+# --------------------------------------------------------------------------
 # Eq. 8: refresh schedule
 # --------------------------------------------------------------------------
 def refresh_schedule(T: int, eta: float, R: int) -> list[int]:

@@ -44,6 +44,7 @@
 // statement whose output is the whole variable, nothing reads the variable before the wait
 // that covers it, and every such variable is named by a statement behind that wait (which
 // keeps its registers reserved).  tests/test_asm_hazards.py checks the generated code.
+#include <type_traits>
 #include <utility>
 
 #include "pulsecol_device.h"
@@ -159,7 +160,8 @@ struct AttnWave {
     static constexpr int ROWS_PER_CHUNK = 64 / PIECES;   // one direct-to-LDS load instruction moves 64 x 16 bytes
     static constexpr int CH = BN / ROWS_PER_CHUNK / 4;   // such instructions per wave and tile (per operand)
     static constexpr bool HAS_V = (MODE != kLseOnly);
-    static constexpr bool GATHER = (MODE == kSparse);
+    static constexpr bool BLOCKS = (MODE == kBlock);       // block-sparse: a tile is one block of BN consecutive keys
+    static constexpr bool GATHER = (MODE == kSparse || MODE == kBlock);
     static constexpr int ODB = HAS_V ? DB : 1;
     static constexpr int NPV = HAS_V ? 2 * DB : 0;       // V fragments (= MFMA pairs) of a half-step
     static constexpr int NP = KK + NPV;                  // MFMA pairs of a half-step
@@ -204,6 +206,7 @@ struct AttnWave {
     int n, ns, ntiles, nhalf;
     bool ragged;
     uint32_t row_bytes;   // byte stride between sequence positions of K / V in global memory
+    uint32_t row_mul;     // what a tile's row word is multiplied by: row_bytes, or (block-sparse) the bytes of a key block
     uint32_t wave_lds;    // LDS address of this wave's first 1 KB chunk in tile slot 0 of K
     uint32_t dma_off;     // global byte offset of the load whose first half has been issued
     const byte* K;
@@ -215,7 +218,9 @@ struct AttnWave {
     float c2;
     float mc[2];          // reference maximum in log2 units (raw maximum * c2), equal in both half-waves
     float l_run[2];       // per-lane partial row sum (this lane's keys only)
-    uint32_t koff[CH], voff[CH];   // global byte offset of this lane's piece inside a row, per load instruction
+    // global byte offset that load instruction i adds to row word * row_mul: this lane's piece inside a row, plus
+    // (block-sparse) the row's offset inside its key block
+    uint32_t koff[CH], voff[CH];
     uint32_t kaddr[KK];   // LDS byte offset (inside a tile slot, first half) of this lane's K fragment kk
     uint32_t vaddr[ODB];  // same for the first 4-row group of the V fragment of d-block db
     int lrow;
@@ -230,7 +235,14 @@ struct AttnWave {
             const int row = (wave * CH + i) * ROWS_PER_CHUNK + lrow;
             koff[i] = (uint32_t)(lslot ^ swizzle_k<PIECES>(row)) * 16u;
             voff[i] = (uint32_t)(lslot ^ swizzle_v<PIECES>(row)) * 16u;
+            if (BLOCKS) {
+                // load i of this lane brings the key at position wave*16 + lrow*CH + i of the block
+                const uint32_t in_block = (uint32_t)(wave * 16 + lrow * CH + i) * row_bytes;
+                koff[i] += in_block;
+                voff[i] += in_block;
+            }
         }
+        row_mul = BLOCKS ? row_bytes * (uint32_t)BN : row_bytes;
         // K fragment kk: tile row lq (+32 for the second half), piece 2*kk + lh
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk)
@@ -251,7 +263,7 @@ struct AttnWave {
     // byte offset of a 16-byte piece of K/V row `row` from the head's base: both factors are
     // below 2^24 (checked on the host), so the full-rate 24-bit multiply-add does it
     __device__ __forceinline__ uint32_t row_offset(int row, uint32_t piece_off) const {
-        return __umul24((uint32_t)row, row_bytes) + piece_off;
+        return __umul24((uint32_t)row, row_mul) + piece_off;
     }
     // Which sequence position goes where: load instruction i of a wave fills LDS tile row
     // (wave*CH + i)*ROWS_PER_CHUNK + lrow, and it takes position wave*16 + lrow*CH + i of the
@@ -261,7 +273,12 @@ struct AttnWave {
     // back so that all CH entries lie inside the pattern.  In the last tile a lane whose positions
     // straddle or pass the end thereby fetches entries that belong to earlier positions a second
     // time; entry_is_new() tells them apart and mask_tail() gives those positions weight zero.
-    typedef int rows_t __attribute__((ext_vector_type(CH)));
+    // (Block-sparse: the one word of a tile is the number of its key block, the same for every lane and load.)
+    typedef int row_vector_t __attribute__((ext_vector_type(CH)));
+    typedef std::conditional_t<BLOCKS, int, row_vector_t> rows_t;
+    static __device__ __forceinline__ int row_word(const rows_t& rows, int i) {
+        if constexpr (BLOCKS) return rows; else return rows[i];
+    }
     __device__ __forceinline__ int first_entry(int first_pos) const {
         const int last = ns > CH ? ns - CH : 0;
         return first_pos < last ? first_pos : last;
@@ -277,6 +294,10 @@ struct AttnWave {
     __device__ __forceinline__ void load_rows(const byte* idx, int t, rows_t& dst) const {
         static_assert(CH * ROWS_PER_CHUNK == 16, "a wave fills 16 rows of a tile");
         t = t < ntiles ? t : ntiles - 1;          // past the end: repeat the last tile (never read back)
+        if constexpr (BLOCKS) {
+            dst = *(const int*)(idx + (uint32_t)t * 4u);
+            return;
+        } else {
         const int e0 = first_entry(t * BN + wave * 16 + lrow * CH);
         if (GATHER) {
             if (__builtin_expect(ns >= CH, 1)) {
@@ -290,6 +311,7 @@ struct AttnWave {
 #pragma unroll
             for (int i = 0; i < CH; ++i) dst[i] = e0 + i < ns ? e0 + i : ns - 1;
         }
+        }
     }
     // The same for the scheduled half-steps (which only run when the pattern has more than one
     // tile, so ns > CH), with a load the compiler does not see: it would otherwise wait for ALL
@@ -302,11 +324,16 @@ struct AttnWave {
     __device__ __forceinline__ void load_rows_async(int t, rows_t& dst) const {
         if (!GATHER) { load_rows(t, dst); return; }
         t = t < ntiles ? t : ntiles - 1;
-        const uint32_t want = (uint32_t)(t * (BN * 4)) + lane_rows_off, last = (uint32_t)(ns - CH) * 4u;
-        const uint32_t off = want < last ? want : last;
-        static_assert(CH == 2 || CH == 4, "row numbers per lane and tile");
-        if constexpr (CH == 4) asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(off), "s"(idx));
-        else asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(dst) : "v"(off), "s"(idx));
+        if constexpr (BLOCKS) {
+            const uint32_t off = (uint32_t)t * 4u;
+            asm volatile("global_load_dword %0, %1, %2" : "=v"(dst) : "v"(off), "s"(idx));
+        } else {
+            const uint32_t want = (uint32_t)(t * (BN * 4)) + lane_rows_off, last = (uint32_t)(ns - CH) * 4u;
+            const uint32_t off = want < last ? want : last;
+            static_assert(CH == 2 || CH == 4, "row numbers per lane and tile");
+            if constexpr (CH == 4) asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(off), "s"(idx));
+            else asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(dst) : "v"(off), "s"(idx));
+        }
     }
     // position inside its tile of the key in LDS tile row `row`
     static __device__ __forceinline__ int tile_pos(int row) {
@@ -322,7 +349,7 @@ struct AttnWave {
 #pragma unroll
         for (int i = 0; i < CH; ++i)
             __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(Kg + row_offset(rows[i], koff[i])),
+                (const __attribute__((address_space(1))) void*)(Kg + row_offset(row_word(rows, i), koff[i])),
                 (PULSECOL_LDS void*)(kslot + (wave * CH + i) * 1024), 16, 0, 0);
     }
     __device__ __forceinline__ void issue_v_tile(byte* __restrict__ vslot, const byte* __restrict__ Vg,
@@ -331,7 +358,7 @@ struct AttnWave {
 #pragma unroll
             for (int i = 0; i < CH; ++i)
                 __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void*)(Vg + row_offset(rows[i], voff[i])),
+                    (const __attribute__((address_space(1))) void*)(Vg + row_offset(row_word(rows, i), voff[i])),
                     (PULSECOL_LDS void*)(vslot + (wave * CH + i) * 1024), 16, 0, 0);
         }
     }
@@ -348,9 +375,9 @@ struct AttnWave {
         uint32_t off;
         if constexpr (J == 0)
             asm volatile("s_add_i32 m0, %1, %2\n\tv_mad_u32_u24 %0, %3, %4, %5"
-                         : "=v"(off) : "s"(wave_lds), "n"(LDS_OFF), "v"(row), "s"(row_bytes), "v"(piece_off));
+                         : "=v"(off) : "s"(wave_lds), "n"(LDS_OFF), "v"(row), "s"(row_mul), "v"(piece_off));
         else
-            asm volatile("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(off) : "v"(row), "s"(row_bytes), "v"(piece_off));
+            asm volatile("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(off) : "v"(row), "s"(row_mul), "v"(piece_off));
         return off;
     }
     // m0 is written by issue_addr and, in compiler-generated code, only right in front of the
@@ -664,11 +691,11 @@ struct AttnWave {
                 if constexpr (ROLE == 0) {
                     if constexpr (P == 0) load_rows_async(next_tile, rows_n);
                     constexpr int j = k_addr_at(P);
-                    if constexpr (j >= 0) dma_off = issue_addr<KW, j>(krows[j], koff[j]);
+                    if constexpr (j >= 0) dma_off = issue_addr<KW, j>(row_word(krows, j), koff[j]);
                 }
                 if constexpr (ROLE == 1 && HAS_V) {
                     constexpr int j = v_addr_at(P);
-                    if constexpr (j >= 0) dma_off = issue_addr<VW, j>(vrows[j], voff[j]);
+                    if constexpr (j >= 0) dma_off = issue_addr<VW, j>(row_word(vrows, j), voff[j]);
                 }
             }
             fence();
@@ -823,7 +850,7 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     asm volatile("" : : "s"(p.q), "s"(p.k), "s"(p.v), "s"(p.o), "s"(p.idx), "s"(p.lse), "s"(p.lse_base2),
                          "s"(p.td.sb), "s"(p.td.sh), "s"(p.td.sn), "s"(p.td_kv.sb), "s"(p.td_kv.sh), "s"(p.td_kv.sn),
                          "s"(p.kv_heads), "s"(p.batch), "s"(p.heads), "s"(p.n), "s"(p.ns), "s"(p.groups),
-                         "s"(p.group_size), "s"(p.scale), "s"(p.work), "s"(p.work_stamp), "s"(p.varlen));
+                         "s"(p.group_size), "s"(p.scale), "s"(p.work), "s"(p.work_stamp), "s"(p.varlen), "s"(p.idx_stride));
     const int nqb = (p.n + BM - 1) / BM;
     const WorkQueues queues{p.work, p.work_stamp, p.batch * p.heads, nqb, p.varlen, p.heads};
     __shared__ int32_t lds_item[2];          // the workgroup's next item: queue, index in the queue
@@ -870,7 +897,7 @@ __global__ void __launch_bounds__(NTHREADS) attn_bf16_kernel(AttnParams p) {
     // the column set of a query block's group (Sec. 3.3: one set per query group)
     auto pattern_of = [&](int bh, int qblk) -> const byte* {
         const int group = p.groups > 1 ? (qblk * BM) / p.group_size : 0;
-        return W::GATHER ? (const byte*)(p.idx + ((int64_t)bh * p.groups + group) * p.ns) : nullptr;
+        return W::GATHER ? (const byte*)(p.idx + ((int64_t)bh * p.groups + group) * p.idx_stride) : nullptr;
     };
 
     // What a query block needs first, requested ahead of its turn (for the first one: now; for
@@ -1223,11 +1250,13 @@ int compute_units() {
 hipError_t launch_attn_bf16(const AttnParams& p, int head_dim, AttnMode mode, hipStream_t s) {
     if (head_dim == 128) {
         if (mode == kSparse) return launch<128, kSparse>(p, s);
+        if (mode == kBlock) return launch<128, kBlock>(p, s);
         if (mode == kDense) return launch<128, kDense>(p, s);
         return launch<128, kLseOnly>(p, s);
     }
     if (head_dim == 64) {
         if (mode == kSparse) return launch<64, kSparse>(p, s);
+        if (mode == kBlock) return launch<64, kBlock>(p, s);
         if (mode == kDense) return launch<64, kDense>(p, s);
         return launch<64, kLseOnly>(p, s);
     }

@@ -156,7 +156,7 @@ pulsecol::AttnParams attn_params(pulsecol_ctx* c, const void* Q, const void* K, 
     pulsecol::AttnParams p{};
     p.q = Q; p.k = K; p.v = V; p.o = O; p.idx = idx; p.lse = lse; p.lse_base2 = lse_base2;
     p.td = c->td; p.td_kv = c->td_kv; p.kv_heads = c->kv_heads;
-    p.batch = c->shape.batch; p.heads = c->shape.heads; p.n = c->shape.seq; p.ns = ns;
+    p.batch = c->shape.batch; p.heads = c->shape.heads; p.n = c->shape.seq; p.ns = ns; p.idx_stride = ns;
     p.groups = c->groups; p.group_size = c->shape.group_size;
     p.scale = c->scale;
     p.varlen = c->varlen_on ? c->varlen : nullptr;
@@ -245,7 +245,7 @@ pulsecol_status select_from_scores(pulsecol_ctx* ctx, double keep_ratio, int32_t
 pulsecol_status run_topk(pulsecol_ctx* ctx, const float* scores, int32_t k, int32_t* out, hipStream_t s) {
     pulsecol::TopkParams tp{};
     tp.scores = scores; tp.idx = out;
-    tp.rows = ctx->shape.batch * ctx->shape.heads * ctx->groups; tp.n = ctx->shape.seq; tp.k = k;
+    tp.rows = ctx->shape.batch * ctx->shape.heads * ctx->groups; tp.n = ctx->shape.seq; tp.k = k; tp.stride = ctx->shape.seq;
     tp.varlen = ctx->varlen_on ? ctx->varlen : nullptr;
     tp.batch = ctx->shape.batch; tp.rows_per_batch = ctx->shape.heads * ctx->groups;
     tp.groups = ctx->groups; tp.group_size = ctx->shape.group_size;
@@ -285,6 +285,21 @@ NoallocDevice* noalloc_device(int dev, hipError_t* err) {
         d->ptr = ptr;
     }
     return d;
+}
+
+// what the block-sparse calls need of a context: the hand-scheduled bf16 kernel (whole 256-row query blocks
+// per block mask), whole key blocks, fixed-length batches, and block offsets that the 24-bit multiply holds
+pulsecol_status check_block_mode(pulsecol_ctx* ctx, const char* who) {
+    const pulsecol_shape& sh = ctx->shape;
+    if (sh.dtype != PULSECOL_BF16) return fail(ctx, PULSECOL_ERR_UNSUPPORTED, std::string(who) + ": block-sparse attention is bf16 only");
+    if (ctx->groups > 1 && sh.group_size % pulsecol::kBlockM_bf16 != 0)
+        return fail(ctx, PULSECOL_ERR_UNSUPPORTED, std::string(who) + ": query blocks of the block mask are multiples of 256 rows (group_size)");
+    if (sh.seq % pulsecol::kBlockN_bf16 != 0)
+        return fail(ctx, PULSECOL_ERR_UNSUPPORTED, std::string(who) + ": seq must be a multiple of the key block (64)");
+    if (ctx->varlen_on) return fail(ctx, PULSECOL_ERR_UNSUPPORTED, std::string(who) + ": not available with per-element sequence lengths");
+    if (ctx->td_kv.sn * 2 * pulsecol::kBlockN_bf16 >= (1 << 24))
+        return fail(ctx, PULSECOL_ERR_UNSUPPORTED, std::string(who) + ": 64 K/V rows span 2^24 bytes or more");
+    return PULSECOL_OK;
 }
 
 }  // namespace
@@ -534,6 +549,66 @@ pulsecol_status pulsecol_attn(pulsecol_ctx* ctx, const void* Q, const void* K, c
     const pulsecol::AttnParams p = attn_params(ctx, Q, K, V, O, idx, k, nullptr, 0);
     const hipError_t e = launch_attn(ctx, p, pulsecol::kSparse, (hipStream_t)stream);
     if (e != hipSuccess) return fail_hip(ctx, e, "column-sparse attention kernel");
+    return PULSECOL_OK;
+}
+
+int32_t pulsecol_num_keep_blocks(int32_t seq, double keep_ratio) {
+    if (seq < pulsecol::kBlockN_bf16 || seq % pulsecol::kBlockN_bf16 != 0) return -1;
+    return pulsecol_num_keep(seq / pulsecol::kBlockN_bf16, keep_ratio);
+}
+
+pulsecol_status pulsecol_select_blocks(pulsecol_ctx* ctx, const void* Q, const void* K, double keep_ratio,
+                                       int32_t* block_idx_out, void* stream) {
+    if (!ctx) return fail(nullptr, PULSECOL_ERR_INVALID_ARG, "pulsecol_select_blocks: ctx is NULL");
+    if (!block_idx_out) return fail(ctx, PULSECOL_ERR_INVALID_ARG, "pulsecol_select_blocks: block_idx_out is NULL");
+    pulsecol_status st = check_block_mode(ctx, "pulsecol_select_blocks");
+    if (st != PULSECOL_OK) return st;
+    const int32_t kb = pulsecol_num_keep_blocks(ctx->shape.seq, keep_ratio);
+    if (kb < 0) return fail(ctx, PULSECOL_ERR_INVALID_ARG, "pulsecol_select_blocks: keep_ratio must be in (0, 1]");
+    st = check_ptrs(ctx, {Q, K}, "pulsecol_select_blocks");
+    if (st != PULSECOL_OK) return st;
+    DeviceGuard guard(ctx->device);
+    if (guard.err != hipSuccess) return fail_hip(ctx, guard.err, "pulsecol_select_blocks: hipSetDevice");
+    hipStream_t s = (hipStream_t)stream;
+    st = run_scores(ctx, Q, K, ctx->scores, s);
+    if (st != PULSECOL_OK) return st;
+    // block masses over the front of every score row, then the same exact top-k on rows of seq / 64 elements
+    const int32_t rows = ctx->shape.batch * ctx->shape.heads * ctx->groups;
+    hipError_t e = pulsecol::launch_block_sums(ctx->scores, ctx->scores, rows, ctx->shape.seq, ctx->shape.seq, pulsecol::kBlockN_bf16, s);
+    if (e != hipSuccess) return fail_hip(ctx, e, "block-mass kernel");
+    pulsecol::TopkParams tp{};
+    tp.scores = ctx->scores; tp.idx = block_idx_out; tp.rows = rows;
+    tp.n = ctx->shape.seq / pulsecol::kBlockN_bf16; tp.k = kb; tp.stride = ctx->shape.seq;
+    e = pulsecol::launch_topk(tp, s);
+    if (e != hipSuccess) return fail_hip(ctx, e, "top-k kernel (key blocks)");
+    return PULSECOL_OK;
+}
+
+pulsecol_status pulsecol_attn_block(pulsecol_ctx* ctx, const void* Q, const void* K, const void* V, const int32_t* block_idx,
+                                    int32_t kb, void* O, void* stream) {
+    if (!ctx) return fail(nullptr, PULSECOL_ERR_INVALID_ARG, "pulsecol_attn_block: ctx is NULL");
+    pulsecol_status st = check_block_mode(ctx, "pulsecol_attn_block");
+    if (st != PULSECOL_OK) return st;
+    st = check_ptrs(ctx, {Q, K, V, O}, "pulsecol_attn_block");
+    if (st != PULSECOL_OK) return st;
+    if (!block_idx) return fail(ctx, PULSECOL_ERR_INVALID_ARG, "pulsecol_attn_block: block_idx is NULL");
+    const int32_t nblocks = ctx->shape.seq / pulsecol::kBlockN_bf16;
+    if (kb < 1 || kb > nblocks) return fail(ctx, PULSECOL_ERR_INVALID_ARG, "pulsecol_attn_block: need 1 <= kb <= seq / 64");
+    DeviceGuard guard(ctx->device);
+    if (guard.err != hipSuccess) return fail_hip(ctx, guard.err, "pulsecol_attn_block: hipSetDevice");
+    if (ctx->validate) {
+        const int64_t count = (int64_t)ctx->shape.batch * ctx->shape.heads * ctx->groups * kb;
+        hipError_t ev = pulsecol::launch_index_range_check(block_idx, count, nblocks, ctx->bad_count, nullptr, 0, 0, 0, (hipStream_t)stream);
+        int32_t bad = 0;
+        if (ev == hipSuccess) ev = hipMemcpyAsync(&bad, ctx->bad_count, sizeof(bad), hipMemcpyDeviceToHost, (hipStream_t)stream);
+        if (ev == hipSuccess) ev = hipStreamSynchronize((hipStream_t)stream);
+        if (ev != hipSuccess) return fail_hip(ctx, ev, "pulsecol_attn_block: index validation");
+        if (bad != 0) return fail(ctx, PULSECOL_ERR_BAD_INDEX, "pulsecol_attn_block: block_idx holds entries outside [0, seq / 64)");
+    }
+    pulsecol::AttnParams p = attn_params(ctx, Q, K, V, O, block_idx, kb * pulsecol::kBlockN_bf16, nullptr, 0);
+    p.idx_stride = kb;
+    const hipError_t e = pulsecol::launch_attn_bf16(p, ctx->shape.head_dim, pulsecol::kBlock, (hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "block-sparse attention kernel");
     return PULSECOL_OK;
 }
 

@@ -15,7 +15,8 @@ struct AttnParams {
     const void* k;
     const void* v;
     void* o;
-    const int32_t* idx;      // [B*H*groups, ns] (one column set per query group) or nullptr for dense
+    const int32_t* idx;      // [B*H*groups, idx_stride] (one column set per query group) or nullptr for dense
+    int32_t idx_stride;      // entries between the sets of consecutive groups (ns for column sets)
     float* lse;              // optional [B*H, n] row log-sum-exp of the scaled logits
     int32_t lse_base2;       // 0: natural log; 1: log2 units (what the column-mass pass consumes)
     TensorDesc td;           // Q and O: [B, heads, n, D]
@@ -54,9 +55,10 @@ struct ScoreParams {
 };
 
 struct TopkParams {
-    const float* scores;     // [rows, n]
+    const float* scores;     // [rows, n], consecutive rows `stride` elements apart (a multiple of 4 where n is)
     int32_t* idx;            // [rows, k]
     int32_t rows, n, k;
+    int64_t stride;
     // variable-length batches (else nullptr): rows = batch * rows_per_batch; row r belongs to batch
     // element b = r / rows_per_batch and is group u = r % groups of its head; it selects varlen[batch + b]
     // of its first varlen[b] scores and pads the rest of its k entries with -1; rows of groups that lie
@@ -65,7 +67,9 @@ struct TopkParams {
     int32_t batch, rows_per_batch, groups, group_size;
 };
 
-enum AttnMode { kSparse = 0, kDense = 1, kLseOnly = 2 };
+// kBlock (bf16 kernel with 256-row query blocks only): idx holds key-BLOCK numbers, one per tile of
+// kBlockN_bf16 consecutive keys; ns = kept blocks * kBlockN_bf16
+enum AttnMode { kSparse = 0, kDense = 1, kLseOnly = 2, kBlock = 3 };
 
 // Tile geometry of the attention kernels.
 constexpr int kBlockM_bf16 = 256;   // query rows per workgroup (4 waves x 64)
@@ -83,6 +87,11 @@ hipError_t launch_attn_f32(const AttnParams& p, int head_dim, AttnMode mode, hip
 hipError_t launch_colmass_bf16(const ScoreParams& p, int head_dim, hipStream_t s);
 hipError_t launch_colmass_f32(const ScoreParams& p, int head_dim, hipStream_t s);
 hipError_t launch_topk(const TopkParams& p, hipStream_t s);
+// Key-block masses for block-sparse selection (Sec. 3.1, block mask): out[r * stride + j] = sum of
+// scores[r * stride + j*block .. +block-1], j < n / block, for every score row r (in place is fine: a row's
+// sums are written over its own first n / block elements after the whole row has been read)
+hipError_t launch_block_sums(const float* scores, float* out, int32_t rows, int32_t n, int64_t stride, int32_t block, hipStream_t s);
+
 // *bad_count (device) = number of wavefront-lanes that saw an entry of idx[0..count) outside [0, n); 0 if none.
 // Variable-length batches (varlen != nullptr, per_batch = entries of idx per batch element, k = entries per
 // row): of each row only the leading varlen[batch + b] entries are checked, against [0, varlen[b]).

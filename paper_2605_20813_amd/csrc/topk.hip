@@ -53,7 +53,7 @@ __global__ void __launch_bounds__(TK_THREADS) topk_kernel(TopkParams p) {
     __shared__ uint32_t wave_cnt[2][TK_WAVES];
 
     const int row = blockIdx.x;
-    const float* __restrict__ s = p.scores + (int64_t)row * p.n;
+    const float* __restrict__ s = p.scores + (int64_t)row * p.stride;
     int32_t* __restrict__ out = p.idx + (int64_t)row * p.k;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -203,7 +203,7 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
 #pragma unroll
     for (int i = 0; i < V4; ++i) {
         u32x4 v = {0u, 0u, 0u, 0u};                          // outside the row: never looked at, every use is guarded by nv
-        if (i < nv) v = *(const u32x4*)(bits + (int64_t)blockIdx.x * p.n + first + i * 256);
+        if (i < nv) v = *(const u32x4*)(bits + (int64_t)blockIdx.x * p.stride + first + i * 256);
 #pragma unroll
         for (int c = 0; c < 4; ++c) key[i][c] = v[c];
     }
@@ -211,7 +211,7 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
   for (int row = blockIdx.x; row < p.rows; row += gridDim.x) {
     int32_t* __restrict__ out = p.idx + (int64_t)row * p.k;
     const bool more = row + (int)gridDim.x < p.rows;
-    const uint32_t* __restrict__ next_bits = bits + (int64_t)(more ? row + (int)gridDim.x : row) * p.n + first;
+    const uint32_t* __restrict__ next_bits = bits + (int64_t)(more ? row + (int)gridDim.x : row) * p.stride + first;
     // this row's geometry was settled when its load was issued; the next row's decides what is fetched for it
     int n_next = 0, k_next = 0;
     if (more) row_geometry(p, row + (int)gridDim.x, n_next, k_next);
@@ -471,12 +471,39 @@ hipError_t launch_rows(const TopkParams& p, hipStream_t s) {
     return hipGetLastError();
 }
 
+// One workgroup per score row: thread i adds up key block i (a fixed order: bit-identical from run to
+// run); a row's sums go over its own first elements once every thread has read its block.
+__global__ void __launch_bounds__(256) block_sums_kernel(const float* __restrict__ scores, float* __restrict__ out,
+                                                         int32_t n, int64_t stride, int32_t block) {
+    const float* __restrict__ row = scores + (int64_t)blockIdx.x * stride;
+    float* __restrict__ dst = out + (int64_t)blockIdx.x * stride;
+    const int nblocks = n / block;
+    for (int base = 0; base < nblocks; base += 256) {
+        const int j = base + threadIdx.x;
+        float acc = 0.f;
+        if (j < nblocks) {
+            const float* src = row + (int64_t)j * block;
+            for (int c = 0; c < block; ++c) acc += src[c];
+        }
+        __syncthreads();            // every block of this round has been read: the sums may overwrite the row's front
+        if (j < nblocks) dst[j] = acc;
+        __syncthreads();
+    }
+}
+
 }  // namespace
+
+hipError_t launch_block_sums(const float* scores, float* out, int32_t rows, int32_t n, int64_t stride, int32_t block, hipStream_t s) {
+    if (rows < 1 || n < block || block < 1 || n % block != 0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(block_sums_kernel, dim3(rows), dim3(256), 0, s, scores, out, n, stride, block);
+    return hipGetLastError();
+}
 
 hipError_t launch_topk(const TopkParams& p, hipStream_t s) {
     if (p.rows < 1 || p.n < 1 || p.k < 1 || p.k > p.n) return hipErrorInvalidValue;
     // rows that one workgroup can hold in registers, and that 16-byte loads can read
-    if (p.n <= 65536 && p.n % 4 == 0 && (reinterpret_cast<uintptr_t>(p.scores) & 15u) == 0) {
+    if (p.stride < p.n) return hipErrorInvalidValue;
+    if (p.n <= 65536 && p.n % 4 == 0 && p.stride % 4 == 0 && (reinterpret_cast<uintptr_t>(p.scores) & 15u) == 0) {
         const int per_wave = (p.n + TK_WAVES - 1) / TK_WAVES;      // elements a wave has to hold
         if (per_wave <= 256) return launch_rows<1>(p, s);
         if (per_wave <= 512) return launch_rows<2>(p, s);

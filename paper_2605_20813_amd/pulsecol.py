@@ -22,6 +22,7 @@ BF16, F32 = 0, 1
 EXPORTS = (
     "pulsecol_validate_shape", "pulsecol_create", "pulsecol_destroy", "pulsecol_set_validation", "pulsecol_set_attn_block", "pulsecol_set_seq_lens", "pulsecol_num_keep",
     "pulsecol_select", "pulsecol_scores", "pulsecol_topk", "pulsecol_attn", "pulsecol_attn_dense",
+    "pulsecol_attn_block", "pulsecol_num_keep_blocks", "pulsecol_select_blocks",
     "pulsecol_refresh_dense", "pulsecol_select_noalloc",
     "pulsecol_refresh_schedule", "pulsecol_refresh_schedule_power", "pulsecol_refresh_schedule_random",
     "pulsecol_attn_tile_shape", "pulsecol_status_str", "pulsecol_last_error",
@@ -69,6 +70,10 @@ def lib() -> ctypes.CDLL:
         L.pulsecol_topk.argtypes = [c_void_p, c_void_p, c_int32, c_void_p, c_void_p]
         L.pulsecol_attn.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_void_p]
         L.pulsecol_attn_dense.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+        L.pulsecol_attn_block.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_void_p]
+        L.pulsecol_num_keep_blocks.argtypes = [c_int32, c_double]
+        L.pulsecol_num_keep_blocks.restype = c_int32
+        L.pulsecol_select_blocks.argtypes = [c_void_p, c_void_p, c_void_p, c_double, c_void_p, c_void_p]
         L.pulsecol_refresh_dense.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_double, c_void_p, c_void_p, c_void_p]
         L.pulsecol_select_noalloc.argtypes = [POINTER(Shape), c_void_p, c_void_p, c_double, c_void_p, c_void_p]
         L.pulsecol_refresh_schedule.argtypes = [c_int32, c_double, c_int32, POINTER(c_int32)]
@@ -106,6 +111,10 @@ def validate_shape(shape: Shape) -> int:
 
 def num_keep(seq: int, keep_ratio: float) -> int:
     return lib().pulsecol_num_keep(seq, keep_ratio)
+
+
+def num_keep_blocks(seq: int, keep_ratio: float) -> int:
+    return lib().pulsecol_num_keep_blocks(seq, keep_ratio)
 
 
 def refresh_schedule(T: int, eta: float, R: int):
@@ -303,6 +312,34 @@ class Context:
             O = self._new_output()
         self._check_tensor(O, "O")
         self._check(lib().pulsecol_attn(self._h, _ptr(Q), _ptr(K), _ptr(V), _ptr(idx), idx.shape[3], _ptr(O), _stream()))
+        return O
+
+    def select_blocks(self, Q, K, keep_ratio: float, block_idx_out=None):
+        """Key blocks (of 64 keys) per query block by block mass; returns int32 [B, H, U, kb]."""
+        s = self.shape
+        kb = num_keep_blocks(s.seq, keep_ratio)
+        if kb < 0:
+            raise PulseColError(ERR_INVALID_ARG, "need seq % 64 == 0 and keep_ratio in (0, 1]")
+        self._check_tensor(Q, "Q")
+        self._check_tensor(K, "K")
+        if block_idx_out is None:
+            block_idx_out = torch.empty(s.batch, s.heads, self.groups, kb, dtype=torch.int32, device=self.device)
+        self._check(lib().pulsecol_select_blocks(self._h, _ptr(Q), _ptr(K), keep_ratio, _ptr(block_idx_out), _stream()))
+        return block_idx_out
+
+    def attn_block(self, Q, K, V, block_idx, O=None):
+        """Block-sparse attention: block_idx int32 [B, H, U, kb] names key blocks of 64 keys."""
+        for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):
+            self._check_tensor(t, nm)
+        s = self.shape
+        if block_idx.dtype != torch.int32 or not block_idx.is_contiguous() or block_idx.device != self.device \
+                or block_idx.dim() != 4 or tuple(block_idx.shape[:3]) != (s.batch, s.heads, self.groups):
+            raise ValueError("block_idx: expected contiguous int32 [B, H, U, kb] on the context's device")
+        if O is None:
+            O = self._new_output()
+        self._check_tensor(O, "O")
+        self._check(lib().pulsecol_attn_block(self._h, _ptr(Q), _ptr(K), _ptr(V), _ptr(block_idx), block_idx.shape[3],
+                                              _ptr(O), _stream()))
         return O
 
     def refresh_dense(self, Q, K, V, keep_ratio: float, O=None, idx_out=None):

@@ -267,9 +267,49 @@ def pin_planted_columns_selected(o):
         assert idx.shape == (1, 64) and heavy <= set(idx[0].tolist())
 
 
+def pin_block_mask(o):
+    # the block-mask equation written out as an n x n matrix, against an independent library's softmax
+    n, d, kb, G = 24, 8, 4, 8
+    Q, K, V = _rand(n, d, 21)
+    r = np.random.default_rng(22)
+    blocks = np.stack([np.sort(r.permutation(n // kb)[:2]) for _ in range(n // G)])         # G[u, c] = 1 for two blocks per query block
+    S = np.zeros((n, n), dtype=bool)
+    for i in range(n):
+        for j in range(n):
+            S[i, j] = (j // kb) in blocks[i // G]
+    Z = torch.from_numpy(o.attention_logits(Q, K))
+    M = torch.where(torch.from_numpy(S), 0.0, float("-inf")).double()
+    want = (torch.softmax(Z + M, dim=1) @ torch.from_numpy(V)).numpy()
+    np.testing.assert_allclose(o.block_sparse_attention(Q, K, V, blocks, kb, group_size=G), want, rtol=1e-12, atol=1e-14)
+    assert o.block_columns([[2, 0]], 3).tolist() == [[6, 7, 8, 0, 1, 2]]
+    # key blocks of one key: the column-sparse result; all key blocks kept: dense attention
+    cols = np.sort(r.permutation(n)[:5])[None]
+    np.testing.assert_allclose(o.block_sparse_attention(Q, K, V, cols, 1), o.sparse_attention_masked(Q, K, V, cols), rtol=1e-13)
+    np.testing.assert_allclose(o.block_sparse_attention(Q, K, V, [list(range(n // kb))], kb), o.dense_attention(Q, K, V), rtol=1e-13)
+    # block masses: sums of the column scores over the block's keys (each row still sums to one); blocks of
+    # one key are the column scores themselves
+    s = o.column_scores(Q, K, group_size=G)
+    m = o.block_scores(Q, K, kb, group_size=G)
+    assert m.shape == (n // G, n // kb)
+    np.testing.assert_allclose(m.sum(axis=1), 1.0, rtol=1e-13)
+    np.testing.assert_allclose(m[1, 2], s[1, 8:12].sum(), rtol=1e-13)
+    np.testing.assert_allclose(o.block_scores(Q, K, 1, group_size=G), s, rtol=1e-13)
+    # a key block made heavy (its keys aligned with every query) must be selected; budget rule on blocks
+    K2 = K.copy()
+    K2[12:16] = 3.0 * Q.mean(axis=0) + 2.0
+    Q2 = np.abs(Q) + 0.5
+    sel = o.select_blocks(Q2, K2, 0.34, kb)              # floor(0.34 * 6) = 2 blocks
+    assert sel.shape == (1, 2) and 3 in sel[0]
+    assert o.select_blocks(Q, K, 0.1, kb).shape == (1, 1)
+    # closed form: the 3 x 3 example with key blocks of one key, query blocks of two rows
+    g, Qc, Kc, Vc = _closed_form()
+    assert o.select_blocks(Qc, Kc, 0.34, 1, group_size=2).tolist() == g["top1_group_size_2"]
+    np.testing.assert_allclose(o.block_sparse_attention(Qc, Kc, Vc, [[0, 1]], 1), _table(g["sparse_idx_0_1"]), rtol=1e-13, atol=1e-15)
+
+
 PINS = [pin_closed_form, pin_dense_matches_library, pin_scores_invariants, pin_topk_bruteforce,
         pin_topk_order_and_ties, pin_sparse_attention_properties, pin_scale_override, pin_num_keep,
-        pin_schedule, pin_schedule_variants, pin_planted_columns_selected]
+        pin_schedule, pin_schedule_variants, pin_planted_columns_selected, pin_block_mask]
 
 
 @pytest.mark.parametrize("pin", PINS, ids=lambda p: p.__name__)
@@ -410,6 +450,21 @@ def _select_budget_is_sparsity(Q, K, keep_ratio, group_size=0, scale=None):
     return topk_columns(column_scores(Q, K, group_size, scale), k)
 
 
+def _block_columns_off_by_one(block_idx, key_block):
+    blocks = np.atleast_2d(np.asarray(block_idx, dtype=np.int64))
+    return (blocks[:, :, None] * key_block + 1 + np.arange(key_block)[None, None, :]).reshape(blocks.shape[0], -1) % 10**9
+
+
+def _block_scores_mean_not_sum(Q, K, key_block, group_size=0, scale=None):
+    s = column_scores(Q, K, group_size, scale)
+    return s.reshape(s.shape[0], s.shape[1] // key_block, key_block).mean(axis=2)
+
+
+def _block_scores_strided_blocks(Q, K, key_block, group_size=0, scale=None):
+    s = column_scores(Q, K, group_size, scale)
+    return s.reshape(s.shape[0], key_block, s.shape[1] // key_block).sum(axis=1)
+
+
 def _num_keep_ceil(n, keep_ratio):
     if n < 1 or not (0.0 < keep_ratio <= 1.0):
         raise ValueError
@@ -429,6 +484,9 @@ MUTANTS = {
     "schedule_zero_based": dict(refresh_schedule=_schedule_zero_based),
     "schedule_full_window": dict(refresh_schedule=_schedule_window_not_minus_one),
     "num_keep_ceil": dict(num_keep=_num_keep_ceil),
+    "block_columns_off_by_one": dict(block_columns=_block_columns_off_by_one),
+    "block_scores_mean_not_sum": dict(block_scores=_block_scores_mean_not_sum),
+    "block_scores_strided_blocks": dict(block_scores=_block_scores_strided_blocks),
     "select_ignores_groups": dict(select_columns=_select_ignores_groups),
     "select_budget_is_sparsity": dict(select_columns=_select_budget_is_sparsity),
     "power_schedule_linear": dict(refresh_schedule_power=_power_linear),
