@@ -168,7 +168,9 @@ __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
     return v;
 }
 
-template <int V4>
+// VARLEN: variable-length batches (rows of their own length and kept count, rows of padding); the
+// fixed-length instantiation carries none of that bookkeeping, which costs it registers it does not have.
+template <int V4, bool VARLEN>
 __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
     constexpr int SEG = 256 * V4;
     static_assert(TKR_BPT * TK_THREADS == TKR_BINS && TKR_BPT % 4 == 0, "whole 16-byte groups of bins per thread");
@@ -189,8 +191,8 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
     auto groups_inside = [&](int n_row) {
         return first >= n_row ? 0 : ((n_row - first + 255) / 256 < V4 ? (n_row - first + 255) / 256 : V4);
     };
-    int n, k_row;
-    row_geometry(p, blockIdx.x, n, k_row);
+    int n = p.n, k_row = p.k;
+    if constexpr (VARLEN) row_geometry(p, blockIdx.x, n, k_row);
     int nv = groups_inside(n);
 
     // The workgroup walks over rows blockIdx.x, + gridDim.x, ...; the scores of the next row are
@@ -213,11 +215,11 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
     const bool more = row + (int)gridDim.x < p.rows;
     const uint32_t* __restrict__ next_bits = bits + (int64_t)(more ? row + (int)gridDim.x : row) * p.stride + first;
     // this row's geometry was settled when its load was issued; the next row's decides what is fetched for it
-    int n_next = 0, k_next = 0;
-    if (more) row_geometry(p, row + (int)gridDim.x, n_next, k_next);
-    const int nv_next = more ? groups_inside(n_next) : 0;
-    pad_row(out, k_row, p.k, tid);
-    if (k_row == 0) {
+    int n_next = p.n, k_next = p.k;
+    if constexpr (VARLEN) { if (more) row_geometry(p, row + (int)gridDim.x, n_next, k_next); }
+    const int nv_next = more ? (VARLEN ? groups_inside(n_next) : nv) : 0;
+    if constexpr (VARLEN) pad_row(out, k_row, p.k, tid);
+    if (VARLEN && k_row == 0) {
         // a row of padding (uniform over the workgroup): nothing to select, only the next row's load
 #pragma unroll
         for (int i = 0; i < V4; ++i) {
@@ -230,7 +232,7 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
         n = n_next; k_row = k_next; nv = nv_next;
         continue;
     }
-    const bool straddles = (n & 3) != 0;              // uniform: variable-length rows only
+    const bool straddles = VARLEN && (n & 3) != 0;    // uniform: variable-length rows only
 
     uint32_t kmax = 0u, kmin = 0xFFFFFFFFu;
 #pragma unroll
@@ -456,19 +458,25 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
             for (int c = 0; c < 4; ++c) key[i][c] = v[c];
         }
     }
-    n = n_next; k_row = k_next; nv = nv_next;
+    if constexpr (VARLEN) { n = n_next; k_row = k_next; nv = nv_next; }
     __syncthreads();                                   // wave_a / wave_b are rewritten by the next row
   }
 }
 
-template <int V4>
-hipError_t launch_rows(const TopkParams& p, hipStream_t s) {
+template <int V4, bool VARLEN>
+hipError_t launch_rows_as(const TopkParams& p, hipStream_t s) {
     // as many workgroups as the chip holds at a time (1024 threads at more than 64 registers: one
     // per CU); each walks over its share of the rows
     const int resident = compute_units();
     const int grid = p.rows < resident ? p.rows : resident;
-    hipLaunchKernelGGL((topk_rows_kernel<V4>), dim3(grid), dim3(TK_THREADS), 0, s, p);
+    hipLaunchKernelGGL((topk_rows_kernel<V4, VARLEN>), dim3(grid), dim3(TK_THREADS), 0, s, p);
     return hipGetLastError();
+}
+
+template <int V4>
+hipError_t launch_rows(const TopkParams& p, hipStream_t s) {
+    if (p.varlen != nullptr) return launch_rows_as<V4, true>(p, s);
+    return launch_rows_as<V4, false>(p, s);
 }
 
 // One workgroup per score row: thread i adds up key block i (a fixed order: bit-identical from run to
