@@ -504,7 +504,9 @@ def groupwise_config(pc, torch, dev, w, keep, G, host_qkv):
 
 def roofline_probes(kept_tflops, dense_tflops):
     """What the simplest kernels reach on this machine (stand-alone program, child process): an
-    MFMA-only loop with constant and with random operands, and a 1 GiB copy."""
+    MFMA-only loop with constant and with random operands, the same loop with one or two softmax
+    weights per matrix instruction (the instruction mix of the attention kernels and of the select
+    passes), and a 1 GiB copy."""
     import subprocess
     exe = os.path.join(ROOT, "roofline_probe.bin")
     if not os.path.exists(exe):
@@ -518,6 +520,10 @@ def roofline_probes(kept_tflops, dense_tflops):
     p["attn_frac_of_mfma_only_random_operands"] = round(kept_tflops / ceil, 4)
     if dense_tflops:
         p["dense_frac_of_mfma_only_random_operands"] = round(dense_tflops / ceil, 4)
+    # the same matrix instructions with the attention kernels' one softmax weight per instruction beside them
+    mix = p.get("mfma_plus_1_weight_tflops")
+    if mix:
+        p["attn_frac_of_mfma_plus_1_weight"] = round(kept_tflops / mix, 4)
     return p
 
 

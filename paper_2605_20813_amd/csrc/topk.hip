@@ -479,31 +479,61 @@ hipError_t launch_rows(const TopkParams& p, hipStream_t s) {
     return launch_rows_as<V4, false>(p, s);
 }
 
-// One workgroup per score row: thread i adds up key block i (a fixed order: bit-identical from run to
-// run); a row's sums go over its own first elements once every thread has read its block.
-__global__ void __launch_bounds__(256) block_sums_kernel(const float* __restrict__ scores, float* __restrict__ out,
-                                                         int32_t n, int64_t stride, int32_t block) {
-    const float* __restrict__ row = scores + (int64_t)blockIdx.x * stride;
+// Block masses, in place.  One workgroup per score row; a sweep of the workgroup covers 1024 consecutive scores with one
+// 16-byte load per lane, so 16 neighbouring lanes hold one key block of 64 scores; its sum is the lane's four values
+// added in order, then four exchange steps inside the 16 lanes (a fixed tree: bit-identical from run to run).  The sum
+// of block j goes to element j of the same row.  Element j is read in sweep j / 1024 and the sum of sweep t lands in
+// elements [16 t, 16 t + 16), so a store can only overtake a load of a sweep that is not later than its own: a barrier
+// between the loads and the stores of every batch of sweeps orders the in-place update.
+constexpr int BS_THREADS = 256;
+constexpr int BS_UNROLL = 8;        // sweeps whose loads are issued together
+
+__global__ void __launch_bounds__(BS_THREADS) block_sums_kernel(const float* __restrict__ scores, float* __restrict__ out,
+                                                                int32_t n, int64_t stride) {
+    const float4* __restrict__ row = reinterpret_cast<const float4*>(scores + (int64_t)blockIdx.x * stride);
     float* __restrict__ dst = out + (int64_t)blockIdx.x * stride;
-    const int nblocks = n / block;
-    for (int base = 0; base < nblocks; base += 256) {
-        const int j = base + threadIdx.x;
-        float acc = 0.f;
-        if (j < nblocks) {
-            const float* src = row + (int64_t)j * block;
-            for (int c = 0; c < block; ++c) acc += src[c];
-        }
-        __syncthreads();            // every block of this round has been read: the sums may overwrite the row's front
-        if (j < nblocks) dst[j] = acc;
+    const int sweeps = n / (4 * BS_THREADS);                 // whole sweeps; the rest (a multiple of 64 scores) follows
+    const int tid = threadIdx.x;
+    auto fold = [](float4 v) {
+        float a = (v.x + v.y) + (v.z + v.w);
+        a += __shfl_xor(a, 1);
+        a += __shfl_xor(a, 2);
+        a += __shfl_xor(a, 4);
+        a += __shfl_xor(a, 8);
+        return a;
+    };
+    int t = 0;
+    for (; t + BS_UNROLL <= sweeps; t += BS_UNROLL) {
+        float4 v[BS_UNROLL];
+#pragma unroll
+        for (int u = 0; u < BS_UNROLL; ++u) v[u] = row[(int64_t)(t + u) * BS_THREADS + tid];
+        float a[BS_UNROLL];
+#pragma unroll
+        for (int u = 0; u < BS_UNROLL; ++u) a[u] = fold(v[u]);
         __syncthreads();
+        if ((tid & 15) == 0) {
+#pragma unroll
+            for (int u = 0; u < BS_UNROLL; ++u) dst[(t + u) * (BS_THREADS / 16) + (tid >> 4)] = a[u];
+        }
+    }
+    // what is left: fewer than BS_UNROLL whole sweeps, then a part of a sweep
+    for (; t <= sweeps; ++t) {
+        const int e = (t * BS_THREADS + tid) * 4;            // first score of this lane
+        const bool live = e < n;
+        float4 v = live ? row[(int64_t)t * BS_THREADS + tid] : float4{0.f, 0.f, 0.f, 0.f};
+        const float a = fold(v);
+        __syncthreads();
+        if (live && (tid & 15) == 0) dst[t * (BS_THREADS / 16) + (tid >> 4)] = a;
     }
 }
 
 }  // namespace
 
 hipError_t launch_block_sums(const float* scores, float* out, int32_t rows, int32_t n, int64_t stride, int32_t block, hipStream_t s) {
-    if (rows < 1 || n < block || block < 1 || n % block != 0) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(block_sums_kernel, dim3(rows), dim3(256), 0, s, scores, out, n, stride, block);
+    // 16 lanes x 16 bytes = one key block; rows start on 16-byte boundaries
+    if (rows < 1 || block != 64 || n < block || n % block != 0 || stride % 4 != 0) return hipErrorInvalidValue;
+    if ((reinterpret_cast<uintptr_t>(scores) & 15u) != 0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(block_sums_kernel, dim3(rows), dim3(BS_THREADS), 0, s, scores, out, n, stride);
     return hipGetLastError();
 }
 
