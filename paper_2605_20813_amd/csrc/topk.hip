@@ -11,6 +11,7 @@
 // 65536 elements, a multiple of 4, 16-byte aligned: every shape of the paper's workloads; a
 // resident grid whose workgroups walk over the rows and fetch the next row while writing out);
 // topk_kernel streams the row from memory five times and takes everything else.
+#include <type_traits>
 #include "pulsecol_device.h"
 #include "pulsecol_kernels.h"
 
@@ -148,6 +149,19 @@ __global__ void __launch_bounds__(TK_THREADS) topk_kernel(TopkParams p) {
 // send every element to the same histogram bin, and same-address LDS atomics serialise): at most
 // three passes, 8192 bins.  Then the ordered compaction: every wave knows from the per-wave
 // totals where its output starts, and places its elements with ballots alone (no barrier inside).
+//
+// A workgroup walks over a run of consecutive rows (the query groups of one head, one after the
+// other), and the k-th largest score of a row is close to that of the row before (a few percent).
+// From the second row on, the select therefore starts from an estimate: every fourth key of the
+// row is counted against two levels below and above the last row's threshold, and the level that
+// a quarter of k keys would exceed is interpolated.  One sweep then counts the keys above a
+// bracket around the estimate and collects the keys inside it, wave by wave, into the candidate
+// list.  If the k-th largest key lies inside (count above < k <= count above + list size, and no
+// wave's share of the list overflowed), the radix passes run over the list alone and the full
+// first pass and the list-building sweep are saved; if not, the row takes the full path.  Either
+// way the threshold is the exact k-th largest key: the estimate only decides how it is found.
+// The bracket's half width follows the estimate's error (see below); it doubles after a miss and
+// halves after an overflow.
 constexpr int TKR_DIGIT = 13;
 constexpr int TKR_BINS = 1 << TKR_DIGIT;
 constexpr int TKR_BPT = TKR_BINS / TK_THREADS;       // histogram bins per thread
@@ -170,8 +184,12 @@ __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
 
 // VARLEN: variable-length batches (rows of their own length and kept count, rows of padding); the
 // fixed-length instantiation carries none of that bookkeeping, which costs it registers it does not have.
+constexpr int TKR_WAVE_CAND = 256;                   // a wave's share of the candidate list on the bracket path
+constexpr uint32_t TKR_PROBE = 1u << 19;             // distance of the probe levels from the last row's threshold, in key units
+constexpr uint32_t TKR_HALF_WIDTH_MIN = 1u << 12, TKR_HALF_WIDTH_MAX = 1u << 22;
+
 template <int V4, bool VARLEN>
-__global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
+__global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p, int rows_per_wg) {
     constexpr int SEG = 256 * V4;
     static_assert(TKR_BPT * TK_THREADS == TKR_BINS && TKR_BPT % 4 == 0, "whole 16-byte groups of bins per thread");
     __shared__ __attribute__((aligned(16))) uint32_t hist[TKR_BINS];
@@ -180,7 +198,9 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
     // the elements that fell into the first pass's bin, if they are few enough: the later passes
     // then walk over this list instead of sweeping the registers again
     constexpr int CAND_MAX = 4096;
+    static_assert(TKR_WAVE_CAND * TK_WAVES == CAND_MAX, "the waves' shares make up the list");
     __shared__ uint32_t cand[CAND_MAX];
+    __shared__ uint32_t seg_cnt[TK_WAVES];             // bracket path: candidates in each wave's share
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -191,11 +211,17 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
     auto groups_inside = [&](int n_row) {
         return first >= n_row ? 0 : ((n_row - first + 255) / 256 < V4 ? (n_row - first + 255) / 256 : V4);
     };
+    const int row_begin = blockIdx.x * rows_per_wg;
+    const int row_end = row_begin + rows_per_wg < p.rows ? row_begin + rows_per_wg : p.rows;
+    if (row_begin >= row_end) return;                  // uniform (the grid is sized so that it does not happen)
     int n = p.n, k_row = p.k;
-    if constexpr (VARLEN) row_geometry(p, blockIdx.x, n, k_row);
+    if constexpr (VARLEN) row_geometry(p, row_begin, n, k_row);
     int nv = groups_inside(n);
+    // the last row's threshold key and the bracket's half width, in key units (2^17: about one percent of a score)
+    uint32_t guess = 0u, half_width = 1u << 17;
+    bool have_guess = false;
 
-    // The workgroup walks over rows blockIdx.x, + gridDim.x, ...; the scores of the next row are
+    // The workgroup walks over rows row_begin .. row_end - 1; the scores of the next row are
     // requested while the running row is written out (each register group as soon as the
     // compaction is done with it), so that only the first row's load is waited for in full.
     // key[][] holds the row: as float bit patterns from the load until the row's turn comes, as
@@ -205,18 +231,18 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
 #pragma unroll
     for (int i = 0; i < V4; ++i) {
         u32x4 v = {0u, 0u, 0u, 0u};                          // outside the row: never looked at, every use is guarded by nv
-        if (i < nv) v = *(const u32x4*)(bits + (int64_t)blockIdx.x * p.stride + first + i * 256);
+        if (i < nv) v = *(const u32x4*)(bits + (int64_t)row_begin * p.stride + first + i * 256);
 #pragma unroll
         for (int c = 0; c < 4; ++c) key[i][c] = v[c];
     }
 
-  for (int row = blockIdx.x; row < p.rows; row += gridDim.x) {
+  for (int row = row_begin; row < row_end; ++row) {
     int32_t* __restrict__ out = p.idx + (int64_t)row * p.k;
-    const bool more = row + (int)gridDim.x < p.rows;
-    const uint32_t* __restrict__ next_bits = bits + (int64_t)(more ? row + (int)gridDim.x : row) * p.stride + first;
+    const bool more = row + 1 < row_end;
+    const uint32_t* __restrict__ next_bits = bits + (int64_t)(more ? row + 1 : row) * p.stride + first;
     // this row's geometry was settled when its load was issued; the next row's decides what is fetched for it
     int n_next = p.n, k_next = p.k;
-    if constexpr (VARLEN) { if (more) row_geometry(p, row + (int)gridDim.x, n_next, k_next); }
+    if constexpr (VARLEN) { if (more) row_geometry(p, row + 1, n_next, k_next); }
     const int nv_next = more ? (VARLEN ? groups_inside(n_next) : nv) : 0;
     if constexpr (VARLEN) pad_row(out, k_row, p.k, tid);
     if (VARLEN && k_row == 0) {
@@ -234,50 +260,143 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
     }
     const bool straddles = VARLEN && (n & 3) != 0;    // uniform: variable-length rows only
 
-    uint32_t kmax = 0u, kmin = 0xFFFFFFFFu;
 #pragma unroll
     for (int i = 0; i < V4; ++i) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            key[i][c] = order_key_of_bits(key[i][c]);
-            if (i < nv && (!straddles || first + i * 256 + c < n)) {
-                kmax = key[i][c] > kmax ? key[i][c] : kmax;
-                kmin = key[i][c] < kmin ? key[i][c] : kmin;
-            }
-        }
+        for (int c = 0; c < 4; ++c) key[i][c] = order_key_of_bits(key[i][c]);
     }
-    kmax = wave_max_u32(kmax);
-    kmin = wave_min_u32(kmin);
-    if (lane == 0) { wave_a[wave] = kmax; wave_b[wave] = kmin; }
-    __syncthreads();
-#pragma unroll
-    for (int w = 0; w < TK_WAVES; ++w) {
-        kmax = wave_a[w] > kmax ? wave_a[w] : kmax;
-        kmin = wave_b[w] < kmin ? wave_b[w] : kmin;
-    }
-    __syncthreads();                                   // wave_a / wave_b are reused below
-    if (straddles) {
-        // the elements a 16-byte load brought in from behind the row's end take the row's smallest key: they
-        // follow every real element in index order, so the selection (k_row <= n real elements) never reaches them
+    // bits of a ballot that belong to the lanes in front of this one, counted on top of `acc`
+    auto count_before = [](uint64_t ballot, uint32_t acc) {
+        return __builtin_amdgcn_mbcnt_hi((uint32_t)(ballot >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ballot, acc));
+    };
+
+    // ---- the bracket around the last row's threshold (see the head of this kernel)
+    uint32_t prefix = 0u, need = (uint32_t)k_row;
+    int hi = -1;
+    bool bracketed = false;
+    uint32_t above_wave = 0u;                          // bracket path: this wave's keys above the bracket
+    uint32_t listed_last = 0u;                         // ... and the row's
+    uint32_t est = 0u;
+    bool placed = false;
+    if (!VARLEN && have_guess) {
+        // (1) Where this row's k-th largest key lies relative to the last row's: every fourth key of the row is
+        // counted against two probe levels, half a million key units (about 4 % of a score) below and above the
+        // last threshold; the level that a quarter of k keys would exceed is interpolated between them.
+        const uint32_t g_lo = guess > TKR_PROBE ? guess - TKR_PROBE : 0u;
+        const uint32_t g_hi = guess < 0xFFFFFFFFu - TKR_PROBE ? guess + TKR_PROBE : 0xFFFFFFFFu;
+        uint32_t cnt = 0u;                             // keys above g_lo in the low half, above g_hi in the high half
 #pragma unroll
         for (int i = 0; i < V4; ++i) {
+            if (i < nv) cnt += (key[i][0] > g_lo ? 1u : 0u) + (key[i][0] > g_hi ? 0x10000u : 0u);
+        }
+        cnt = wave_sum_u32(cnt);                       // at most 16 * 64 per wave and half, 16384 per row
+        if (lane == 0) wave_a[wave] = cnt;
+        __syncthreads();
+        uint32_t all = 0u;
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-                if (i < nv && first + i * 256 + c >= n) key[i][c] = kmin;
+        for (int w = 0; w < TK_WAVES; ++w) all += wave_a[w];
+        __syncthreads();                               // wave_a is reused below
+        const uint32_t c_lo = 4u * (all & 0xFFFFu), c_hi = 4u * (all >> 16);
+        if (c_lo >= (uint32_t)k_row && (uint32_t)k_row > c_hi) {
+            const float frac = (float)(c_lo - (uint32_t)k_row) / (float)(c_lo - c_hi);
+            est = g_lo + (uint32_t)(frac * (float)(g_hi - g_lo));
+            placed = true;
+        }
+    }
+    if (placed) {
+        // (2) the bracket around the estimate
+        const uint32_t lo_key = est > half_width ? est - half_width : 0u;
+        const uint32_t hi_key = est < 0xFFFFFFFFu - half_width ? est + half_width : 0xFFFFFFFFu;
+        const uint32_t span = hi_key - lo_key;         // > 0: half_width >= 1
+        uint32_t above = 0u, off = 0u;                 // off: candidates of this wave so far (uniform)
+#pragma unroll
+        for (int i = 0; i < V4; ++i) {
+            if (i < nv) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const uint32_t kx = key[i][c];
+                    above += kx > hi_key ? 1u : 0u;
+                    const bool hit = kx - lo_key <= span;
+                    const uint64_t hit_b = __ballot(hit);
+                    if (hit_b != 0ull) {
+                        const uint32_t at = count_before(hit_b, off);
+                        if (hit && at < (uint32_t)TKR_WAVE_CAND) cand[wave * TKR_WAVE_CAND + at] = kx;
+                        off += __popcll(hit_b);
+                    }
+                }
+            }
+        }
+        above = wave_sum_u32(above);
+        if (lane == 0) { wave_a[wave] = above; seg_cnt[wave] = off; }
+        __syncthreads();
+        uint32_t all_above = 0u, all_listed = 0u;
+        bool overflow = false;
+#pragma unroll
+        for (int w = 0; w < TK_WAVES; ++w) {
+            all_above += wave_a[w];
+            all_listed += seg_cnt[w];
+            overflow = overflow || seg_cnt[w] > (uint32_t)TKR_WAVE_CAND;
+        }
+        __syncthreads();                               // wave_a is reused below
+        listed_last = all_listed;
+        if (!overflow && all_above < (uint32_t)k_row && (uint32_t)k_row <= all_above + all_listed) {
+            bracketed = true;
+            above_wave = above;
+            need = (uint32_t)k_row - all_above;
+            // every key on the list agrees with the bracket's ends above their highest differing bit
+            hi = 31 - __clz((int)(lo_key ^ hi_key));
+            prefix = hi >= 31 ? 0u : ((lo_key >> (hi + 1)) << (hi + 1));
+        } else if (overflow) {
+            half_width = half_width > 2u * TKR_HALF_WIDTH_MIN ? half_width >> 1 : TKR_HALF_WIDTH_MIN;
+        } else {
+            half_width = half_width < TKR_HALF_WIDTH_MAX ? half_width << 1 : TKR_HALF_WIDTH_MAX;
         }
     }
 
+    if (!bracketed) {
+        uint32_t kmax = 0u, kmin = 0xFFFFFFFFu;
+#pragma unroll
+        for (int i = 0; i < V4; ++i) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (i < nv && (!straddles || first + i * 256 + c < n)) {
+                    kmax = key[i][c] > kmax ? key[i][c] : kmax;
+                    kmin = key[i][c] < kmin ? key[i][c] : kmin;
+                }
+            }
+        }
+        kmax = wave_max_u32(kmax);
+        kmin = wave_min_u32(kmin);
+        if (lane == 0) { wave_a[wave] = kmax; wave_b[wave] = kmin; }
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < TK_WAVES; ++w) {
+            kmax = wave_a[w] > kmax ? wave_a[w] : kmax;
+            kmin = wave_b[w] < kmin ? wave_b[w] : kmin;
+        }
+        __syncthreads();                                   // wave_a / wave_b are reused below
+        if (straddles) {
+            // the elements a 16-byte load brought in from behind the row's end take the row's smallest key: they
+            // follow every real element in index order, so the selection (k_row <= n real elements) never reaches them
+#pragma unroll
+            for (int i = 0; i < V4; ++i) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (i < nv && first + i * 256 + c >= n) key[i][c] = kmin;
+            }
+        }
+        // Bits above `hi` are the same in every key of the row.
+        hi = 31 - __clz((int)(kmax ^ kmin));           // -1 if all keys are equal
+        prefix = hi >= 31 ? 0u : ((kmax >> (hi + 1)) << (hi + 1));
+    }
+
     // ---- radix select: afterwards `prefix` is the key of the k-th largest element and `need`
-    //      how many elements equal to it belong to the top-k.  Bits above `hi` are the same in
-    //      every key of the row.
-    int hi = 31 - __clz((int)(kmax ^ kmin));           // -1 if all keys are equal
-    uint32_t prefix = hi >= 31 ? 0u : ((kmax >> (hi + 1)) << (hi + 1));
-    uint32_t need = (uint32_t)k_row;
+    //      how many elements equal to it belong to the top-k.
     // register groups of this lane that still hold an element matching the prefix: all of them in
     // the first pass, next to none later (a bin of the first pass holds n/8192 elements on
     // average), so that the later passes skip almost all of their work, whole waves at a time
     uint32_t live = nv >= 32 ? 0xFFFFFFFFu : ((1u << nv) - 1u);
-    bool first_pass = true, listed = false;
+    bool first_pass = !bracketed, listed = bracketed;
     uint32_t ncand = 0;
     while (hi >= 0) {
         const int width = hi + 1 < TKR_DIGIT ? hi + 1 : TKR_DIGIT;
@@ -295,6 +414,15 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
                 if (i < nv) {
 #pragma unroll
                     for (int c = 0; c < 4; ++c) atomicAdd(&hist[(key[i][c] ^ prefix) >> shift], 1u);
+                }
+            }
+        } else if (bracketed) {
+            // the list lies in the waves' shares, seg_cnt[w] entries at the front of share w
+#pragma unroll
+            for (int j = tid; j < CAND_MAX; j += TK_THREADS) {
+                if ((uint32_t)(j % TKR_WAVE_CAND) < seg_cnt[j / TKR_WAVE_CAND]) {
+                    const uint32_t x = (cand[j] ^ prefix) >> shift;
+                    if (x < limit) atomicAdd(&hist[x], 1u);
                 }
             }
         } else if (listed) {
@@ -380,15 +508,40 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
         //  the last pass, behind the barrier below)
     }
 
-    // ---- ordered compaction.  Per wave: elements above the threshold and elements equal to it.
+    if (bracketed) {
+        // the half width follows the estimate's error: it shrinks by an eighth per row and is raised at once
+        // to two and a half times the last error
+        const uint32_t err = prefix > est ? prefix - est : est - prefix;
+        uint32_t next = half_width - (half_width >> 3);
+        const uint32_t floor_hw = err < TKR_HALF_WIDTH_MAX ? err * 2u + (err >> 1) : TKR_HALF_WIDTH_MAX;
+        next = next > floor_hw ? next : floor_hw;
+        half_width = next < TKR_HALF_WIDTH_MIN ? TKR_HALF_WIDTH_MIN : (next > TKR_HALF_WIDTH_MAX ? TKR_HALF_WIDTH_MAX : next);
+        // ... and a wave's share of the list is short: no wider than what gave three quarters of the list's room
+        if (listed_last > 3u * TK_THREADS) half_width -= half_width >> 2;
+    }
+    guess = prefix;
+    have_guess = !VARLEN;          // (the variable-length instantiation has no registers to spare for the estimate)
+
+    // ---- ordered compaction.  Per wave: elements above the threshold and elements equal to it
+    // (on the bracket path: the keys above the bracket are counted already, the rest is on the
+    // wave's share of the list).
     uint32_t n_gt = 0, n_eq = 0;
+    if (bracketed) {
+        for (uint32_t j = lane; j < seg_cnt[wave]; j += 64) {
+            const uint32_t kx = cand[wave * TKR_WAVE_CAND + j];
+            n_gt += kx > prefix ? 1u : 0u;
+            n_eq += kx == prefix ? 1u : 0u;
+        }
+        n_gt += lane == 0 ? above_wave : 0u;
+    } else {
 #pragma unroll
-    for (int i = 0; i < V4; ++i) {
-        if (i < nv) {
+        for (int i = 0; i < V4; ++i) {
+            if (i < nv) {
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                n_gt += key[i][c] > prefix ? 1u : 0u;
-                n_eq += key[i][c] == prefix ? 1u : 0u;
+                for (int c = 0; c < 4; ++c) {
+                    n_gt += key[i][c] > prefix ? 1u : 0u;
+                    n_eq += key[i][c] == prefix ? 1u : 0u;
+                }
             }
         }
     }
@@ -409,48 +562,59 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
             eq_seen += e;
         }
     }
-    // bits of a ballot that belong to the lanes in front of this one, counted on top of `acc`
-    auto count_before = [](uint64_t ballot, uint32_t acc) {
-        return __builtin_amdgcn_mbcnt_hi((uint32_t)(ballot >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ballot, acc));
-    };
-#pragma unroll
-    for (int i = 0; i < V4; ++i) {
-      if (wave * SEG + i * 256 < n) {                  // uniform: nothing of this wave lies beyond
+    // the same in every lane: kept in scalar registers, like the running counts below
+    eq_seen = __builtin_amdgcn_readfirstlane(eq_seen);
+    out_pos = __builtin_amdgcn_readfirstlane(out_pos);
+    const bool wave_has_eq = __builtin_amdgcn_readfirstlane(n_eq) != 0u;
+    // Lane masks throughout: a comparison is one instruction that leaves its mask in scalar registers, the
+    // logic on the masks is scalar work beside the vector pipe, and nothing is evaluated under a narrowed
+    // execution mask except the stores themselves.  Two versions of the loop: most waves hold no element
+    // equal to the threshold (ties at the k-th value are rare) and run the one that does not look for any.
+    auto compact_group = [&](int i, auto with_eq_c) {
+        constexpr bool WITH_EQ = decltype(with_eq_c)::value;
         const bool in = i < nv;
-        // elements equal to the threshold are rare (ties at the k-th value): the four ballots that
-        // rank them are taken only if the wave holds one in this register group
-        bool eq[4], sel[4];
-        uint32_t eq_rank = eq_seen, eq_all = 0;
+        bool sel[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) eq[c] = in && key[i][c] == prefix;
-        if (__ballot(eq[0] || eq[1] || eq[2] || eq[3]) != 0ull) {
+        for (int c = 0; c < 4; ++c) sel[c] = in & (key[i][c] > prefix);
+        if constexpr (WITH_EQ) {
+            bool eq[4];
+            uint32_t eq_rank = eq_seen;                     // equal elements of the lanes in front ...
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
+                eq[c] = in & (key[i][c] == prefix);
                 const uint64_t eq_b = __ballot(eq[c]);
-                eq_rank = count_before(eq_b, eq_rank);          // equal elements of the lanes in front
-                eq_all += __popcll(eq_b);
+                eq_rank = count_before(eq_b, eq_rank);
+                eq_seen += __popcll(eq_b);
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                sel[c] = sel[c] | (eq[c] & (eq_rank < need));
+                eq_rank += eq[c] ? 1u : 0u;                 // ... and of this lane's earlier elements
             }
         }
-        uint64_t sel_b[4];
         uint32_t pos = out_pos, sel_all = 0;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            sel[c] = in && (key[i][c] > prefix || (eq[c] && eq_rank < need));
-            eq_rank += eq[c] ? 1u : 0u;                         // ... and of this lane's earlier elements
-            sel_b[c] = __ballot(sel[c]);
-            pos = count_before(sel_b[c], pos);
-            sel_all += __popcll(sel_b[c]);
+            const uint64_t sel_b = __ballot(sel[c]);
+            pos = count_before(sel_b, pos);
+            sel_all += __popcll(sel_b);
         }
+        // (guard: holds by construction; no store can land behind the row's k_row entries.  Folded into the
+        //  masks: a branch here would make the compiler carry the masks through vector registers.)
+        const bool fits = out_pos + sel_all <= (uint32_t)k_row;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            if (sel[c]) {
-                if (pos < (uint32_t)k_row) out[pos] = first + i * 256 + c;     // guard: holds by construction
-                ++pos;
-            }
+            if (sel[c] & fits) out[pos] = first + i * 256 + c;
+            pos += sel[c] ? 1u : 0u;
         }
-        eq_seen += eq_all;
         out_pos += sel_all;
-      }
+    };
+#pragma unroll
+    for (int i = 0; i < V4; ++i) {
+        if (wave * SEG + i * 256 < n) {                  // uniform: nothing of this wave lies beyond
+            if (wave_has_eq) compact_group(i, std::true_type{});
+            else compact_group(i, std::false_type{});
+        }
         // the compaction is done with this register group: refill it with the next row's scores
         if (i < nv_next) {
             const u32x4 v = *(const u32x4*)(next_bits + i * 256);
@@ -466,10 +630,11 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p) {
 template <int V4, bool VARLEN>
 hipError_t launch_rows_as(const TopkParams& p, hipStream_t s) {
     // as many workgroups as the chip holds at a time (1024 threads at more than 64 registers: one
-    // per CU); each walks over its share of the rows
+    // per CU); each walks over its run of consecutive rows
     const int resident = compute_units();
-    const int grid = p.rows < resident ? p.rows : resident;
-    hipLaunchKernelGGL((topk_rows_kernel<V4, VARLEN>), dim3(grid), dim3(TK_THREADS), 0, s, p);
+    const int rows_per_wg = (p.rows + resident - 1) / resident;
+    const int grid = (p.rows + rows_per_wg - 1) / rows_per_wg;
+    hipLaunchKernelGGL((topk_rows_kernel<V4, VARLEN>), dim3(grid), dim3(TK_THREADS), 0, s, p, rows_per_wg);
     return hipGetLastError();
 }
 

@@ -261,6 +261,34 @@ def test_topk_orders_signs_magnitudes_and_narrow_ranges(n):
         assert np.array_equal(idx, oracle.topk_columns(f64(s), k)), f"k={k}"
 
 
+@pytest.mark.parametrize("rows,n,k", [(777, 4096, 409), (600, 16384, 1638), (520, 65536, 6553)])
+def test_topk_rows_of_changing_distributions(rows, n, k):
+    """A workgroup walks over consecutive rows and starts each select from a bracket around the threshold of
+    the row before.  Consecutive rows here differ in scale, sign, spread and number of ties, so the bracket
+    misses on either side, overflows, or holds the answer among ties: every row must still be exact."""
+    say(f"topk changing rows={rows} n={n} k={k}")
+    g = torch.Generator().manual_seed(rows + n)
+    s = torch.rand(rows, n, generator=g) / n
+    kind = torch.arange(rows) % 9
+    s[kind == 1] *= 1000.0                                                         # threshold far above the last one
+    s[kind == 2] *= 1e-3                                                           # far below
+    s[kind == 3] = 1.0 + torch.randint(0, 5, (int((kind == 3).sum()), n), generator=g).float() * 2.0 ** -23   # a few values, many ties
+    s[kind == 4] = -s[kind == 4]                                                   # negative
+    s[kind == 5] = 0.25                                                            # all equal
+    s[kind == 6] = s[kind == 6] * (1.0 + 1e-6 * torch.randn(int((kind == 6).sum()), 1, generator=g))   # like the row before the break
+    s[kind == 7] = torch.round(s[kind == 7] * n * 64.0) / (n * 64.0)              # 65 levels: the threshold is a tie
+    # kind 0 and 8: plain rows next to each other (the bracket holds)
+    with pc.Context(1, rows, n, 128, torch.bfloat16) as ctx:
+        idx = ctx.topk(s.view(1, rows, 1, n).to(DEV), k)
+        again = ctx.topk(s.view(1, rows, 1, n).to(DEV), k)
+        torch.cuda.synchronize()
+    assert torch.equal(idx, again)
+    want = oracle.topk_columns(f64(s), k)
+    got = idx.cpu().numpy().reshape(rows, k)
+    bad = np.nonzero((got != want).any(axis=1))[0]
+    assert bad.size == 0, f"rows {bad[:8].tolist()} (kinds {kind[bad[:8]].tolist()}) differ"
+
+
 def test_topk_degenerate_rows():
     n = 3000
     say("topk degenerate rows")
