@@ -153,8 +153,8 @@ __global__ void __launch_bounds__(TK_THREADS) topk_kernel(TopkParams p) {
 // A workgroup walks over a run of consecutive rows (the query groups of one head, one after the
 // other), and the k-th largest score of a row is close to that of the row before (a few percent).
 // From the second row on, the select therefore starts from an estimate: every fourth key of the
-// row is counted against two levels below and above the last row's threshold, and the level that
-// a quarter of k keys would exceed is interpolated.  One sweep then counts the keys above a
+// row is counted against the last row's threshold and a level below and above it, and the level
+// that a quarter of k keys would exceed is interpolated.  One sweep then counts the keys above a
 // bracket around the estimate and collects the keys inside it, wave by wave, into the candidate
 // list.  If the k-th largest key lies inside (count above < k <= count above + list size, and no
 // wave's share of the list overflowed), the radix passes run over the list alone and the full
@@ -176,16 +176,29 @@ __device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
     for (int d = 32; d >= 1; d >>= 1) { const uint32_t o = __shfl_xor(v, d); v = o < v ? o : v; }
     return v;
 }
-__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
+// Inclusive prefix sum over the 64 lanes with data-parallel-primitive moves (no LDS round trips: a
+// shuffle goes through the LDS crossbar, and a row's select has a dozen reductions on its serial path):
+// four shifts inside the rows of 16 lanes, then lane 15 of rows 0 and 2 onto rows 1 and 3, then lane 31
+// onto rows 2 and 3.
+__device__ __forceinline__ uint32_t wave_prefix_sum_u32(uint32_t v) {
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, true);      // row_shr:1
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, true);      // row_shr:2
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, true);      // row_shr:4
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, true);      // row_shr:8
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false);     // row_bcast:15 -> rows 1, 3
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false);     // row_bcast:31 -> rows 2, 3
     return v;
+}
+// the sum over the wave, the same in every lane (a scalar)
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_readlane((int)wave_prefix_sum_u32(v), 63);
 }
 
 // VARLEN: variable-length batches (rows of their own length and kept count, rows of padding); the
 // fixed-length instantiation carries none of that bookkeeping, which costs it registers it does not have.
 constexpr int TKR_WAVE_CAND = 256;                   // a wave's share of the candidate list on the bracket path
-constexpr uint32_t TKR_PROBE = 1u << 19;             // distance of the probe levels from the last row's threshold, in key units
+constexpr int TKR_FEW = 32;                          // keys that one wave ranks directly instead of another radix pass
+constexpr uint32_t TKR_PROBE = 1u << 20;             // distance of the probe levels from the last row's threshold, in key units
 constexpr uint32_t TKR_HALF_WIDTH_MIN = 1u << 12, TKR_HALF_WIDTH_MAX = 1u << 22;
 
 template <int V4, bool VARLEN>
@@ -201,6 +214,7 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p, int
     static_assert(TKR_WAVE_CAND * TK_WAVES == CAND_MAX, "the waves' shares make up the list");
     __shared__ uint32_t cand[CAND_MAX];
     __shared__ uint32_t seg_cnt[TK_WAVES];             // bracket path: candidates in each wave's share
+    __shared__ uint32_t few[TKR_FEW];                  // the last keys of a select, ranked directly
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -280,26 +294,36 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p, int
     bool placed = false;
     if (!VARLEN && have_guess) {
         // (1) Where this row's k-th largest key lies relative to the last row's: every fourth key of the row is
-        // counted against two probe levels, half a million key units (about 4 % of a score) below and above the
-        // last threshold; the level that a quarter of k keys would exceed is interpolated between them.
+        // counted against three levels, the last threshold and a million key units (about 8 % of a score) below
+        // and above it.  Between the two levels that enclose a quarter of k, the level is interpolated on the
+        // logarithm of the counts: the number of keys above a level falls off roughly exponentially with the
+        // level near the top of a row, and a straight line between the counts is off by a fifth of the interval.
         const uint32_t g_lo = guess > TKR_PROBE ? guess - TKR_PROBE : 0u;
         const uint32_t g_hi = guess < 0xFFFFFFFFu - TKR_PROBE ? guess + TKR_PROBE : 0xFFFFFFFFu;
-        uint32_t cnt = 0u;                             // keys above g_lo in the low half, above g_hi in the high half
+        uint32_t cnt = 0u, cnt_mid = 0u;               // cnt: keys above g_lo in the low half, above g_hi in the high half
 #pragma unroll
         for (int i = 0; i < V4; ++i) {
-            if (i < nv) cnt += (key[i][0] > g_lo ? 1u : 0u) + (key[i][0] > g_hi ? 0x10000u : 0u);
+            if (i < nv) {
+                cnt += (key[i][0] > g_lo ? 1u : 0u) + (key[i][0] > g_hi ? 0x10000u : 0u);
+                cnt_mid += key[i][0] > guess ? 1u : 0u;
+            }
         }
         cnt = wave_sum_u32(cnt);                       // at most 16 * 64 per wave and half, 16384 per row
-        if (lane == 0) wave_a[wave] = cnt;
+        cnt_mid = wave_sum_u32(cnt_mid);
+        if (lane == 0) { wave_a[wave] = cnt; wave_b[wave] = cnt_mid; }
         __syncthreads();
-        uint32_t all = 0u;
+        uint32_t all = 0u, all_mid = 0u;
 #pragma unroll
-        for (int w = 0; w < TK_WAVES; ++w) all += wave_a[w];
-        __syncthreads();                               // wave_a is reused below
-        const uint32_t c_lo = 4u * (all & 0xFFFFu), c_hi = 4u * (all >> 16);
+        for (int w = 0; w < TK_WAVES; ++w) { all += wave_a[w]; all_mid += wave_b[w]; }
+        __syncthreads();                               // wave_a / wave_b are reused below
+        const uint32_t c_lo = 4u * (all & 0xFFFFu), c_hi = 4u * (all >> 16), c_mid = 4u * all_mid;
         if (c_lo >= (uint32_t)k_row && (uint32_t)k_row > c_hi) {
-            const float frac = (float)(c_lo - (uint32_t)k_row) / (float)(c_lo - c_hi);
-            est = g_lo + (uint32_t)(frac * (float)(g_hi - g_lo));
+            const bool upper = c_mid >= (uint32_t)k_row;           // the level lies between the last threshold and g_hi
+            const uint32_t from = upper ? guess : g_lo, to = upper ? g_hi : guess;
+            const float a = (float)(upper ? c_mid : c_lo), b = (float)(upper ? c_hi : c_mid);
+            const float la = __log2f(a), lb = __log2f(b > 0.5f ? b : 0.5f), lk = __log2f((float)k_row);
+            const float frac = la > lb ? (la - lk) / (la - lb) : 0.f;
+            est = from + (uint32_t)(frac * (float)(to - from));
             placed = true;
         }
     }
@@ -456,13 +480,11 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p, int
             const u32x4 v = *(const u32x4*)&hist[TKR_BPT * tid + 4 * b];
             mine += (v[0] + v[1]) + (v[2] + v[3]);
         }
-        uint32_t suffix = mine;                        // inclusive suffix sum over the lanes of the wave
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const uint32_t o = __shfl_down(suffix, d);
-            if (lane + d < 64) suffix += o;
-        }
-        if (lane == 0) wave_a[wave] = suffix;
+        // inclusive suffix sum over the lanes of the wave: the wave's total less the lanes in front
+        const uint32_t upto = wave_prefix_sum_u32(mine);
+        const uint32_t wave_total = (uint32_t)__builtin_amdgcn_readlane((int)upto, 63);
+        const uint32_t suffix = wave_total - upto + mine;
+        if (lane == 0) wave_a[wave] = wave_total;
         __syncthreads();
         uint32_t above = suffix - mine;
 #pragma unroll
@@ -482,6 +504,41 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p, int
         prefix |= sh_bin << shift;
         need = sh_need;
         hi = shift - 1;
+        const uint32_t in_bin = sh_cnt;
+        if (!first_pass && hi >= 0 && in_bin <= (uint32_t)TKR_FEW && (listed || bracketed)) {
+            // A handful of keys left on the list: instead of another pass they are put side by side and one
+            // wave ranks them directly.  (sh_ncand was set to zero together with sh_bin.)
+            auto offer = [&](uint32_t kx) {
+                if (((kx ^ prefix) >> (hi + 1)) == 0u) {
+                    const uint32_t at = atomicAdd(&sh_ncand, 1u);
+                    if (at < (uint32_t)TKR_FEW) few[at] = kx;               // guard: holds by construction (in_bin counted them)
+                }
+            };
+            if (bracketed) {
+#pragma unroll
+                for (int j = tid; j < CAND_MAX; j += TK_THREADS)
+                    if ((uint32_t)(j % TKR_WAVE_CAND) < seg_cnt[j / TKR_WAVE_CAND]) offer(cand[j]);
+            } else {
+                for (uint32_t j = tid; j < ncand; j += TK_THREADS) offer(cand[j]);
+            }
+            __syncthreads();
+            if (wave == 0) {
+                const uint32_t mine = few[(uint32_t)lane < in_bin ? lane : 0];
+                uint32_t gt = 0u, ge = 0u;
+                for (uint32_t j = 0; j < in_bin; ++j) {
+                    const uint32_t other = few[j];
+                    gt += other > mine ? 1u : 0u;
+                    ge += other >= mine ? 1u : 0u;
+                }
+                // the key with fewer than `need` keys above it and at least `need` keys not below it
+                // (every lane that holds it writes the same two words)
+                if ((uint32_t)lane < in_bin && gt < need && need <= ge) { sh_bin = mine; sh_need = need - gt; }
+            }
+            __syncthreads();
+            prefix = sh_bin;
+            need = sh_need;
+            hi = -1;
+        }
         if (first_pass && hi >= 0 && sh_cnt <= (uint32_t)CAND_MAX) {
             // one more sweep over the registers, the last: whoever agrees with the prefix down to
             // the first digit goes on the list (in any order: the passes only count)
