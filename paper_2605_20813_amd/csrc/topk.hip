@@ -252,8 +252,16 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p, int
 
   for (int row = row_begin; row < row_end; ++row) {
     int32_t* __restrict__ out = p.idx + (int64_t)row * p.k;
+    // The thread's number, hidden from the compiler's loop-invariant hoisting once per row: it would compute
+    // everything that follows from it (the 64 column numbers of the lane, LDS addresses, lane masks) in front of
+    // the loop and, with no registers for them, keep them in scratch.
+    int tid_hidden = threadIdx.x;
+    asm volatile("" : "+v"(tid_hidden));
+    const int tid = tid_hidden;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int first_r = wave * SEG + lane * 4;
     const bool more = row + 1 < row_end;
-    const uint32_t* __restrict__ next_bits = bits + (int64_t)(more ? row + 1 : row) * p.stride + first;
+    const uint32_t* __restrict__ next_bits = bits + (int64_t)(more ? row + 1 : row) * p.stride + first_r;
     // this row's geometry was settled when its load was issued; the next row's decides what is fetched for it
     int n_next = p.n, k_next = p.k;
     if constexpr (VARLEN) { if (more) row_geometry(p, row + 1, n_next, k_next); }
@@ -323,7 +331,7 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p, int
             const float a = (float)(upper ? c_mid : c_lo), b = (float)(upper ? c_hi : c_mid);
             const float la = __log2f(a), lb = __log2f(b > 0.5f ? b : 0.5f), lk = __log2f((float)k_row);
             const float frac = la > lb ? (la - lk) / (la - lb) : 0.f;
-            est = from + (uint32_t)(frac * (float)(to - from));
+            est = __builtin_amdgcn_readfirstlane(from + (uint32_t)(frac * (float)(to - from)));      // (uniform: kept in a scalar register)
             placed = true;
         }
     }
@@ -383,7 +391,7 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p, int
         for (int i = 0; i < V4; ++i) {
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                if (i < nv && (!straddles || first + i * 256 + c < n)) {
+                if (i < nv && (!straddles || first_r + i * 256 + c < n)) {
                     kmax = key[i][c] > kmax ? key[i][c] : kmax;
                     kmin = key[i][c] < kmin ? key[i][c] : kmin;
                 }
@@ -406,7 +414,7 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p, int
             for (int i = 0; i < V4; ++i) {
 #pragma unroll
                 for (int c = 0; c < 4; ++c)
-                    if (i < nv && first + i * 256 + c >= n) key[i][c] = kmin;
+                    if (i < nv && first_r + i * 256 + c >= n) key[i][c] = kmin;
             }
         }
         // Bits above `hi` are the same in every key of the row.
@@ -572,11 +580,11 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p, int
         uint32_t next = half_width - (half_width >> 3);
         const uint32_t floor_hw = err < TKR_HALF_WIDTH_MAX ? err * 2u + (err >> 1) : TKR_HALF_WIDTH_MAX;
         next = next > floor_hw ? next : floor_hw;
-        half_width = next < TKR_HALF_WIDTH_MIN ? TKR_HALF_WIDTH_MIN : (next > TKR_HALF_WIDTH_MAX ? TKR_HALF_WIDTH_MAX : next);
+        half_width = __builtin_amdgcn_readfirstlane(next < TKR_HALF_WIDTH_MIN ? TKR_HALF_WIDTH_MIN : (next > TKR_HALF_WIDTH_MAX ? TKR_HALF_WIDTH_MAX : next));
         // ... and a wave's share of the list is short: no wider than what gave three quarters of the list's room
         if (listed_last > 3u * TK_THREADS) half_width -= half_width >> 2;
     }
-    guess = prefix;
+    guess = __builtin_amdgcn_readfirstlane(prefix);
     have_guess = !VARLEN;          // (the variable-length instantiation has no registers to spare for the estimate)
 
     // ---- ordered compaction.  Per wave: elements above the threshold and elements equal to it
@@ -661,7 +669,7 @@ __global__ void __launch_bounds__(TK_THREADS) topk_rows_kernel(TopkParams p, int
         const bool fits = out_pos + sel_all <= (uint32_t)k_row;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            if (sel[c] & fits) out[pos] = first + i * 256 + c;
+            if (sel[c] & fits) out[pos] = first_r + i * 256 + c;
             pos += sel[c] ? 1u : 0u;
         }
         out_pos += sel_all;
