@@ -220,6 +220,9 @@ def main():
                    "k": k, "schedule_steps": w.steps, "schedule_refresh_steps": cfg_refresh,
                    "timed_steps": steps, "timed_refresh_steps": refresh, "block_m": block_m, "block_n": block_n},
         "value_from": value_from,
+        # the same figure put together from the launch times of the timed steps (short bursts run at a higher clock
+        # than the sustained run of the whole schedule that `value` comes from)
+        "value_from_launch_times": round(attn_ms + select_ms * len(cfg_refresh) / w.steps, 4),
         "value_steps": value_steps,
         "value_refresh_steps": value_refresh,
         "attn_ms": round(attn_ms, 4),
